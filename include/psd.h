@@ -1,0 +1,220 @@
+/* psd.h - C ABI of the MI355X (gfx950) implementation of Pyramid Speculative
+ * Decoding: a draft model proposes tokens, a qualifier model verifies them in
+ * one multi-position pass, and the target model verifies the qualified window
+ * in one pass; every verify pass is followed by a vocabulary-wide
+ * softmax -> divergence -> fuzzy-threshold accept / first-reject scan /
+ * resample step.
+ *
+ * Conventions
+ *   - Every function returns PSD_OK (0) or a negative error code; nothing throws
+ *     across this boundary.  On failure no output argument is written, except
+ *     that psd_create sets *out = NULL.
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory of the context's (or the current) device.  Each argument
+ *     says which it is.
+ *   - The library owns every device allocation it makes; callers own every
+ *     buffer they pass in, and may free it as soon as the call returns.
+ *   - A context is not thread-safe: one call at a time per context.
+ *   - Determinism: equal (weights, parameters, prompt, seed) give equal tokens
+ *     on every run; no reduction in the library depends on scheduling order.
+ *
+ * Readings of the paper that this interface fixes (the paper leaves them open)
+ *   - Div (Sections 3.1-3.2) is the Jensen-Shannon divergence in nats, so
+ *     thresholds live in [0, ln 2]; the comparison is Div <= tau as printed.
+ *   - A position over the threshold falls back to the standard
+ *     speculative-sampling rule (accept with probability min(1, p(x)/q(x)),
+ *     else resample from norm(max(0, p - q))); tau = 0 is therefore standard
+ *     speculative decoding (Sections 3.1, 3.3, 3.4).
+ *   - A fully accepted window earns one bonus token from the verifier's last
+ *     row (the "+1" of Section 3.3).  The qualifier's bonus is only taken
+ *     while the window of l_Q tokens is not yet full.
+ *   - In the target stage the proposer distribution of a window token is the
+ *     qualifier row it was judged under or drawn from (Figure 1 caption).
+ *   - One temperature divides the logits of all three models before softmax;
+ *     the full vocabulary is used (no top-k / top-p).
+ *   - Random draws: Philox4x32-10, key = 64-bit seed, counter =
+ *     (vocab index / 4, absolute position of the token being decided,
+ *     purpose, stage), word = vocab index % 4, u = (top 23 bits + 1/2) / 2^23.
+ *     Purposes: 0 fresh sample from a model's own distribution (draft proposals
+ *     and bonus tokens; stage field 0), 1 acceptance coin (vocab index 0),
+ *     2 residual resample; stage 1 = qualifier judging the draft, 2 = target
+ *     judging the window.  Categorical draws are exponential races:
+ *     token = argmax_v w_v / (-ln u_v), ties to the lowest index.
+ */
+#ifndef PSD_H
+#define PSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    PSD_OK = 0,
+    PSD_EINVAL = -1, /* bad pointer, size, threshold, mismatched vocabularies, ... */
+    PSD_ESHAPE = -2, /* sequence would exceed max_seq, or a width/shape the kernels do not support */
+    PSD_ENOMEM = -3, /* device pool or workspace too small */
+    PSD_EHIP = -4    /* a HIP runtime call failed; see psd_last_error */
+};
+
+enum { PSD_F32 = 0, PSD_BF16 = 1 };
+
+#define PSD_MAX_WIDTH 32 /* most tokens one forward pass can take: k2 + 1 <= 32, k1 <= 31 */
+
+typedef struct psd_ctx psd_ctx; /* opaque, library-owned */
+
+/* One Llama-style decoder (RMSNorm, rotary embedding on pairs (i, i + hd/2),
+ * grouped-query causal attention, SwiGLU MLP, LM head tied to the embedding).
+ * `weights` is a HOST pointer to one blob of `dtype` elements in this order,
+ * every matrix row-major [out][in]:
+ *   embed[vocab][d]
+ *   per layer: attn_norm[d], wq[H*hd][d], wk[KV*hd][d], wv[KV*hd][d], wo[d][H*hd],
+ *              ffn_norm[d], w_gate[F][d], w_up[F][d], w_down[d][F]
+ *   final_norm[d]
+ * with hd = d / H.  Requirements: hd in {16, 32, 64, 128}, H % KV == 0,
+ * d % 32 == 0, F % 32 == 0, H*hd == d.  The blob is copied (and re-tiled) into
+ * the context's pool during psd_create. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab;
+    float rope_theta, rms_eps;
+    int32_t dtype; /* PSD_F32 or PSD_BF16: storage type of the weights and of the KV cache */
+    int32_t reserved;
+    const void* weights; /* host */
+    size_t weights_bytes; /* must equal the blob size implied by the shape */
+} psd_model_desc;
+
+enum {
+    PSD_FLAG_GRAPH = 1 /* replay captured hipGraphs for the forward passes instead of launching kernel by kernel */
+};
+
+typedef struct {
+    float T_q, T_t;      /* tau_Q, tau_T of Section 3.2, in nats, >= 0 */
+    float temperature;   /* > 0 */
+    int32_t k1, k2;      /* l_D, l_Q of the paper: 1 <= k1 <= 31, 1 <= k2 <= 31 */
+    int32_t max_seq;     /* KV capacity in tokens; a generate call needs n_prompt + n_new + k2 + 2 <= max_seq */
+    int32_t device;      /* HIP device ordinal */
+    int32_t flags;       /* PSD_FLAG_* */
+    size_t pool_bytes;   /* device pool size; 0 = exactly what the three models need */
+} psd_params;
+
+typedef struct {
+    int64_t proposed_q, accepted_q, fuzzy_q; /* draft tokens judged by the qualifier / accepted / accepted by threshold */
+    int64_t proposed_t, accepted_t, fuzzy_t; /* window tokens judged by the target / accepted / accepted by threshold */
+    int64_t passes_d, passes_q, passes_t;    /* forward passes of each model during decoding */
+    double ms_prefill;                       /* prompt ingestion, all three models */
+    double ms_decode;                        /* from the end of prefill to the last token (device time, HIP events) */
+} psd_stats;
+
+/* Builds a context: one device pool holding the three models' re-tiled weights,
+ * their paged KV caches and all scratch.  The three models must share `vocab`
+ * (the method compares their distributions entry by entry).
+ * Errors: PSD_EINVAL (null pointer, unsupported shape, k1/k2/threshold/temperature out of range,
+ * vocab mismatch, wrong weights_bytes), PSD_ENOMEM (pool_bytes too small), PSD_EHIP. */
+int psd_create(const psd_model_desc* draft, const psd_model_desc* qualifier, const psd_model_desc* target,
+               const psd_params* params, psd_ctx** out);
+
+void psd_destroy(psd_ctx* ctx);
+
+/* Device bytes a pool must have for these models and parameters. */
+size_t psd_pool_bytes_needed(const psd_model_desc* draft, const psd_model_desc* qualifier,
+                             const psd_model_desc* target, const psd_params* params);
+
+/* Changes thresholds / window lengths / temperature of an existing context
+ * (k2 must not exceed the k2 it was created with, nor k1 its k1). */
+int psd_set_decoding(psd_ctx* ctx, float T_q, float T_t, int32_t k1, int32_t k2, float temperature);
+
+/* The two-stage loop of Figure 1: prefill the prompt, then repeat
+ * { draft k1 tokens, qualifier verifies (tau_Q) } until k2 tokens are qualified,
+ * target verifies them (tau_T), commit the accepted prefix plus the replacement
+ * or bonus token, roll every KV cache back to the committed length.
+ *   prompt      host, n_prompt >= 1 token ids in [0, vocab)
+ *   out_tokens  host, caller-owned, receives exactly n_new ids
+ *   out_stats   host, caller-owned, may be NULL
+ * Errors: PSD_EINVAL, PSD_ESHAPE (n_prompt + n_new + k2 + 2 > max_seq), PSD_EHIP. */
+int psd_generate(psd_ctx* ctx, const int32_t* prompt, int32_t n_prompt, int32_t n_new, uint64_t seed,
+                 int32_t* out_tokens, psd_stats* out_stats);
+
+/* Plain autoregressive sampling from one model (0 draft, 1 qualifier, 2 target)
+ * with the same fresh-sample draws: the no-speculation baseline. */
+int psd_generate_plain(psd_ctx* ctx, int32_t which, const int32_t* prompt, int32_t n_prompt, int32_t n_new,
+                       uint64_t seed, int32_t* out_tokens, psd_stats* out_stats);
+
+/* One forward pass of model `which` over `w` tokens (1 <= w <= PSD_MAX_WIDTH) at
+ * positions pos0 .. pos0+w-1; KV rows below pos0 must have been written by
+ * earlier calls (pos0 may also re-write older rows: that is a rollback).
+ *   tokens      host, w ids
+ *   logits_out  host, [w][vocab] floats, may be NULL (KV update only)
+ * Test / measurement hook for logits parity; runs the same kernels psd_generate runs. */
+int psd_forward(psd_ctx* ctx, int32_t which, const int32_t* tokens, int32_t w, int32_t pos0, float* logits_out);
+
+/* ACCEPT of one verify stage (Sections 3.1-3.2, with the fallback rule of 3.4), stand-alone.
+ *   logits_p  [k+1][vocab] verifier rows,  logits_q  [k][vocab] proposer rows,
+ *   tokens    [k] proposed ids; token i sits at absolute position position0 + i
+ *   where     0: all pointers are host memory, 1: all pointers are device memory
+ *   stage     1 or 2 (selects the random streams, see top of file)
+ *   take_bonus  when all k are accepted: draw one more token from verifier row k
+ * Outputs (same memory space as the inputs): n_accepted (int32), next_token (int32, -1 if none),
+ * div_out [k] floats (may be NULL): the divergence of every proposed position.
+ * 0 <= k <= PSD_MAX_WIDTH - 1.  Stateless: equal arguments give equal results. */
+int psd_accept(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k, int32_t vocab,
+               float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage, int32_t take_bonus,
+               int32_t where, int32_t* n_accepted, int32_t* next_token, float* div_out);
+
+/* Batched ACCEPT for throughput measurement: n_trials independent stages of equal k in one launch
+ * sequence.  All pointers are DEVICE memory; trial b uses seed + b.
+ *   logits_p [n_trials][k+1][vocab], logits_q [n_trials][k][vocab], tokens [n_trials][k]
+ *   n_accepted, next_token [n_trials]; div_out [n_trials][k] (may be NULL)
+ *   workspace: device scratch of at least psd_accept_workspace_bytes(n_trials, k, vocab) bytes
+ *   stream: a hipStream_t passed as void* (NULL = the default stream); the call only enqueues work. */
+size_t psd_accept_workspace_bytes(int32_t n_trials, int32_t k, int32_t vocab);
+int psd_accept_batch(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t n_trials,
+                     int32_t k, int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
+                     uint32_t stage, int32_t take_bonus, int32_t* n_accepted, int32_t* next_token, float* div_out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Fresh sample from softmax(logits / temperature) by the exponential race (how the
+ * draft proposes, Figure 1): rows [n_rows][vocab], row r is decided for position position0 + r.
+ * where: 0 host pointers, 1 device pointers.  tokens_out [n_rows]. */
+int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float temperature, uint64_t seed,
+               uint32_t position0, int32_t where, int32_t* tokens_out);
+
+/* Trace hook for tests: when set, psd_generate copies the inputs of every draft
+ * sample (kind 0, k = 0, logits_p = the draft row) and every ACCEPT (kind 1 / 2 =
+ * stage) back to the host and calls fn after the step has been decided.  All
+ * pointers are host memory valid during the callback only.  Slow; tests only. */
+typedef void (*psd_trace_fn)(void* user, int32_t kind, uint32_t position0, int32_t k, int32_t take_bonus,
+                             const float* logits_p, const float* logits_q, const int32_t* tokens,
+                             int32_t n_accepted, int32_t next_token, const float* div);
+int psd_set_trace(psd_ctx* ctx, psd_trace_fn fn, void* user);
+
+/* Per-kernel device time, measured with HIP events on the library's stream.
+ * psd_profile(ctx, 1) switches to kernel-by-kernel launches with an event pair
+ * around every launch (graphs are bypassed) and clears the table; psd_profile(ctx, 0)
+ * switches back.  psd_kernel_stats copies up to `cap` rows to host memory and
+ * returns the number of rows (or a negative error). */
+typedef struct {
+    char name[48];      /* kernel family and shape class, e.g. "gemm_bf16 draft w1" */
+    int64_t launches;
+    double ms_total;
+    double bytes_total; /* algorithmic bytes those launches had to move (weights + activations + KV) */
+} psd_kernel_stat;
+int psd_profile(psd_ctx* ctx, int32_t on);
+int psd_kernel_stats(psd_ctx* ctx, psd_kernel_stat* out, int32_t cap);
+
+/* Device-memory plumbing for callers that have no other HIP binding (tests, benchmarks): plain
+ * hipMalloc / hipFree / hipMemcpy / hipDeviceSynchronize on the current device.
+ * kind: 0 host->device, 1 device->host, 2 device->device. */
+int psd_dev_alloc(size_t bytes, void** out);
+int psd_dev_free(void* ptr);
+int psd_dev_copy(void* dst, const void* src, size_t bytes, int32_t kind);
+int psd_dev_sync(void);
+
+const char* psd_strerror(int code);
+const char* psd_last_error(const psd_ctx* ctx); /* ctx may be NULL: last error of stand-alone calls on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSD_H */

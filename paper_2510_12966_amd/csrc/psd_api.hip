@@ -1,0 +1,150 @@
+// Context-free parts of the C ABI: error strings, and the host-pointer variants of ACCEPT and SAMPLE
+// (they stage through temporary device buffers; the hot path never uses them).
+#include <string.h>
+
+#include "psd_host.h"
+
+namespace psd {
+
+char* tls_error() {
+    static thread_local char buf[512];
+    return buf;
+}
+
+void set_error(char* dst, const char* fmt, ...) {
+    if (!dst) return;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+}
+
+struct DevBuf {  // frees on scope exit
+    void* p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+};
+
+}  // namespace psd
+
+using namespace psd;
+
+extern "C" const char* psd_strerror(int code) {
+    switch (code) {
+        case PSD_OK: return "ok";
+        case PSD_EINVAL: return "invalid argument";
+        case PSD_ESHAPE: return "shape or sequence length out of range";
+        case PSD_ENOMEM: return "device pool or workspace too small";
+        case PSD_EHIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+extern "C" int psd_accept(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k,
+                          int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
+                          uint32_t stage, int32_t take_bonus, int32_t where, int32_t* n_accepted,
+                          int32_t* next_token, float* div_out) {
+    char* err = tls_error();
+    if (!logits_p || !n_accepted || !next_token || (k > 0 && (!logits_q || !tokens)))
+        PSD_FAIL(PSD_EINVAL, err, "psd_accept: null pointer");
+    if (k < 0 || k > PSD_MAX_WIDTH - 1 || vocab < 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: k=%d vocab=%d", k, vocab);
+    if (stage != 1 && stage != 2) PSD_FAIL(PSD_EINVAL, err, "psd_accept: stage must be 1 or 2");
+    if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: where must be 0 or 1");
+    if (!(T >= 0.f) || !(temperature > 0.f)) PSD_FAIL(PSD_EINVAL, err, "psd_accept: T=%g temperature=%g", T, temperature);
+    const size_t ws_bytes = psd_accept_workspace_bytes(1, k, vocab);
+    const size_t np = (size_t)(k + 1) * vocab, nq = (size_t)k * vocab;
+    DevBuf ws, dp, dq, dt, dres, ddiv;
+    PSD_HIP(hipMalloc(&ws.p, ws_bytes), err);
+    PSD_HIP(hipMalloc(&dres.p, 2 * sizeof(int32_t)), err);
+    const float *p = logits_p, *q = logits_q;
+    const int32_t* t = tokens;
+    float* dv = div_out;
+    if (where == 0) {
+        PSD_HIP(hipMalloc(&dp.p, np * sizeof(float)), err);
+        PSD_HIP(hipMemcpy(dp.p, logits_p, np * sizeof(float), hipMemcpyHostToDevice), err);
+        p = (const float*)dp.p;
+        if (k > 0) {
+            PSD_HIP(hipMalloc(&dq.p, nq * sizeof(float)), err);
+            PSD_HIP(hipMemcpy(dq.p, logits_q, nq * sizeof(float), hipMemcpyHostToDevice), err);
+            PSD_HIP(hipMalloc(&dt.p, k * sizeof(int32_t)), err);
+            PSD_HIP(hipMemcpy(dt.p, tokens, k * sizeof(int32_t), hipMemcpyHostToDevice), err);
+            q = (const float*)dq.p;
+            t = (const int32_t*)dt.p;
+            if (div_out) {
+                PSD_HIP(hipMalloc(&ddiv.p, k * sizeof(float)), err);
+                dv = (float*)ddiv.p;
+            }
+        } else {
+            dv = nullptr;
+        }
+    }
+    int32_t* res = (int32_t*)dres.p;
+    int rc = psd_accept_batch(p, q, t, 1, k, vocab, T, temperature, seed, position0, stage, take_bonus, res, res + 1,
+                              dv, ws.p, ws_bytes, nullptr);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipDeviceSynchronize(), err);
+    if (where == 0) {
+        int32_t h[2];
+        PSD_HIP(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost), err);
+        *n_accepted = h[0];
+        *next_token = h[1];
+        if (div_out && k > 0) PSD_HIP(hipMemcpy(div_out, dv, k * sizeof(float), hipMemcpyDeviceToHost), err);
+    } else {
+        PSD_HIP(hipMemcpy(n_accepted, res, sizeof(int32_t), hipMemcpyDeviceToDevice), err);
+        PSD_HIP(hipMemcpy(next_token, res + 1, sizeof(int32_t), hipMemcpyDeviceToDevice), err);
+    }
+    return PSD_OK;
+}
+
+extern "C" int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float temperature, uint64_t seed,
+                          uint32_t position0, int32_t where, int32_t* tokens_out) {
+    char* err = tls_error();
+    if (!logits || !tokens_out) PSD_FAIL(PSD_EINVAL, err, "psd_sample: null pointer");
+    if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
+        PSD_FAIL(PSD_EINVAL, err, "psd_sample: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
+    if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "psd_sample: where must be 0 or 1");
+    DevBuf part, dl, dt;
+    PSD_HIP(hipMalloc(&part.p, (size_t)n_rows * accept_chunks(vocab) * 8), err);
+    const float* l = logits;
+    int32_t* t = tokens_out;
+    if (where == 0) {
+        PSD_HIP(hipMalloc(&dl.p, (size_t)n_rows * vocab * sizeof(float)), err);
+        PSD_HIP(hipMemcpy(dl.p, logits, (size_t)n_rows * vocab * sizeof(float), hipMemcpyHostToDevice), err);
+        PSD_HIP(hipMalloc(&dt.p, n_rows * sizeof(int32_t)), err);
+        l = (const float*)dl.p;
+        t = (int32_t*)dt.p;
+    }
+    int rc = sample_launch(l, n_rows, vocab, temperature, seed, position0, nullptr, t, part.p, nullptr, err);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipDeviceSynchronize(), err);
+    if (where == 0) PSD_HIP(hipMemcpy(tokens_out, t, n_rows * sizeof(int32_t), hipMemcpyDeviceToHost), err);
+    return PSD_OK;
+}
+
+extern "C" int psd_dev_alloc(size_t bytes, void** out) {
+    char* err = tls_error();
+    if (!out || bytes == 0) PSD_FAIL(PSD_EINVAL, err, "psd_dev_alloc: bad argument");
+    void* p = nullptr;
+    PSD_HIP(hipMalloc(&p, bytes), err);
+    *out = p;
+    return PSD_OK;
+}
+
+extern "C" int psd_dev_free(void* ptr) {
+    char* err = tls_error();
+    if (ptr) PSD_HIP(hipFree(ptr), err);
+    return PSD_OK;
+}
+
+extern "C" int psd_dev_copy(void* dst, const void* src, size_t bytes, int32_t kind) {
+    char* err = tls_error();
+    if (!dst || !src || kind < 0 || kind > 2) PSD_FAIL(PSD_EINVAL, err, "psd_dev_copy: bad argument");
+    const hipMemcpyKind kinds[3] = {hipMemcpyHostToDevice, hipMemcpyDeviceToHost, hipMemcpyDeviceToDevice};
+    PSD_HIP(hipMemcpy(dst, src, bytes, kinds[kind]), err);
+    return PSD_OK;
+}
+
+extern "C" int psd_dev_sync(void) {
+    char* err = tls_error();
+    PSD_HIP(hipDeviceSynchronize(), err);
+    return PSD_OK;
+}

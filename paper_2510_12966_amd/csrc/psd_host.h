@@ -1,0 +1,56 @@
+// Host-side plumbing shared by the library's translation units: error strings and HIP call checking.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "../../include/psd.h"
+
+namespace psd {
+
+// last error of context-free calls on this thread (contexts keep their own copy as well)
+char* tls_error();
+void set_error(char* dst, const char* fmt, ...);
+
+#define PSD_HIP(call, errbuf)                                                                         \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess) {                                                                       \
+            psd::set_error((errbuf), "%s failed at %s:%d: %s", #call, __FILE__, __LINE__,             \
+                           hipGetErrorString(e_));                                                    \
+            return PSD_EHIP;                                                                          \
+        }                                                                                             \
+    } while (0)
+
+#define PSD_FAIL(code, errbuf, ...)                \
+    do {                                           \
+        psd::set_error((errbuf), __VA_ARGS__);     \
+        return (code);                             \
+    } while (0)
+
+// ---- ACCEPT stage, device-level entry used by the scheduler and by the C ABI -------------------
+struct AcceptOut {   // one per trial, device memory
+    int32_t n_accepted;
+    int32_t next_token;
+    int32_t n_fuzzy;
+    int32_t pad;
+};
+
+constexpr int kAcceptChunk = 4096;  // vocabulary entries per workgroup
+
+inline int accept_chunks(int vocab) { return (vocab + kAcceptChunk - 1) / kAcceptChunk; }
+size_t accept_workspace_bytes(int n_trials, int k, int vocab);
+
+// Enqueues the ACCEPT kernels on `stream`.  All pointers are device memory.  div_out may be null.
+// Every launch shape is checked against the workspace size before anything is enqueued.
+int accept_launch(const float* logits_p, const float* logits_q, const int32_t* tokens, int n_trials, int k,
+                  int vocab, float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
+                  int take_bonus, AcceptOut* out, float* div_out, void* workspace, size_t workspace_bytes,
+                  hipStream_t stream, char* errbuf);
+
+// Fresh samples: row r -> token for position position0 + r.  partial: n_rows * accept_chunks(vocab) * 8 bytes.
+// position0_dev (optional, device) overrides position0 when non-null: the draft chain keeps it on the device.
+int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
+                  const int32_t* position0_dev, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf);
+
+}  // namespace psd

@@ -1,0 +1,137 @@
+"""GPU parity of the ACCEPT stage and of fresh sampling against the CPU oracle, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_12966_amd as psd
+from paper_2510_12966_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DIV_TOL = 1e-5       # fp32 kernel against the fp64 oracle on the same fp32 logits
+TIE_DIV = 1e-6       # |div - T| below this: the threshold decision may differ
+TIE_COIN = 1e-6      # relative distance of the coin from p/q
+TIE_RACE = 1e-5      # relative gap of the two best race keys
+
+
+def _stage_inputs(seed, trial, k, V, rho, stage):
+    t, q, d = synth.accept_logits(seed, trial, k, V, rho)
+    lp, lq = (q, d[:k]) if stage == 1 else (t, q[:k])
+    # proposals: fresh samples from the proposer rows (the oracle draws them: they are inputs here)
+    x = np.array([oracle.sample_row(lq[i], 1.0, seed + trial, 1000 + i)[0] for i in range(k)], dtype=np.int32)
+    return lp, lq, x
+
+
+def _compare(lp, lq, x, T, temp, seed, pos0, stage, bonus):
+    n, tok, div = psd.accept(lp, lq, x, T, temp, seed, pos0, stage, bonus)
+    res, odiv = oracle.accept(lp, lq, x, T, temp, seed, pos0, stage, bonus)
+    assert np.abs(div - odiv).max(initial=0.0) <= DIV_TOL
+    near = res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN
+    if n != res.n_accepted:
+        assert near, (n, res.n_accepted, res.margin_div, res.margin_coin)
+        return "tie"
+    if tok != res.next_token:
+        assert res.margin_race < TIE_RACE, (tok, res.next_token, res.margin_race)
+        return "tie"
+    return "exact"
+
+
+@pytest.mark.parametrize("k", [4, 8])
+@pytest.mark.parametrize("rho", [0.5, 0.8, 0.95])
+def test_accept_full_vocab_microbench_inputs(k, rho):
+    V = 128256
+    ties = 0
+    for trial, T in enumerate([0.0, 0.05, 0.2, 0.4, math.log(2)]):
+        for stage in (1, 2):
+            lp, lq, x = _stage_inputs(7, trial, k, V, rho, stage)
+            ties += _compare(lp, lq, x, T, 1.0, 7 + trial, 300 + trial, stage, True) == "tie"
+    assert ties <= 1
+
+
+@pytest.mark.parametrize("V", [2, 3, 97, 512, 4096, 4099, 8193, 32000])
+def test_accept_ragged_vocab_and_edge_k(V):
+    rng = np.random.default_rng(V)
+    for k in (0, 1, 5, 31):
+        lp = rng.normal(0, 2.5, (k + 1, V)).astype(np.float32)
+        lq = (0.8 * lp[:k] + 0.6 * rng.normal(0, 2.5, (k, V))).astype(np.float32)
+        x = rng.integers(0, V, k).astype(np.int32)
+        for T in (0.0, 0.1, 1.0):
+            for temp in (1.0, 0.7):
+                for bonus in (True, False):
+                    _compare(lp, lq, x, T, temp, 11, 40, 1 + (k % 2), bonus)
+
+
+def test_accept_identical_rows_and_extreme_logits():
+    rng = np.random.default_rng(1)
+    lp = rng.normal(0, 3, (4, 5000)).astype(np.float32)
+    n, tok, div = psd.accept(lp, lp[:3], [1, 2, 3], 0.0, 1.0, 5, 0, 2, True)
+    assert n == 3 and np.abs(div).max() <= 1e-6
+    assert tok == oracle.accept(lp, lp[:3], [1, 2, 3], 0.0, 1.0, 5, 0, 2, True)[0].next_token
+    # one-hot-like rows: same argmax -> divergence ~0, different argmax -> ~ln 2
+    a = np.full((2, 300), -60.0, np.float32); a[:, 7] = 40.0
+    b = np.full((1, 300), -60.0, np.float32); b[0, 9] = 40.0
+    n, tok, div = psd.accept(a, b, [9], 0.5, 1.0, 1, 0, 1, True)
+    assert abs(div[0] - math.log(2)) < 1e-5 and n == 0 and tok == 7
+    n, tok, div = psd.accept(a, a[:1], [7], 0.0, 1.0, 1, 0, 1, True)
+    assert div[0] <= 1e-6 and n == 1 and tok == 7
+
+
+def test_accept_out_of_range_token_is_rejected_not_faulted():
+    rng = np.random.default_rng(2)
+    lp = rng.normal(0, 1, (3, 100)).astype(np.float32)
+    lq = rng.normal(0, 1, (2, 100)).astype(np.float32)
+    n, tok, _ = psd.accept(lp, lq, [100000, 3], 0.0, 1.0, 1, 0, 1, True)
+    assert n == 0 and 0 <= tok < 100
+
+
+def test_accept_argument_errors():
+    lp = np.zeros((2, 10), np.float32)
+    with pytest.raises(psd.PsdError):
+        psd.accept(lp, lp[:1], [1], -0.1)
+    with pytest.raises(psd.PsdError):
+        psd.accept(lp, lp[:1], [1], 0.1, temperature=0.0)
+    with pytest.raises(psd.PsdError):
+        psd.accept(lp, lp[:1], [1], 0.1, stage=3)
+
+
+@pytest.mark.parametrize("V", [5, 512, 4099, 128256])
+def test_sample_matches_oracle(V):
+    rows = 6
+    lg = synth.normal(3, V, rows * V, 0.0, 3.0).reshape(rows, V)
+    for temp in (1.0, 0.7):
+        got = psd.sample(lg, temp, seed=21, position0=90)
+        for r in range(rows):
+            want, gap = oracle.sample_row(lg[r], temp, 21, 90 + r)
+            assert got[r] == want or gap < TIE_RACE
+
+
+def test_accept_histogram_matches_oracle_on_batched_trials():
+    """Accept-length histogram of the batched entry point against the oracle, trial by trial."""
+    k, V, B, rho, T = 4, 128256, 24, 0.8, 0.3
+    P, Q, X = [], [], []
+    for b in range(B):
+        lp, lq, x = _stage_inputs(7, b, k, V, rho, 2)
+        P.append(lp); Q.append(lq); X.append(x)
+    dp = psd.DeviceBuffer.from_numpy(np.stack(P)); dq = psd.DeviceBuffer.from_numpy(np.stack(Q))
+    dx = psd.DeviceBuffer.from_numpy(np.stack(X))
+    na = psd.DeviceBuffer(4 * B); nt = psd.DeviceBuffer(4 * B); dv = psd.DeviceBuffer(4 * B * k)
+    wsb = psd.accept_workspace_bytes(B, k, V)
+    ws = psd.DeviceBuffer(wsb)
+    psd.accept_batch(dp, dq, dx, B, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
+    psd.dev_sync()
+    na, nt, dv = na.to_numpy(np.int32, B), nt.to_numpy(np.int32, B), dv.to_numpy(np.float32, (B, k))
+    hist_g = np.bincount(na, minlength=k + 1)
+    hist_o = np.zeros(k + 1, dtype=np.int64)
+    ties = 0
+    for b in range(B):
+        res, odiv = oracle.accept(P[b], Q[b], X[b], T, 1.0, 100 + b, 50, 2, True)
+        hist_o[res.n_accepted] += 1
+        assert np.abs(dv[b] - odiv).max() <= DIV_TOL
+        if na[b] != res.n_accepted or nt[b] != res.next_token:
+            assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN or res.margin_race < TIE_RACE
+            ties += 1
+    assert ties <= 1
+    if ties == 0:
+        assert np.array_equal(hist_g, hist_o)
