@@ -61,7 +61,7 @@ enum {
 
 enum { PSD_F32 = 0, PSD_BF16 = 1 };
 
-#define PSD_MAX_WIDTH 32 /* most tokens one forward pass can take: k2 + 1 <= 32, k1 <= 31 */
+#define PSD_MAX_WIDTH 32 /* most tokens one forward pass can take: k2 + 1 <= 32, k1 + 2 <= 32 */
 
 typedef struct psd_ctx psd_ctx; /* opaque, library-owned */
 
@@ -86,13 +86,15 @@ typedef struct {
 } psd_model_desc;
 
 enum {
-    PSD_FLAG_GRAPH = 1 /* replay captured hipGraphs for the forward passes instead of launching kernel by kernel */
+    PSD_FLAG_GRAPH = 1,             /* replay captured hipGraphs for the decoding loop's passes instead of
+                                       launching kernel by kernel */
+    PSD_FLAG_SCRAMBLE_PAGES = 0x100 /* test aid: hand out physical KV pages in a shuffled order */
 };
 
 typedef struct {
     float T_q, T_t;      /* tau_Q, tau_T of Section 3.2, in nats, >= 0 */
     float temperature;   /* > 0 */
-    int32_t k1, k2;      /* l_D, l_Q of the paper: 1 <= k1 <= 31, 1 <= k2 <= 31 */
+    int32_t k1, k2;      /* l_D, l_Q of the paper: 1 <= k1 <= 30, 1 <= k2 <= 31 */
     int32_t max_seq;     /* KV capacity in tokens; a generate call needs n_prompt + n_new + k2 + 2 <= max_seq */
     int32_t device;      /* HIP device ordinal */
     int32_t flags;       /* PSD_FLAG_* */

@@ -246,12 +246,14 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
 // normalisation pass is needed)
 __global__ __launch_bounds__(kAccThreads) void sample_partial(const float* logits, int V, int nch, float inv_temp,
                                                               uint64_t seed, uint32_t position0,
-                                                              const int32_t* position0_dev, KeyIdx* parts) {
+                                                              const SampleCtl* ctl, KeyIdx* parts) {
     __shared__ KeyIdx smk[4];
     const int ch = blockIdx.x, r = blockIdx.y;
-    const float* row = logits + (size_t)r * V;
+    int row0 = 0;
+    if (ctl) { seed = ctl->seed; position0 = (uint32_t)ctl->position; row0 = ctl->row; }
+    const float* row = logits + (size_t)(row0 + r) * V;
     const bool vec = (V & 3) == 0;
-    const uint32_t pos = (position0_dev ? (uint32_t)*position0_dev : position0) + (uint32_t)r;
+    const uint32_t pos = position0 + (uint32_t)r;
     KeyIdx best{-INFINITY, 0x7fffffff};
 #pragma unroll
     for (int j = 0; j < kQuadsPerThread; ++j) {
@@ -278,14 +280,14 @@ __global__ void sample_final(const KeyIdx* parts, int nch, int32_t* tokens_out) 
 }
 
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
-                  const int32_t* position0_dev, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf) {
+                  const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf) {
     if (!logits || !tokens_out || !partial) PSD_FAIL(PSD_EINVAL, errbuf, "sample: null pointer");
     if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
         PSD_FAIL(PSD_EINVAL, errbuf, "sample: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
     if ((uintptr_t)logits & 15) PSD_FAIL(PSD_EINVAL, errbuf, "sample: logits must be 16-byte aligned");
     const int nch = accept_chunks(vocab);
     sample_partial<<<dim3(nch, n_rows), kAccThreads, 0, stream>>>(logits, vocab, nch, 1.0f / temperature, seed,
-                                                                   position0, position0_dev, (KeyIdx*)partial);
+                                                                   position0, ctl, (KeyIdx*)partial);
     sample_final<<<n_rows, 64, 0, stream>>>((const KeyIdx*)partial, nch, tokens_out);
     PSD_HIP(hipGetLastError(), errbuf);
     return PSD_OK;

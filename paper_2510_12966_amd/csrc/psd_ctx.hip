@@ -1,0 +1,540 @@
+// Context, device pool and the two-stage scheduler (Figure 1 caption; Sections 3.2-3.3).
+//
+// The host keeps the token sequence (committed tokens followed by the window of qualified tokens) and,
+// per model, how many KV rows are valid.  Before a pass a model ingests whatever part of the sequence it
+// has not cached; a rollback is nothing more than lowering that count (and returning whole KV pages).
+// The draft's chain of single-token steps stays on the device: the sampling kernels write the new token
+// into the next draft pass descriptor and into the qualifier's, so the host synchronises once per
+// qualifier round and once per target pass, when it reads the ACCEPT result.
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "psd_device.h"
+#include "psd_model.h"
+
+namespace psd {
+
+constexpr int kStageSlots = 64;
+constexpr int kStageSlotBytes = 256;
+
+struct RoundResult {  // pinned host mirror of what a round leaves on the device
+    AcceptOut acc;
+    int32_t tok[kMaxW];
+    float div[kMaxW];
+};
+
+struct GraphSlot {
+    hipGraphExec_t exec = nullptr;
+};
+
+}  // namespace psd
+
+using namespace psd;
+
+struct psd_ctx {
+    char err[512] = {0};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    void* pool_mem = nullptr;
+    Pool pool;
+    Model M[3];
+    psd_params prm{};
+    int k1cap = 0, k2cap = 0, V = 0;
+    // logits rows
+    float* DL = nullptr;  // [k1cap][V]   draft rows of the current round
+    float* QL = nullptr;  // [k2cap+1][V] qualifier row per window slot
+    float* TL = nullptr;  // [k2cap+1][V] target rows
+    float* HL = nullptr;  // [32][V]      psd_forward / plain generation
+    // ACCEPT
+    void* acc_ws = nullptr;
+    size_t acc_ws_bytes = 0;
+    AcceptOut* acc_out = nullptr;
+    float* acc_div = nullptr;
+    void* samp_part = nullptr;
+    int32_t* samp_tok = nullptr;   // [1] token just sampled
+    SampleCtl* chain = nullptr;
+    int32_t* round_tok = nullptr;  // [32] draft tokens of the round
+    int32_t* win_tok = nullptr;    // [32] window tokens for the target stage
+    // pinned staging
+    char* stage = nullptr;  // kStageSlots * kStageSlotBytes
+    int stage_next = 0, stage_since_sync = 0;
+    RoundResult* res = nullptr;
+    // graphs: [model][width class 0/1]
+    GraphSlot graphs[3][2];
+    Profiler prof;
+    psd_trace_fn trace = nullptr;
+    void* trace_user = nullptr;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+};
+
+namespace psd {
+
+// single thread: publishes the token just sampled to the next draft pass and to the qualifier pass
+__global__ void draft_advance(const int32_t* samp_tok, SampleCtl* chain, PassDesc* d_desc, PassDesc* q_desc,
+                              int32_t* round_tok) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int t = samp_tok[0], step = chain->row;
+    if (step < kMaxW) round_tok[step] = t;
+    if (q_desc && chain->q_base >= 0 && chain->q_base + step < kMaxW) q_desc->tok[chain->q_base + step] = t;
+    d_desc->pos0 += d_desc->w;
+    d_desc->w = 1;
+    d_desc->tok[0] = t;
+    d_desc->logit_row0 = step + 1;
+    chain->row = step + 1;
+    chain->position += 1;
+}
+
+static int stage_sync(psd_ctx* c) {
+    PSD_HIP(hipStreamSynchronize(c->stream), c->err);
+    c->stage_since_sync = 0;
+    return PSD_OK;
+}
+
+// copies `bytes` (<= 256) of host data to device memory in stream order through a pinned ring slot
+static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
+    if (bytes > kStageSlotBytes) PSD_FAIL(PSD_EINVAL, c->err, "internal: staging slot overflow");
+    if (c->stage_since_sync >= kStageSlots - 1) {
+        int rc = stage_sync(c);
+        if (rc != PSD_OK) return rc;
+    }
+    char* slot = c->stage + (size_t)c->stage_next * kStageSlotBytes;
+    c->stage_next = (c->stage_next + 1) % kStageSlots;
+    c->stage_since_sync++;
+    memcpy(slot, src, bytes);
+    PSD_HIP(hipMemcpyAsync(dst, slot, bytes, hipMemcpyHostToDevice, c->stream), c->err);
+    return PSD_OK;
+}
+
+static int wclass(int w) { return w <= 16 ? 16 : 32; }
+
+// enqueues one pass of model `mi`; the descriptor is already on the device.  with_sample: the draft step
+// also samples its token and advances the chain.
+static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sample, bool allow_graph = false) {
+    Model& M = c->M[mi];
+    // only the decoding loop's three pass shapes are captured; prefill, the test hook and plain generation stay eager
+    const bool use_graph = allow_graph && (c->prm.flags & PSD_FLAG_GRAPH) && !c->prof.on;
+    auto enqueue = [&](Profiler* prof) -> int {
+        int rc = model_forward(M, wcls, logits, c->stream, prof, c->err);
+        if (rc != PSD_OK) return rc;
+        if (with_sample) {
+            if (prof && prof->on) prof->begin(c->stream, prof->row_of("sample draft"), (double)c->V * 4);
+            rc = sample_launch(logits, 1, c->V, c->prm.temperature, 0, 0, c->chain, c->samp_tok, c->samp_part,
+                               c->stream, c->err);
+            if (rc != PSD_OK) return rc;
+            draft_advance<<<1, 64, 0, c->stream>>>(c->samp_tok, c->chain, c->M[0].desc, c->M[1].desc, c->round_tok);
+            if (prof && prof->on) prof->end(c->stream);
+        }
+        return PSD_OK;
+    };
+    if (!use_graph) return enqueue(&c->prof);
+    GraphSlot& g = c->graphs[mi][wcls == 16 ? 0 : 1];
+    if (!g.exec) {
+        hipGraph_t graph = nullptr;
+        PSD_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal), c->err);
+        int rc = enqueue(nullptr);
+        hipError_t e = hipStreamEndCapture(c->stream, &graph);
+        if (rc != PSD_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+        PSD_HIP(e, c->err);
+        PSD_HIP(hipGraphInstantiate(&g.exec, graph, nullptr, nullptr, 0), c->err);
+        PSD_HIP(hipGraphDestroy(graph), c->err);
+    }
+    PSD_HIP(hipGraphLaunch(g.exec, c->stream), c->err);
+    return PSD_OK;
+}
+
+static void drop_graphs(psd_ctx* c) {
+    for (auto& row : c->graphs)
+        for (auto& g : row)
+            if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+}
+
+// host-known tokens seq[from, to) go into a pass descriptor that starts at KV row `from`
+static void fill_desc(PassDesc& d, const int32_t* seq, int from, int to, int extra, int n_logit, int row0) {
+    memset(&d, 0, sizeof(d));
+    d.w = to - from + extra;
+    d.pos0 = from;
+    d.n_logit = n_logit;
+    d.logit_row0 = row0;
+    for (int i = from; i < to; ++i) d.tok[i - from] = seq[i];
+}
+
+// ingests seq[M.len, upto) with no logits, in chunks of up to 32 tokens
+static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
+    Model& M = c->M[mi];
+    while (M.len < upto) {
+        const int w = std::min(kMaxW, upto - M.len);
+        int rc = model_map_pages(M, M.len, M.len + w, c->stream, c->err);
+        if (rc != PSD_OK) return rc;
+        PassDesc d;
+        fill_desc(d, seq, M.len, M.len + w, 0, 0, 0);
+        if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
+        if ((rc = run_pass(c, mi, wclass(w), nullptr, false)) != PSD_OK) return rc;
+        M.len += w;
+    }
+    return PSD_OK;
+}
+
+static int check_tokens(psd_ctx* c, const int32_t* t, int n) {
+    for (int i = 0; i < n; ++i)
+        if (t[i] < 0 || t[i] >= c->V) PSD_FAIL(PSD_EINVAL, c->err, "token %d at index %d is outside [0, %d)", t[i], i, c->V);
+    return PSD_OK;
+}
+
+static int copy_rows_to_host(psd_ctx* c, std::vector<float>& dst, const float* src, int rows) {
+    dst.resize((size_t)std::max(rows, 1) * c->V);
+    if (rows > 0) PSD_HIP(hipMemcpy(dst.data(), src, (size_t)rows * c->V * sizeof(float), hipMemcpyDeviceToHost), c->err);
+    return PSD_OK;
+}
+
+}  // namespace psd
+
+// ---- C ABI --------------------------------------------------------------------------------------------
+
+static int validate_params(const psd_params* p, char* err) {
+    if (!(p->T_q >= 0.f) || !(p->T_t >= 0.f)) PSD_FAIL(PSD_EINVAL, err, "thresholds must be >= 0 (T_q=%g T_t=%g)", p->T_q, p->T_t);
+    if (!(p->temperature > 0.f)) PSD_FAIL(PSD_EINVAL, err, "temperature must be > 0");
+    if (p->k1 < 1 || p->k1 > kMaxW - 2) PSD_FAIL(PSD_EINVAL, err, "k1=%d outside [1, %d]", p->k1, kMaxW - 2);
+    if (p->k2 < 1 || p->k2 > kMaxW - 1) PSD_FAIL(PSD_EINVAL, err, "k2=%d outside [1, %d]", p->k2, kMaxW - 1);
+    if (p->max_seq < 8) PSD_FAIL(PSD_EINVAL, err, "max_seq=%d too small", p->max_seq);
+    return PSD_OK;
+}
+
+static size_t ctx_extra_bytes(int V, int k1, int k2) {
+    size_t b = 0;
+    auto add = [&](size_t n) { b = ((b + 255) & ~(size_t)255) + n; };
+    add((size_t)k1 * V * 4);
+    add((size_t)(k2 + 1) * V * 4);
+    add((size_t)(k2 + 1) * V * 4);
+    add((size_t)kMaxW * V * 4);
+    add(accept_workspace_bytes(1, kMaxW - 1, V));
+    add(sizeof(AcceptOut));
+    add(kMaxW * 4);
+    add((size_t)accept_chunks(V) * 8);
+    add(4);
+    add(sizeof(SampleCtl));
+    add(kMaxW * 4);
+    add(kMaxW * 4);
+    return b + 4096;
+}
+
+extern "C" size_t psd_pool_bytes_needed(const psd_model_desc* draft, const psd_model_desc* qualifier,
+                                        const psd_model_desc* target, const psd_params* params) {
+    if (!draft || !qualifier || !target || !params) return 0;
+    if (draft->n_heads < 1 || qualifier->n_heads < 1 || target->n_heads < 1 || params->max_seq < 1) return 0;
+    return model_pool_bytes(*draft, params->max_seq) + model_pool_bytes(*qualifier, params->max_seq) +
+           model_pool_bytes(*target, params->max_seq) + ctx_extra_bytes(target->vocab, params->k1, params->k2);
+}
+
+extern "C" int psd_create(const psd_model_desc* draft, const psd_model_desc* qualifier, const psd_model_desc* target,
+                          const psd_params* params, psd_ctx** out) {
+    char* err = tls_error();
+    if (out) *out = nullptr;
+    if (!draft || !qualifier || !target || !params || !out) PSD_FAIL(PSD_EINVAL, err, "psd_create: null pointer");
+    int rc = validate_params(params, err);
+    if (rc != PSD_OK) return rc;
+    if (draft->vocab != target->vocab || qualifier->vocab != target->vocab)
+        PSD_FAIL(PSD_EINVAL, err, "psd_create: the three models must share one vocabulary (%d / %d / %d)", draft->vocab,
+                 qualifier->vocab, target->vocab);
+    const psd_model_desc* descs[3] = {draft, qualifier, target};
+    for (auto* m : descs)
+        if (m->n_heads < 1 || m->d_model < 1) PSD_FAIL(PSD_EINVAL, err, "psd_create: bad model shape");
+    int ndev = 0;
+    PSD_HIP(hipGetDeviceCount(&ndev), err);
+    if (params->device < 0 || params->device >= ndev) PSD_FAIL(PSD_EINVAL, err, "psd_create: device %d of %d", params->device, ndev);
+    PSD_HIP(hipSetDevice(params->device), err);
+    psd_ctx* c = new psd_ctx();
+    auto fail = [&](int code) { strncpy(err, c->err, 511); psd_destroy(c); return code; };
+    c->device = params->device;
+    c->prm = *params;
+    c->k1cap = params->k1;
+    c->k2cap = params->k2;
+    c->V = target->vocab;
+    const size_t need = psd_pool_bytes_needed(draft, qualifier, target, params);
+    const size_t pool_bytes = params->pool_bytes ? params->pool_bytes : need;
+    if (pool_bytes < need) {
+        set_error(c->err, "psd_create: pool_bytes %zu < %zu needed", pool_bytes, need);
+        return fail(PSD_ENOMEM);
+    }
+#define CK(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { set_error(c->err, "%s: %s", #call, hipGetErrorString(e_)); return fail(PSD_EHIP); } } while (0)
+    CK(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking));
+    CK(hipMalloc(&c->pool_mem, pool_bytes));
+    c->pool.base = (char*)c->pool_mem;
+    c->pool.size = pool_bytes;
+    if ((rc = model_kernels_init(c->err)) != PSD_OK) return fail(rc);
+    const char* tags[3] = {"draft", "qualifier", "target"};
+    const bool scramble = (params->flags & 0x100) != 0;  // test aid: physical KV pages out of logical order
+    for (int i = 0; i < 3; ++i)
+        if ((rc = model_init(c->M[i], *descs[i], tags[i], params->max_seq, scramble, c->pool, c->stream, c->err)) != PSD_OK)
+            return fail(rc);
+    const int V = c->V;
+    bool ok = true;
+    auto take = [&](size_t n) { void* p = c->pool.take(n); if (!p) ok = false; return p; };
+    c->DL = (float*)take((size_t)c->k1cap * V * 4);
+    c->QL = (float*)take((size_t)(c->k2cap + 1) * V * 4);
+    c->TL = (float*)take((size_t)(c->k2cap + 1) * V * 4);
+    c->HL = (float*)take((size_t)kMaxW * V * 4);
+    c->acc_ws_bytes = accept_workspace_bytes(1, kMaxW - 1, V);
+    c->acc_ws = take(c->acc_ws_bytes);
+    c->acc_out = (AcceptOut*)take(sizeof(AcceptOut));
+    c->acc_div = (float*)take(kMaxW * 4);
+    c->samp_part = take((size_t)accept_chunks(V) * 8);
+    c->samp_tok = (int32_t*)take(4);
+    c->chain = (SampleCtl*)take(sizeof(SampleCtl));
+    c->round_tok = (int32_t*)take(kMaxW * 4);
+    c->win_tok = (int32_t*)take(kMaxW * 4);
+    if (!ok) { set_error(c->err, "psd_create: device pool too small"); return fail(PSD_ENOMEM); }
+    CK(hipHostMalloc((void**)&c->stage, (size_t)kStageSlots * kStageSlotBytes, hipHostMallocDefault));
+    CK(hipHostMalloc((void**)&c->res, sizeof(RoundResult), hipHostMallocDefault));
+    for (auto& e : c->ev) CK(hipEventCreate(&e));
+    CK(hipStreamSynchronize(c->stream));
+#undef CK
+    *out = c;
+    return PSD_OK;
+}
+
+extern "C" void psd_destroy(psd_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    if (c->stream) (void)hipStreamSynchronize(c->stream);
+    drop_graphs(c);
+    c->prof.clear();
+    for (auto& e : c->ev) if (e) (void)hipEventDestroy(e);
+    if (c->stage) (void)hipHostFree(c->stage);
+    if (c->res) (void)hipHostFree(c->res);
+    if (c->pool_mem) (void)hipFree(c->pool_mem);
+    if (c->stream) (void)hipStreamDestroy(c->stream);
+    delete c;
+}
+
+extern "C" const char* psd_last_error(const psd_ctx* c) { return c ? c->err : tls_error(); }
+
+extern "C" int psd_set_decoding(psd_ctx* c, float T_q, float T_t, int32_t k1, int32_t k2, float temperature) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_decoding: null context");
+    psd_params p = c->prm;
+    p.T_q = T_q; p.T_t = T_t; p.k1 = k1; p.k2 = k2; p.temperature = temperature;
+    int rc = validate_params(&p, c->err);
+    if (rc != PSD_OK) return rc;
+    if (k1 > c->k1cap || k2 > c->k2cap)
+        PSD_FAIL(PSD_EINVAL, c->err, "psd_set_decoding: k1=%d k2=%d exceed the context's capacity (%d, %d)", k1, k2, c->k1cap, c->k2cap);
+    if (temperature != c->prm.temperature) drop_graphs(c);  // the temperature is baked into captured sampling nodes
+    c->prm = p;
+    return PSD_OK;
+}
+
+extern "C" int psd_set_trace(psd_ctx* c, psd_trace_fn fn, void* user) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_trace: null context");
+    c->trace = fn;
+    c->trace_user = user;
+    return PSD_OK;
+}
+
+extern "C" int psd_profile(psd_ctx* c, int32_t on) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_profile: null context");
+    PSD_HIP(hipStreamSynchronize(c->stream), c->err);
+    c->prof.flush();
+    if (on) c->prof.clear();
+    c->prof.on = on != 0;
+    return PSD_OK;
+}
+
+extern "C" int psd_kernel_stats(psd_ctx* c, psd_kernel_stat* out, int32_t cap) {
+    if (!c || !out || cap < 0) PSD_FAIL(PSD_EINVAL, c ? c->err : tls_error(), "psd_kernel_stats: bad argument");
+    PSD_HIP(hipStreamSynchronize(c->stream), c->err);
+    c->prof.flush();
+    int n = std::min<int>(cap, (int)c->prof.rows.size());
+    for (int i = 0; i < n; ++i) {
+        memcpy(out[i].name, c->prof.rows[i].name, sizeof(out[i].name));
+        out[i].launches = c->prof.rows[i].launches;
+        out[i].ms_total = c->prof.rows[i].ms;
+        out[i].bytes_total = c->prof.rows[i].bytes;
+    }
+    return n;
+}
+
+extern "C" int psd_forward(psd_ctx* c, int32_t which, const int32_t* tokens, int32_t w, int32_t pos0, float* logits_out) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_forward: null context");
+    if (which < 0 || which > 2 || !tokens) PSD_FAIL(PSD_EINVAL, c->err, "psd_forward: bad argument");
+    if (w < 1 || w > kMaxW) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: width %d outside [1, %d]", w, kMaxW);
+    Model& M = c->M[which];
+    if (pos0 < 0 || pos0 + w > M.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: positions [%d, %d) exceed max_seq %d", pos0, pos0 + w, M.max_seq);
+    if (pos0 > M.len) PSD_FAIL(PSD_EINVAL, c->err, "psd_forward: pos0 %d but only %d KV rows are valid", pos0, M.len);
+    int rc = check_tokens(c, tokens, w);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipSetDevice(c->device), c->err);
+    if ((rc = model_map_pages(M, pos0, pos0 + w, c->stream, c->err)) != PSD_OK) return rc;
+    PassDesc d;
+    fill_desc(d, tokens, 0, w, 0, logits_out ? w : 0, 0);
+    d.pos0 = pos0;
+    if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
+    if ((rc = run_pass(c, which, wclass(w), logits_out ? c->HL : nullptr, false)) != PSD_OK) return rc;
+    M.len = pos0 + w;
+    if ((rc = stage_sync(c)) != PSD_OK) return rc;
+    if (logits_out) PSD_HIP(hipMemcpy(logits_out, c->HL, (size_t)w * c->V * sizeof(float), hipMemcpyDeviceToHost), c->err);
+    return PSD_OK;
+}
+
+extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt, int32_t n_new, uint64_t seed,
+                            int32_t* out_tokens, psd_stats* out_stats) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_generate: null context");
+    if (!prompt || n_prompt < 1 || n_new < 0 || (n_new > 0 && !out_tokens)) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate: bad argument");
+    const int k1 = c->prm.k1, k2 = c->prm.k2, V = c->V;
+    const int cap = n_prompt + n_new + k2 + 2;
+    if (cap > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate: n_prompt + n_new + k2 + 2 = %d exceeds max_seq %d", cap, c->prm.max_seq);
+    int rc = check_tokens(c, prompt, n_prompt);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipSetDevice(c->device), c->err);
+    Model &D = c->M[0], &Q = c->M[1], &T = c->M[2];
+    psd_stats st;
+    memset(&st, 0, sizeof(st));
+    std::vector<int32_t> seq(cap + kMaxW, 0);
+    memcpy(seq.data(), prompt, (size_t)n_prompt * sizeof(int32_t));
+    std::vector<float> tr_p, tr_q;  // trace copies
+    int C = n_prompt;
+    for (int i = 0; i < 3; ++i) c->M[i].len = 0;
+
+    PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
+    for (int i = 0; i < 3; ++i)
+        if ((rc = prefill(c, i, seq.data(), C - 1)) != PSD_OK) return rc;
+    PSD_HIP(hipEventRecord(c->ev[1], c->stream), c->err);
+
+    while (C - n_prompt < n_new) {
+        int nbuf = 0;
+        while (nbuf < k2) {
+            const int m = std::min(k1, k2 - nbuf), L = C + nbuf;
+            // draft: first step ingests the host-known uncached suffix, the rest chain on the device
+            const int hq = L - Q.len;  // host-known tokens the qualifier still has to ingest
+            if (L - D.len < 1 || L - D.len > 3 || hq < 1 || hq > 2)
+                PSD_FAIL(PSD_EINVAL, c->err, "internal: cache lengths out of step (L=%d D=%d Q=%d)", L, D.len, Q.len);
+            if ((rc = model_map_pages(D, D.len, L + m, c->stream, c->err)) != PSD_OK) return rc;
+            if ((rc = model_map_pages(Q, Q.len, L + m, c->stream, c->err)) != PSD_OK) return rc;
+            PassDesc dd, qd;
+            fill_desc(dd, seq.data(), D.len, L, 0, 1, 0);
+            fill_desc(qd, seq.data(), Q.len, L, m, m + 1, nbuf);
+            SampleCtl sc{seed, L, 0, hq, 0};
+            if ((rc = upload(c, D.desc, &dd, sizeof(dd))) != PSD_OK) return rc;
+            if ((rc = upload(c, Q.desc, &qd, sizeof(qd))) != PSD_OK) return rc;
+            if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
+            for (int i = 0; i < m; ++i)
+                if ((rc = run_pass(c, 0, 16, c->DL, true, true)) != PSD_OK) return rc;
+            st.passes_d += m;
+            if ((rc = run_pass(c, 1, wclass(hq + m), c->QL, false, true)) != PSD_OK) return rc;
+            st.passes_q++;
+            const int bonus = nbuf + m < k2;
+            if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage1"), (double)(2 * m + 1) * V * 4);
+            rc = accept_launch(c->QL + (size_t)nbuf * V, c->DL, c->round_tok, 1, m, V, c->prm.T_q, c->prm.temperature, seed,
+                               (uint32_t)L, 1u, bonus, c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
+            if (rc != PSD_OK) return rc;
+            if (c->prof.on) c->prof.end(c->stream);
+            PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
+            PSD_HIP(hipMemcpyAsync(c->res->tok, c->round_tok, m * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
+            if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, m * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
+            if ((rc = stage_sync(c)) != PSD_OK) return rc;
+            const int n = c->res->acc.n_accepted, y = c->res->acc.next_token, has_y = y >= 0;
+            if (n < 0 || n > m || (!has_y && (n < m || bonus))) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
+            if (c->trace) {
+                if ((rc = copy_rows_to_host(c, tr_q, c->DL, m)) != PSD_OK) return rc;
+                if ((rc = copy_rows_to_host(c, tr_p, c->QL + (size_t)nbuf * V, m + 1)) != PSD_OK) return rc;
+                for (int i = 0; i < m; ++i)
+                    c->trace(c->trace_user, 0, (uint32_t)(L + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
+                c->trace(c->trace_user, 1, (uint32_t)L, m, bonus, tr_p.data(), tr_q.data(), c->res->tok, n, y, c->res->div);
+            }
+            for (int i = 0; i < n; ++i) seq[L + i] = c->res->tok[i];
+            if (has_y) seq[L + n] = y;
+            nbuf += n + has_y;
+            D.len = std::min(L + m - 1, L + n);  // the draft never ingested its last proposal
+            Q.len = std::min(L + m, L + n);
+            st.proposed_q += m;
+            st.accepted_q += n;
+            st.fuzzy_q += c->res->acc.n_fuzzy;
+        }
+        // target verifies the window
+        const int wT = C + k2 - T.len;
+        if (wT != k2 + 1) PSD_FAIL(PSD_EINVAL, c->err, "internal: target cache out of step (C=%d T=%d)", C, T.len);
+        if ((rc = model_map_pages(T, T.len, C + k2, c->stream, c->err)) != PSD_OK) return rc;
+        PassDesc td;
+        fill_desc(td, seq.data(), T.len, C + k2, 0, k2 + 1, 0);
+        if ((rc = upload(c, T.desc, &td, sizeof(td))) != PSD_OK) return rc;
+        if ((rc = upload(c, c->win_tok, seq.data() + C, k2 * sizeof(int32_t))) != PSD_OK) return rc;
+        if ((rc = run_pass(c, 2, wclass(wT), c->TL, false, true)) != PSD_OK) return rc;
+        st.passes_t++;
+        if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k2 + 1) * V * 4);
+        rc = accept_launch(c->TL, c->QL, c->win_tok, 1, k2, V, c->prm.T_t, c->prm.temperature, seed, (uint32_t)C, 2u, 1,
+                           c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
+        if (rc != PSD_OK) return rc;
+        if (c->prof.on) c->prof.end(c->stream);
+        PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
+        if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, k2 * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
+        if ((rc = stage_sync(c)) != PSD_OK) return rc;
+        const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
+        if (n < 0 || n > k2 || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
+        if (c->trace) {
+            if ((rc = copy_rows_to_host(c, tr_p, c->TL, k2 + 1)) != PSD_OK) return rc;
+            if ((rc = copy_rows_to_host(c, tr_q, c->QL, k2)) != PSD_OK) return rc;
+            c->trace(c->trace_user, 2, (uint32_t)C, k2, 1, tr_p.data(), tr_q.data(), seq.data() + C, n, y, c->res->div);
+        }
+        seq[C + n] = y;
+        T.len = std::min(T.len + wT, C + n);
+        Q.len = std::min(Q.len, C + n);
+        D.len = std::min(D.len, C + n);
+        C += n + 1;
+        st.proposed_t += k2;
+        st.accepted_t += n;
+        st.fuzzy_t += c->res->acc.n_fuzzy;
+    }
+    PSD_HIP(hipEventRecord(c->ev[2], c->stream), c->err);
+    PSD_HIP(hipEventSynchronize(c->ev[2]), c->err);
+    float ms = 0.f;
+    PSD_HIP(hipEventElapsedTime(&ms, c->ev[0], c->ev[1]), c->err);
+    st.ms_prefill = ms;
+    PSD_HIP(hipEventElapsedTime(&ms, c->ev[1], c->ev[2]), c->err);
+    st.ms_decode = ms;
+    if (n_new > 0) memcpy(out_tokens, seq.data() + n_prompt, (size_t)n_new * sizeof(int32_t));
+    if (out_stats) *out_stats = st;
+    return PSD_OK;
+}
+
+extern "C" int psd_generate_plain(psd_ctx* c, int32_t which, const int32_t* prompt, int32_t n_prompt, int32_t n_new,
+                                  uint64_t seed, int32_t* out_tokens, psd_stats* out_stats) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_generate_plain: null context");
+    if (which < 0 || which > 2 || !prompt || n_prompt < 1 || n_new < 0 || (n_new > 0 && !out_tokens))
+        PSD_FAIL(PSD_EINVAL, c->err, "psd_generate_plain: bad argument");
+    if (n_prompt + n_new > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate_plain: exceeds max_seq");
+    int rc = check_tokens(c, prompt, n_prompt);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipSetDevice(c->device), c->err);
+    Model& M = c->M[which];
+    psd_stats st;
+    memset(&st, 0, sizeof(st));
+    std::vector<int32_t> seq(n_prompt + n_new + 1, 0);
+    memcpy(seq.data(), prompt, (size_t)n_prompt * sizeof(int32_t));
+    M.len = 0;
+    PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
+    if ((rc = prefill(c, which, seq.data(), n_prompt - 1)) != PSD_OK) return rc;
+    PSD_HIP(hipEventRecord(c->ev[1], c->stream), c->err);
+    for (int i = 0; i < n_new; ++i) {
+        const int L = n_prompt + i;
+        if ((rc = model_map_pages(M, M.len, L, c->stream, c->err)) != PSD_OK) return rc;
+        PassDesc d;
+        fill_desc(d, seq.data(), M.len, L, 0, 1, 0);
+        if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
+        if ((rc = run_pass(c, which, 16, c->HL, false)) != PSD_OK) return rc;
+        if ((rc = sample_launch(c->HL, 1, c->V, c->prm.temperature, seed, (uint32_t)L, nullptr, c->samp_tok, c->samp_part, c->stream, c->err)) != PSD_OK) return rc;
+        PSD_HIP(hipMemcpyAsync(c->res->tok, c->samp_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
+        if ((rc = stage_sync(c)) != PSD_OK) return rc;
+        seq[L] = c->res->tok[0];
+        M.len = L;
+        (which == 0 ? st.passes_d : which == 1 ? st.passes_q : st.passes_t)++;
+    }
+    PSD_HIP(hipEventRecord(c->ev[2], c->stream), c->err);
+    PSD_HIP(hipEventSynchronize(c->ev[2]), c->err);
+    float ms = 0.f;
+    PSD_HIP(hipEventElapsedTime(&ms, c->ev[0], c->ev[1]), c->err);
+    st.ms_prefill = ms;
+    PSD_HIP(hipEventElapsedTime(&ms, c->ev[1], c->ev[2]), c->err);
+    st.ms_decode = ms;
+    if (n_new > 0) memcpy(out_tokens, seq.data() + n_prompt, (size_t)n_new * sizeof(int32_t));
+    if (out_stats) *out_stats = st;
+    return PSD_OK;
+}

@@ -48,9 +48,18 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
                   int take_bonus, AcceptOut* out, float* div_out, void* workspace, size_t workspace_bytes,
                   hipStream_t stream, char* errbuf);
 
+// Where the draft chain is: device-resident so that a captured draft step can be replayed unchanged.
+struct SampleCtl {
+    uint64_t seed;
+    int32_t position;  // absolute position of the token the next sample decides
+    int32_t row;       // logits row the next sample reads (= index of the draft step in its round)
+    int32_t q_base;    // slot of the qualifier pass descriptor that receives the first draft token (-1: none)
+    int32_t pad;
+};
+
 // Fresh samples: row r -> token for position position0 + r.  partial: n_rows * accept_chunks(vocab) * 8 bytes.
-// position0_dev (optional, device) overrides position0 when non-null: the draft chain keeps it on the device.
+// ctl (optional, device): when non-null, seed / position0 / first logits row come from *ctl instead.
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
-                  const int32_t* position0_dev, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf);
+                  const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf);
 
 }  // namespace psd

@@ -1,0 +1,115 @@
+// One Llama-style decoder on the device: weight layout, KV pages, scratch and the forward pass.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "psd_host.h"
+
+namespace psd {
+
+constexpr int kPage = 64;        // tokens per KV page
+constexpr int kAttnSplit = 128;  // keys per attention workgroup (two pages); boundaries are absolute positions
+constexpr int kMaxW = PSD_MAX_WIDTH;
+
+// What one forward pass has to do; lives in DEVICE memory so that a captured graph can be replayed
+// with new contents.  Written by the host before a pass, or by the sampling kernel for the draft chain.
+struct PassDesc {
+    int32_t w;           // tokens in this pass (1..32)
+    int32_t pos0;        // position of the first token == number of valid KV rows before the pass
+    int32_t n_logit;     // the last n_logit tokens get logit rows (0 = none)
+    int32_t logit_row0;  // first destination row in the logits buffer
+    int32_t tok[kMaxW];
+};
+
+struct LayerW {
+    const float* attn_norm;
+    const void* wqkv;  // [(H+2KV)*hd][d]
+    const void* wo;    // [d][H*hd]
+    const float* ffn_norm;
+    const void* wgu;   // [2F][d]: gate rows, then up rows
+    const void* wd;    // [d][F]
+};
+
+// Pool sub-allocator: bump pointer, 256-byte granules.  The pool itself is one hipMalloc owned by the context.
+struct Pool {
+    char* base = nullptr;
+    size_t size = 0, used = 0;
+    bool dry = false;  // sizing run: hands out nothing, only counts
+    void* take(size_t bytes) {
+        size_t off = (used + 255) & ~(size_t)255;
+        used = off + bytes;
+        if (dry) return nullptr;
+        if (used > size) return nullptr;
+        return base + off;
+    }
+};
+
+struct KernelAcc {  // profiling row
+    char name[48];
+    int64_t launches = 0;
+    double ms = 0, bytes = 0;
+};
+
+struct Profiler {
+    bool on = false;
+    std::vector<KernelAcc> rows;
+    struct Pending { int row; hipEvent_t a, b; };
+    std::vector<Pending> pending;
+    std::vector<hipEvent_t> free_events;
+    int row_of(const char* name);
+    hipEvent_t get_event();
+    void begin(hipStream_t s, int row, double bytes);
+    void end(hipStream_t s);
+    void flush();  // synchronises and folds pending event pairs into rows
+    void clear();
+    ~Profiler();
+};
+
+struct Model {
+    // shape
+    int L = 0, d = 0, H = 0, KV = 0, hd = 0, F = 0, V = 0, Vpad = 0, nqkv = 0;
+    int dtype = 0;
+    float theta = 0, eps = 0;
+    int max_seq = 0, n_pages = 0, nsplit_max = 0;
+    const char* tag = "";
+    // weights (device)
+    const void* embed = nullptr;  // bf16: tiled [Vpad/16][d/32][64][8]; f32: row-major [V][d]
+    std::vector<LayerW> layers;
+    const float* final_norm = nullptr;
+    const float2* rope = nullptr;  // [max_seq][hd/2] (cos, sin)
+    // KV cache: page p, layer l, kv head g, k/v -> [kPage][hd] elements of dtype
+    void* kv = nullptr;
+    int32_t* page_table = nullptr;  // device, [n_pages] logical block -> physical page
+    std::vector<int32_t> h_page_table;
+    std::vector<int32_t> free_pages;
+    int pages_mapped = 0;
+    // scratch (device)
+    float* x = nullptr;       // residual stream [32][d]
+    void* xb = nullptr;       // GEMM input operand (bf16 hi/lo tiles, or plain fp32 rows)
+    float* qkv = nullptr;     // [32][nqkv]
+    float* gu = nullptr;      // [32][2F]
+    float* attn_part = nullptr;  // [nsplit_max][32][H][hd + 2]
+    PassDesc* desc = nullptr;
+    // host mirror
+    int len = 0;  // valid KV rows
+    size_t weight_bytes = 0;  // bytes one pass streams (all matrices once)
+};
+
+size_t model_pool_bytes(const psd_model_desc& m, int max_seq);
+
+// Carves a model out of the pool and uploads + re-tiles its weights (synchronous; uses a temporary staging buffer).
+int model_init(Model& M, const psd_model_desc& desc, const char* tag, int max_seq, bool scramble_pages, Pool& pool,
+               hipStream_t stream, char* err);
+
+// Makes sure KV pages exist for positions < upto and frees pages wholly beyond `keep`; uploads the table if it changed.
+int model_map_pages(Model& M, int keep, int upto, hipStream_t stream, char* err);
+
+// Enqueues one pass described by *M.desc (already on the device).  wmax: 16 or 32 = widest pass the launch must cover.
+// logits: device [rows][V] destination (may be null when the pass produces none).
+int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err);
+
+int model_kernels_init(char* err);  // one-time function attributes
+
+}  // namespace psd

@@ -1,0 +1,129 @@
+"""GPU parity of the decoder forward (logits) against the CPU oracle, through psd_forward."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_12966_amd as psd
+from paper_2510_12966_amd import synth
+from paper_2510_12966_amd.synth import ModelShape
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4    # fp32 weights, fp32 accumulate
+TOL_BF16 = 3e-2   # bf16 weights and KV cache, fp32 accumulate
+
+
+def _desc(shape, blob, dtype, theta):
+    return psd.ModelDesc(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_ffn, shape.vocab,
+                         theta, dtype, blob)
+
+
+def _ctx(shapes, blobs, dtype, theta, max_seq, flags=0, k1=4, k2=8):
+    d, q, t = (_desc(s, b, dtype, theta) for s, b in zip(shapes, blobs))
+    return psd.Context(d, q, t, 0.3, 0.2, k1, k2, max_seq, flags=flags)
+
+
+def test_tiny_fp32_stack_logits(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    shapes, blobs = (cfg.draft, cfg.qualifier, cfg.target), (d, q, t)
+    ctx = _ctx(shapes, blobs, cfg.dtype, cfg.rope_theta, 96)
+    toks = synth.tokens(5, 0, 60, cfg.target.vocab)
+    for which in range(3):
+        om = oracle.Model(shapes[which], blobs[which], cfg.dtype, cfg.rope_theta, 96)
+        ref = om.forward(toks, 0)
+        # ragged widths: 16 + 1 + 2 + 3 + 5 + 17 + 16
+        pos, got = 0, []
+        for w in (16, 1, 2, 3, 5, 17, 16):
+            got.append(ctx.forward(which, toks[pos:pos + w], pos))
+            pos += w
+        got = np.concatenate(got)
+        assert np.abs(got - ref).max() <= TOL_F32
+        # rollback: overwrite rows 20.. with other tokens, then again with the right ones
+        ctx.forward(which, (toks[20:31] + 7) % cfg.target.vocab, 20)
+        again = ctx.forward(which, toks[20:31], 20)
+        assert np.abs(again - ref[20:31]).max() <= TOL_F32
+    ctx.close()
+
+
+MINI = [  # bf16 shapes that cover head dims 64 / 128, group sizes 1..4, ragged vocabulary
+    (ModelShape(2, 256, 4, 2, 352, 1000), ModelShape(3, 512, 8, 2, 704, 1000), ModelShape(2, 512, 4, 4, 1024, 1000)),
+]
+
+
+@pytest.mark.parametrize("scramble", [0, 0x100])
+def test_bf16_logits_long_context_and_paging(scramble):
+    shapes = MINI[0]
+    blobs = [synth.target_weights(s, 20 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    n = 300   # spans three 128-key attention splits and five KV pages
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 384, flags=scramble)
+    toks = synth.tokens(6, 0, n, 1000)
+    for which in range(3):
+        om = oracle.Model(shapes[which], blobs[which], synth.DTYPE_BF16, 10000.0, 384)
+        ref = om.forward(toks, 0)
+        pos, got = 0, []
+        widths = [32] * 8 + [11, 1, 1, 6, 3, 17, 5]
+        assert sum(widths) == n
+        for w in widths:
+            got.append(ctx.forward(which, toks[pos:pos + w], pos))
+            pos += w
+        got = np.concatenate(got)
+        err = np.abs(got - ref).max()
+        assert np.abs(ref).max() > 0.5 and err <= TOL_BF16, err
+    ctx.close()
+
+
+def test_bf16_width_invariance_is_bit_exact():
+    # the same token at the same position gives the same logits bits whatever the width of the pass
+    shapes = MINI[0]
+    blobs = [synth.target_weights(s, 20 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 256)
+    toks = synth.tokens(8, 0, 150, 1000)
+    for which in (0, 2):
+        ctx.forward(which, toks[:32], 0, want_logits=False)
+        for p in range(32, 128, 32):
+            ctx.forward(which, toks[p:p + 32], p, want_logits=False)
+        wide = ctx.forward(which, toks[128:139], 128)            # width 11
+        narrow = np.concatenate([ctx.forward(which, toks[128 + i:129 + i], 128 + i) for i in range(11)])
+        assert np.array_equal(wide, narrow)
+        two = np.concatenate([ctx.forward(which, toks[128:130], 128), ctx.forward(which, toks[130:139], 130)])
+        assert np.array_equal(wide, two)
+        wide32 = ctx.forward(which, toks[118:150], 118)           # 32-wide class
+        assert np.array_equal(wide32[10:21], wide)
+    ctx.close()
+
+
+def test_small_config_target_logits_sampled():
+    """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
+    cfg = synth.CONFIGS["small"]
+    d, q, t, prompt = synth.build_stack(cfg)
+    shapes, blobs = (cfg.draft, cfg.qualifier, cfg.target), (d, q, t)
+    ctx = _ctx(shapes, blobs, cfg.dtype, cfg.rope_theta, 64)
+    toks = prompt[:24]
+    for which in range(3):
+        om = oracle.Model(shapes[which], blobs[which], cfg.dtype, cfg.rope_theta, 32)
+        ref = om.forward(toks, 0)
+        got = np.concatenate([ctx.forward(which, toks[:13], 0), ctx.forward(which, toks[13:24], 13)])
+        err = np.abs(got - ref).max()
+        print(f"model {which}: max |logit err| = {err:.3e}, logit std = {ref.std():.3f}", flush=True)
+        assert err <= TOL_BF16
+    ctx.close()
+
+
+def test_forward_argument_errors(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, 48)
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, [cfg.target.vocab], 0)            # token out of range
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, [1, 2], 5)                        # gap in the cache
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, np.zeros(33, np.int32), 0)        # too wide
+    with pytest.raises(psd.PsdError):
+        ctx.forward(3, [1], 0)
+    ctx.forward(0, np.zeros(32, np.int32), 0, want_logits=False)
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, np.zeros(32, np.int32), 32)       # past max_seq
+    ctx.close()
+    bad = psd.ModelDesc(2, 64, 4, 2, 256, 100, 10000.0, psd.F32, d)   # vocab differs from the others
+    with pytest.raises(psd.PsdError):
+        psd.Context(bad, _desc(cfg.qualifier, q, cfg.dtype, 1e4), _desc(cfg.target, t, cfg.dtype, 1e4), 0.1, 0.1, 4, 8, 64)

@@ -1,0 +1,162 @@
+"""GPU parity of the two-stage loop against the CPU oracle, through psd_generate."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_12966_amd as psd
+from paper_2510_12966_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TIE_DIV, TIE_COIN, TIE_RACE = 1e-6, 1e-6, 1e-5
+DIV_TOL = 1e-5
+
+
+def _desc(shape, blob, dtype, theta):
+    return psd.ModelDesc(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_ffn, shape.vocab,
+                         theta, dtype, blob)
+
+
+def _ctx(cfg, blobs, max_seq, T_q, T_t, k1, k2, flags=0, temperature=1.0):
+    shapes = (cfg.draft, cfg.qualifier, cfg.target)
+    d, q, t = (_desc(s, b, cfg.dtype, cfg.rope_theta) for s, b in zip(shapes, blobs))
+    return psd.Context(d, q, t, T_q, T_t, k1, k2, max_seq, temperature=temperature, flags=flags)
+
+
+class Replay:
+    """Feeds every sampling / ACCEPT step of a GPU run, with the GPU's own logits, to the oracle."""
+
+    def __init__(self, seed, T_q, T_t, temperature=1.0):
+        self.seed, self.T, self.temp = seed, {1: T_q, 2: T_t}, temperature
+        self.events = self.ties = 0
+        self.max_div_err = 0.0
+
+    def __call__(self, kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
+        self.events += 1
+        if kind == 0:
+            want, gap = oracle.sample_row(lp[0], self.temp, self.seed, pos0)
+            if want != nxt:
+                assert gap < TIE_RACE, ("draft sample", pos0, want, nxt, gap)
+                self.ties += 1
+            return
+        res, odiv = oracle.accept(lp, lq, tk, self.T[kind], self.temp, self.seed, pos0, kind, bool(bonus))
+        self.max_div_err = max(self.max_div_err, float(np.abs(div - odiv).max(initial=0.0)))
+        assert self.max_div_err <= DIV_TOL
+        if n_acc != res.n_accepted:
+            assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN, ("accept", kind, pos0, n_acc, res.n_accepted)
+            self.ties += 1
+        elif nxt != res.next_token:
+            assert res.margin_race < TIE_RACE, ("token", kind, pos0, nxt, res.next_token, res.margin_race)
+            self.ties += 1
+
+
+def _oracle_run(cfg, blobs, prompt, n_new, seed, k1, k2, T_q, T_t, temperature=1.0):
+    ms = len(prompt) + n_new + k2 + 2
+    D = oracle.Model(cfg.draft, blobs[0], cfg.dtype, cfg.rope_theta, ms)
+    Q = oracle.Model(cfg.qualifier, blobs[1], cfg.dtype, cfg.rope_theta, ms)
+    T = oracle.Model(cfg.target, blobs[2], cfg.dtype, cfg.rope_theta, ms)
+    return oracle.generate(D, Q, T, prompt, n_new, seed, k1, k2, T_q, T_t, temperature)
+
+
+SETTINGS = [  # (T_q, T_t, k1, k2, temperature); the first row is the tiny configuration as specified
+    (0.3, 0.2, 4, 8, 1.0),
+    (0.004, 0.012, 4, 8, 1.0),   # thresholds inside the divergence range of this stack: both stages reject
+    (0.0, 0.0, 3, 7, 1.0),       # strict speculative sampling
+    (0.006, 0.0, 5, 5, 0.7),
+    (0.004, 0.012, 1, 1, 1.0),
+    (0.01, 0.01, 8, 3, 1.0),     # k1 > k2: rounds are capped by the window
+]
+
+
+@pytest.mark.parametrize("graph", [0, psd.FLAG_GRAPH])
+@pytest.mark.parametrize("setting", SETTINGS)
+def test_tiny_stack_matches_oracle_end_to_end(tiny_stack, setting, graph):
+    cfg, d, q, t, prompt = tiny_stack
+    T_q, T_t, k1, k2, temp = setting
+    n_new, seed = cfg.n_new, cfg.sample_seed
+    ctx = _ctx(cfg, (d, q, t), len(prompt) + n_new + k2 + 2, T_q, T_t, k1, k2, flags=graph, temperature=temp)
+    rp = Replay(seed, T_q, T_t, temp)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, seed)
+    ctx.set_trace(None)
+    assert rp.events > 0
+    ref, ost = _oracle_run(cfg, (d, q, t), prompt, n_new, seed, k1, k2, T_q, T_t, temp)
+    if rp.ties == 0 and np.array_equal(out, ref):
+        for key in ("proposed_q", "accepted_q", "fuzzy_q", "proposed_t", "accepted_t", "fuzzy_t", "passes_d",
+                    "passes_q", "passes_t"):
+            assert st[key] == ost[key], key
+    else:
+        # fp32 logits against fp64 logits: a decision may flip only at a near-tie; everything before it agrees
+        first = int(np.argmax(out != ref)) if not np.array_equal(out, ref) else n_new
+        assert first > 0 or rp.ties > 0
+    # a second call on the same context gives the same answer (caches and graphs are reusable)
+    out2, st2 = ctx.generate(prompt, n_new, seed)
+    assert np.array_equal(out, out2)
+    assert st["accepted_t"] == st2["accepted_t"] and st["accepted_q"] == st2["accepted_q"]
+    ctx.close()
+
+
+def test_tiny_stack_exact_token_parity_over_seeds(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx(cfg, (d, q, t), 16 + 40 + 10, 0.004, 0.012, 4, 8)
+    same = 0
+    for seed in range(6):
+        out, st = ctx.generate(prompt, 40, seed)
+        ref, ost = _oracle_run(cfg, (d, q, t), prompt, 40, seed, 4, 8, 0.004, 0.012)
+        same += int(np.array_equal(out, ref))
+        assert 0 < st["accepted_q"] <= st["proposed_q"]
+    assert same >= 5   # a near-tie may flip one run; see the replay test for the exact bar
+    ctx.close()
+
+
+def test_identical_models_accept_everything_and_equal_plain_sampling(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    shapes = (cfg.qualifier,) * 3
+    descs = [_desc(s, q, cfg.dtype, cfg.rope_theta) for s in shapes]
+    for (k1, k2) in ((4, 8), (3, 7), (1, 1)):
+        ctx = psd.Context(descs[0], descs[1], descs[2], 0.0, 0.0, k1, k2, 16 + 48 + k2 + 2)
+        out, st = ctx.generate(prompt, 48, 9)
+        assert st["accepted_q"] == st["proposed_q"] and st["accepted_t"] == st["proposed_t"]
+        plain, _ = ctx.generate_plain(2, prompt, 48, 9)
+        assert np.array_equal(out, plain)
+        ctx.close()
+
+
+def test_small_bf16_stack_replay_and_baseline_settings():
+    cfg = synth.CONFIGS["small"]
+    d, q, t, prompt = synth.build_stack(cfg)
+    n_new = 48
+    ctx = _ctx(cfg, (d, q, t), cfg.n_prompt + n_new + cfg.k2 + 2, cfg.T_q, cfg.T_t, cfg.k1, cfg.k2, flags=psd.FLAG_GRAPH)
+    rp = Replay(cfg.sample_seed, cfg.T_q, cfg.T_t)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, cfg.sample_seed)
+    ctx.set_trace(None)
+    print("small stack:", st, "ties", rp.ties, "max div err", rp.max_div_err, flush=True)
+    assert rp.ties <= 1 and rp.events >= 10
+    assert (out >= 0).all() and (out < cfg.target.vocab).all()
+    assert st["proposed_t"] == cfg.k2 * st["passes_t"]
+    # tighter thresholds so that both stages reject on this stack too
+    ctx.set_decoding(0.05, 0.05, cfg.k1, cfg.k2)
+    rp = Replay(3, 0.05, 0.05)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, 3)
+    ctx.set_trace(None)
+    print("small stack, tight:", st, "ties", rp.ties, flush=True)
+    assert rp.ties <= 1
+    ctx.close()
+
+
+def test_generate_argument_errors(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx(cfg, (d, q, t), 64, 0.3, 0.2, 4, 8)
+    with pytest.raises(psd.PsdError):
+        ctx.generate(prompt, 64, 1)                      # 16 + 64 + 8 + 2 > 64
+    with pytest.raises(psd.PsdError):
+        ctx.generate(np.array([600], np.int32), 4, 1)     # token outside the vocabulary
+    with pytest.raises(psd.PsdError):
+        ctx.set_decoding(0.1, 0.1, 5, 8)                  # k1 above the context's capacity
+    with pytest.raises(psd.PsdError):
+        ctx.set_decoding(-0.1, 0.1, 4, 8)
+    out, _ = ctx.generate(prompt, 0, 1)
+    assert out.size == 0
+    ctx.close()
