@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the three-model speculative loop on one MI355X.
+
+A step is one psd_generate call: prefill of the synthetic prompt by the three models, then the
+draft -> qualifier -> target loop until n_new tokens exist.  Prints ONE JSON line (see README /
+the design doc for the fields).  Weights, prompt and every random draw are seeded and synthetic.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="paper", choices=["tiny", "small", "paper", "long"])
+    ap.add_argument("--n-new", type=int, default=0, help="override the configuration's n_new")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs the batch-1 loop on ONE GPU; --gpus N with N > 1 is not supported "
+            "(the loop is a dependency chain; see DESIGN.md for how it would shard)")
+        return 2
+
+    import paper_2510_12966_amd as psd
+    from paper_2510_12966_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    n_new = args.n_new or cfg.n_new
+    t0 = time.time()
+    d, q, t, prompt = synth.build_stack(cfg)
+    log(f"[bench] synthetic weights for '{cfg.name}' built in {time.time() - t0:.1f} s "
+        f"({(d.nbytes + q.nbytes + t.nbytes) / 1e9:.2f} GB)")
+    shapes = (cfg.draft, cfg.qualifier, cfg.target)
+    descs = [psd.ModelDesc(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.d_ffn, s.vocab, cfg.rope_theta,
+                           cfg.dtype, b) for s, b in zip(shapes, (d, q, t))]
+    max_seq = cfg.n_prompt + n_new + cfg.k2 + 2
+    t0 = time.time()
+    ctx = psd.Context(descs[0], descs[1], descs[2], cfg.T_q, cfg.T_t, cfg.k1, cfg.k2, max_seq,
+                      temperature=cfg.temperature, flags=0 if args.no_graph else psd.FLAG_GRAPH)
+    log(f"[bench] context created (weights uploaded and re-tiled) in {time.time() - t0:.1f} s")
+
+    for i in range(args.warmup):
+        out, st = ctx.generate(prompt, n_new, cfg.sample_seed)
+        log(f"[bench] warmup {i}: decode {st['ms_decode']:.1f} ms, prefill {st['ms_prefill']:.1f} ms")
+    psd.dev_sync()
+    decode_ms = prefill_ms = 0.0
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        out, st = ctx.generate(prompt, n_new, cfg.sample_seed + i)
+        decode_ms += st["ms_decode"]
+        prefill_ms += st["ms_prefill"]
+    psd.dev_sync()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    value = n_new * args.steps / wall
+    log(f"[bench] {args.steps} steps: {ms_per_step:.1f} ms/step, decode-only {n_new * args.steps / decode_ms * 1e3:.1f} tok/s, "
+        f"last stats {st}")
+
+    bytes_per_pass = {"draft": None, "qualifier": None, "target": None}
+    roofline = None
+    kernels = []
+    if not args.no_profile:
+        # per-kernel device time: the same loop once more, launched kernel by kernel with a HIP event pair
+        # around every launch on the library's stream
+        ctx.profile(True)
+        _, pst = ctx.generate(prompt, n_new, cfg.sample_seed)
+        kernels = ctx.kernel_stats()
+        ctx.profile(False)
+        kernels.sort(key=lambda r: -r["ms_total"])
+        tot = sum(r["ms_total"] for r in kernels)
+        for r in kernels[:12]:
+            gbs = r["bytes_total"] / r["ms_total"] / 1e6 if r["ms_total"] > 0 else 0.0
+            log(f"[bench]   {r['name']:<34s} {r['launches']:>7d} launches {r['ms_total']:>9.2f} ms "
+                f"({100 * r['ms_total'] / tot:4.1f}%)  {gbs:8.1f} GB/s")
+        dom = kernels[0]
+        ach = dom["bytes_total"] / dom["ms_total"] / 1e6
+        roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_launch_us": round(dom["ms_total"] / dom["launches"] * 1e3, 2),
+                    "bytes_per_launch": round(dom["bytes_total"] / dom["launches"]),
+                    "all_gemm_GBps": None}
+        g = [r for r in kernels if r["name"].startswith("gemm")]
+        if g:
+            roofline["all_gemm_GBps"] = round(sum(r["bytes_total"] for r in g) / sum(r["ms_total"] for r in g) / 1e6, 1)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        # bounded sample of the same workload: same models and decoding parameters, a short prompt and
+        # roughly one target pass worth of tokens (the fp64 oracle needs ~0.2 TFLOP per target pass here)
+        sp = {"tiny": (cfg.n_prompt, cfg.n_new), "small": (16, 24), "paper": (4, 8), "long": (4, 8)}[cfg.name]
+        ms = sp[0] + sp[1] + cfg.k2 + 2
+        oD = oracle.Model(cfg.draft, d, cfg.dtype, cfg.rope_theta, ms)
+        oQ = oracle.Model(cfg.qualifier, q, cfg.dtype, cfg.rope_theta, ms)
+        oT = oracle.Model(cfg.target, t, cfg.dtype, cfg.rope_theta, ms)
+        t0 = time.perf_counter()
+        oout, ost = oracle.generate(oD, oQ, oT, prompt[:sp[0]], sp[1], cfg.sample_seed, cfg.k1, cfg.k2, cfg.T_q, cfg.T_t,
+                                    cfg.temperature)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(sp[1] / dt, 4), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+               "sample": f"same models and decoding parameters, prompt truncated to {sp[0]} tokens, {sp[1]} new tokens "
+                         f"(prefill included), {dt:.1f} s"}
+        log(f"[bench] oracle: {sp[1]} tokens in {dt:.1f} s on {cores} threads, stats {ost}")
+
+    line = {
+        "metric": "generated tokens/s (batch 1), three-model PyramidSD loop",
+        "value": round(value, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: draft {cfg.draft.n_layers}L/{cfg.draft.d_model}, qualifier "
+                               f"{cfg.qualifier.n_layers}L/{cfg.qualifier.d_model}, target {cfg.target.n_layers}L/"
+                               f"{cfg.target.d_model}, vocab {cfg.target.vocab}; prompt {cfg.n_prompt}, n_new {n_new}, "
+                               f"k1 {cfg.k1}, k2 {cfg.k2}, T_q {cfg.T_q}, T_t {cfg.T_t}, temperature {cfg.temperature}",
+                   "graphs": not args.no_graph},
+        "decode_tokens_per_s": round(n_new * args.steps / decode_ms * 1e3, 2),
+        "prefill_ms_per_step": round(prefill_ms / args.steps, 2),
+        "accept_rate_q": round(st["accepted_q"] / max(st["proposed_q"], 1), 4),
+        "accept_rate_t": round(st["accepted_t"] / max(st["proposed_t"], 1), 4),
+        "passes": {"draft": st["passes_d"], "qualifier": st["passes_q"], "target": st["passes_t"]},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "paper_context": "124.13 tok/s PSD_F best, 1.91x over SD, RTX 4090, trained Llama 1B/3B/8B (Tables 2-3)",
+    }
+    print(json.dumps(line), flush=True)
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

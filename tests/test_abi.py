@@ -1,0 +1,60 @@
+"""CPU-side checks of the boundary: the library loads and exports every symbol the header declares,
+and the Python structs have the C layout.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "psd.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = set(re.findall(r"\b(psd_[a-z_0-9]+)\s*\(", src))
+    names -= {"psd_trace_fn"}
+    return sorted(names)
+
+
+def test_header_declares_the_boundary_calls():
+    names = _declared()
+    for must in ("psd_create", "psd_generate", "psd_accept", "psd_forward", "psd_destroy", "psd_strerror"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2510_12966_amd import binding
+
+    path = binding.lib_path()
+    if not os.path.exists(path):
+        from paper_2510_12966_amd import build
+        build.build()
+    try:
+        lib = ctypes.CDLL(path)
+    except OSError as e:
+        pytest.skip(f"HIP runtime not loadable here: {e}")
+    for name in _declared():
+        assert hasattr(lib, name), name
+    lib.psd_strerror.restype = ctypes.c_char_p
+    assert lib.psd_strerror(0) == b"ok"
+    assert b"invalid" in lib.psd_strerror(-1)
+
+
+def test_struct_layouts_match_the_header():
+    from paper_2510_12966_amd import binding as b
+
+    assert ctypes.sizeof(b._ModelDesc) == 6 * 4 + 2 * 4 + 2 * 4 + 8 + 8
+    assert b._ModelDesc.weights.offset == 40 and b._ModelDesc.weights_bytes.offset == 48
+    assert ctypes.sizeof(b._Params) == 8 * 4 + 8 and b._Params.pool_bytes.offset == 32
+    assert ctypes.sizeof(b.Stats) == 9 * 8 + 2 * 8
+    assert ctypes.sizeof(b.KernelStat) == 48 + 8 + 8 + 8
+
+
+def test_binding_has_no_fallback_and_does_not_import_the_oracle():
+    import paper_2510_12966_amd.binding as b
+
+    src = open(b.__file__).read() + open(os.path.join(os.path.dirname(b.__file__), "__init__.py")).read()
+    assert "oracle" not in src
+    assert "is missing" in src   # a missing library is an error, never a silent CPU path
