@@ -79,7 +79,8 @@ struct Model {
     std::vector<LayerW> layers;
     const float* final_norm = nullptr;
     const float2* rope = nullptr;  // [max_seq][hd/2] (cos, sin)
-    // KV cache: page p, layer l, kv head g, k/v -> [kPage][hd] elements of dtype
+    // KV cache: page p, layer l, kv head g, k/v -> kPage * hd elements of dtype; K is [slot][hd];
+    // V is [slot][hd] for fp32 models and transposed, [hd][slot], for bf16 models (MFMA operand order)
     void* kv = nullptr;
     int32_t* page_table = nullptr;  // device, [n_pages] logical block -> physical page
     std::vector<int32_t> h_page_table;
@@ -87,7 +88,11 @@ struct Model {
     int pages_mapped = 0;
     // scratch (device)
     float* x = nullptr;       // residual stream [32][d]
-    void* xb = nullptr;       // GEMM input operand (bf16 hi/lo tiles, or plain fp32 rows)
+    void* xb = nullptr;       // GEMM input operand (bf16 hi/lo tiles, or plain fp32 rows): normalised residual
+    void* xb2 = nullptr;      // second operand buffer: attention output / SwiGLU output (bf16 path)
+    float* ss = nullptr;      // [d/16][32] partial sums of squares of the residual stream (bf16 path)
+    void* sk_part = nullptr;  // split-K partial tiles (bf16 path)
+    unsigned int* sk_count = nullptr;
     float* qkv = nullptr;     // [32][nqkv]
     float* gu = nullptr;      // [32][2F]
     float* attn_part = nullptr;  // [nsplit_max][32][H][hd + 2]

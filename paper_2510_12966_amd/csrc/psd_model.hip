@@ -97,8 +97,12 @@ __global__ void bf16_to_f32_vec(const uint16_t* in, float* out, int n) {
     if (i < n) out[i] = bf16_to_f32(in[i]);
 }
 
-// row-major bf16 [N][K] -> MFMA A-operand tiles [Npad/16][K/32][64][8]; rows >= N become zeros
-__global__ __launch_bounds__(256) void tile_bf16(const uint4* src, uint4* dst, int N, int K, size_t n_chunks) {
+// row-major bf16 [N][K] -> MFMA A-operand tiles [Npad/16][K/32][64][8]; rows >= N become zeros.
+// mode 1 (fused q/k/v projection): inside every head of `hd` rows, tile row 2e / 2e+1 of tile t holds the rotary
+//   pair (j, j + hd/2), j = 8 t + e, so that one lane of the GEMM result owns both halves of a pair.
+// mode 2 (fused gate/up projection, `hd` = F): tile row 2e / 2e+1 of tile t holds gate / up row 8 t + e.
+__global__ __launch_bounds__(256) void tile_bf16(const uint4* src, uint4* dst, int N, int K, size_t n_chunks, int mode,
+                                                 int hd) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_chunks) return;
     const int KS = K >> 5;
@@ -106,7 +110,15 @@ __global__ __launch_bounds__(256) void tile_bf16(const uint4* src, uint4* dst, i
     const size_t t = i >> 6;
     const int ks = (int)(t % KS);
     const int tile = (int)(t / KS);
-    const int n = tile * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
+    int n = tile * 16 + (lane & 15);
+    const int k = ks * 32 + (lane >> 4) * 8;
+    if (mode == 1) {
+        const int head = n / hd, within = n % hd, tt = within >> 4, tr = within & 15;
+        n = head * hd + tt * 8 + (tr >> 1) + (tr & 1) * (hd >> 1);
+    } else if (mode == 2) {
+        const int tr = n & 15;
+        n = (tr & 1) * hd + tile * 8 + (tr >> 1);
+    }
     dst[i] = n < N ? src[((size_t)n * K + k) >> 3] : make_uint4(0, 0, 0, 0);
 }
 
@@ -242,78 +254,183 @@ __global__ void attn_combine_pack(const float* part, const PassDesc* desc, void*
     pack_store<BF16>(xb, H * hd, c, h * hd + i, o / Lsum);
 }
 
-// ---- skinny GEMMs -----------------------------------------------------------------------------------
+// ---- skinny GEMMs (bf16 weights, MFMA) ---------------------------------------------------------------
+// Epilogues fused into the GEMM that produces the value:
+//   EPI_QKV     rms scale, rotary embedding, q to the query buffer, k / v into the paged KV cache
+//   EPI_RESID   x += y, then the next RMSNorm's operand (x * gain, bf16 hi/lo) and its sum-of-squares partials
+//   EPI_SWIGLU  rms scale, silu(gate) * up, packed as the down projection's operand
+//   EPI_LOGITS  rms scale, logits rows
+// RMSNorm is split in two: the producer writes x * gain and per-tile partial sums of x^2, the consumer
+// multiplies its result by rsqrt(mean x^2 + eps) (a per-token scalar commutes with the matrix product).
+enum { EPI_QKV = 10, EPI_SWIGLU = 11 };
+
+struct GemmArgs {
+    const u32x4* Wt;       // tiled weights [Npad/16][KS][64] x 16 B
+    const u32x4* XB;       // packed activations [KS][2][2][64] x 16 B
+    int N, KS;
+    const PassDesc* desc;
+    // rms scale of the input (EPI_QKV, EPI_SWIGLU, EPI_LOGITS): partial sums of squares [d/16][32]
+    const float* ss_in;
+    int ss_tiles;
+    float inv_d, eps;
+    // outputs
+    float* Y;              // RESID: residual stream [32][ldy]; LOGITS: logits [rows][ldy]; QKV: query buffer [32][ldy]
+    int ldy;
+    void* xb_out;          // RESID / SWIGLU: operand of the next GEMM
+    const float* gain_out; // RESID: gain of the RMSNorm that follows
+    float* ss_out;         // RESID: [N/16][32]
+    // QKV only
+    const float2* rope;
+    uint16_t* kv;
+    const int32_t* page_table;
+    int layer, L, H, KV, hd;
+    // split-K across workgroups (gridDim.y > 1)
+    f32x4* sk_part;        // [tile][S][2][64]
+    unsigned int* sk_count;  // [tile], zero between launches
+};
+
+__device__ inline float rms_scale(const GemmArgs& a, int c, int g) {
+    // every lane sums the tiles congruent to g mod 4 in order, then a fixed butterfly over g
+    float s = 0.f;
+    for (int t = g; t < a.ss_tiles; t += 4) s += a.ss_in[t * 32 + c];
+    s += __shfl_xor(s, 16, kWave);
+    s += __shfl_xor(s, 32, kWave);
+    return rsqrtf(s * a.inv_d + a.eps);
+}
+
+// stores 4 (or 2) consecutive features of column c into a packed operand
+__device__ inline void pack4(void* xb, int c, int f0, const float v[4]) {
+    const int ks = f0 >> 5, gq = (f0 & 31) >> 3, e = f0 & 7, t = c >> 4, cc = c & 15;
+    uint16_t* p = (uint16_t*)xb + ((((size_t)ks * 2 + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { hi[r] = f32_to_bf16(v[r]); lo[r] = f32_to_bf16(v[r] - bf16_to_f32(hi[r])); }
+    *reinterpret_cast<uint2*>(p) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+    *reinterpret_cast<uint2*>(p + 512) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+}
+__device__ inline void pack2(void* xb, int c, int f0, float v0, float v1) {
+    const int ks = f0 >> 5, gq = (f0 & 31) >> 3, e = f0 & 7, t = c >> 4, cc = c & 15;
+    uint16_t* p = (uint16_t*)xb + ((((size_t)ks * 2 + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
+    const uint16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
+    const uint16_t l0 = f32_to_bf16(v0 - bf16_to_f32(h0)), l1 = f32_to_bf16(v1 - bf16_to_f32(h1));
+    *reinterpret_cast<uint32_t*>(p) = h0 | ((uint32_t)h1 << 16);
+    *reinterpret_cast<uint32_t*>(p + 512) = l0 | ((uint32_t)l1 << 16);
+}
+
+// value tile of one lane: rows n0 + 4 g + r (r = 0..3) of column c
 template <int EPI>
-__device__ inline void epi_store4(float* Y, int ldy, int N, int n, int c, const PassDesc* desc, f32x4 v) {
-    int row = c;
+__device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w, f32x4 v, float rs) {
+    const int n = tile * 16 + g * 4;
     if constexpr (EPI == EPI_LOGITS) {
-        const int first = desc->w - desc->n_logit;
-        if (c < first) return;
-        row = desc->logit_row0 + c - first;
-    }
-    float* dst = Y + (size_t)row * ldy + n;
-    if constexpr (EPI == EPI_RESID) {
-        // ldy and n are multiples of 4 here (model widths are multiples of 32)
-        float4 o = *reinterpret_cast<float4*>(dst);
-        o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
-        *reinterpret_cast<float4*>(dst) = o;
-    } else {
-        if ((ldy & 3) == 0 && n + 3 < N) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        const int first = w - a.desc->n_logit;
+        if (c < first || n >= a.N) return;
+        float* dst = a.Y + (size_t)(a.desc->logit_row0 + c - first) * a.ldy + n;
+        if ((a.ldy & 3) == 0 && n + 3 < a.N) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0] * rs, v[1] * rs, v[2] * rs, v[3] * rs);
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                if (n + r < N) dst[r] = v[r];
+                if (n + r < a.N) dst[r] = v[r] * rs;
+        }
+    } else if constexpr (EPI == EPI_RESID) {
+        float* dst = a.Y + (size_t)c * a.ldy + n;
+        float4 o = *reinterpret_cast<float4*>(dst);
+        o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
+        *reinterpret_cast<float4*>(dst) = o;
+        const float4 gn = *reinterpret_cast<const float4*>(a.gain_out + n);
+        const float pk[4] = {o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w};
+        pack4(a.xb_out, c, n, pk);
+        float ss = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
+        ss += __shfl_xor(ss, 16, kWave);
+        ss += __shfl_xor(ss, 32, kWave);
+        if (g == 0) a.ss_out[tile * 32 + c] = ss;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // weight rows are interleaved: tile row 2e = gate of feature 8 tile + e, tile row 2e + 1 = its up row
+        const float g0 = v[0] * rs, u0 = v[1] * rs, g1 = v[2] * rs, u1 = v[3] * rs;
+        pack2(a.xb_out, c, tile * 8 + g * 2, g0 / (1.f + expf(-g0)) * u0, g1 / (1.f + expf(-g1)) * u1);
+    } else if constexpr (EPI == EPI_QKV) {
+        // weight rows are permuted inside every head: tile row 2e, 2e + 1 = rotary pair (j, j + hd/2), j = 8 t + e
+        const int hd = a.hd, half = hd >> 1;
+        const int head = (tile * 16) / hd, t_in = ((tile * 16) % hd) >> 4;
+        const int pos = a.desc->pos0 + c;
+        const int page = a.page_table[pos / kPage], slot = pos % kPage;
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+            const int j = t_in * 8 + g * 2 + pr;
+            float x0 = v[2 * pr] * rs, x1 = v[2 * pr + 1] * rs;
+            if (head < a.H + a.KV) {
+                const float2 cs = a.rope[(size_t)pos * half + j];
+                const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
+                x0 = r0; x1 = r1;
+            }
+            if (head < a.H) {
+                float* q = a.Y + (size_t)c * a.ldy + (size_t)head * hd;
+                q[j] = x0;
+                q[j + half] = x1;
+            } else if (head < a.H + a.KV) {   // K page: [slot][hd]
+                uint16_t* k = a.kv + kv_base(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
+                k[j] = f32_to_bf16(x0);
+                k[j + half] = f32_to_bf16(x1);
+            } else {                          // V page, transposed: [hd][slot]
+                uint16_t* vv = a.kv + kv_base(page, a.layer, a.L, head - a.H - a.KV, a.KV, 1, hd);
+                vv[(size_t)j * kPage + slot] = f32_to_bf16(x0);
+                vv[(size_t)(j + half) * kPage + slot] = f32_to_bf16(x1);
+            }
         }
     }
 }
 
-// One workgroup (4 waves) per 16 output rows; the waves split K and are summed in wave order.
-// Wt: tiled weights [Npad/16][KS][64] x 16 B, XB: packed activations [KS][2][2][64] x 16 B.
+// One workgroup (4 waves) per 16 output rows and K range; the waves split that range and are summed in wave
+// order; with gridDim.y > 1 the K ranges of different workgroups are summed in range order by whichever
+// workgroup finishes last (no waiting: the others leave their partial tile and go).
 template <int NT, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16(const u32x4* __restrict__ Wt, const u32x4* __restrict__ XB,
-                                                 float* __restrict__ Y, int N, int KS, int ldy,
-                                                 const PassDesc* __restrict__ desc) {
+__global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
     __shared__ f32x4 red[3][NT][64];
     const int tile = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int k0 = (KS * wave) >> 2, k1 = (KS * (wave + 1)) >> 2;
-    const u32x4* a_ptr = Wt + ((size_t)tile * KS + k0) * 64 + lane;
-    const u32x4* b_ptr = XB + (size_t)k0 * 256 + lane;
+    const int S = gridDim.y, sp = blockIdx.y;
+    const int kb = (int)(((long)a.KS * sp) / S), ke = (int)(((long)a.KS * (sp + 1)) / S);
+    const int k0 = kb + (((ke - kb) * wave) >> 2), k1 = kb + (((ke - kb) * (wave + 1)) >> 2);
+    const int g = lane >> 4, cc = lane & 15;
+    constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
+    float rs[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) rs[t] = 1.f;
+    if (kScaled && wave == 0 && S == 1) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) rs[t] = rms_scale(a, t * 16 + cc, g);
+    }
+    const u32x4* a_ptr = a.Wt + ((size_t)tile * a.KS + k0) * 64 + lane;
+    const u32x4* b_ptr = a.XB + (size_t)k0 * 256 + lane;
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = 4;
+    constexpr int U = 8;
     int ks = k0;
     for (; ks + U <= k1; ks += U) {
-        u32x4 a[U], b[U][NT][2];
+        u32x4 wv[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(a_ptr + (size_t)u * 64);
+        for (int u = 0; u < U; ++u) wv[u] = __builtin_nontemporal_load(a_ptr + (size_t)u * 64);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                b[u][t][0] = b_ptr[(size_t)u * 256 + t * 128];
-                b[u][t][1] = b_ptr[(size_t)u * 256 + t * 128 + 64];
-            }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u]),
-                                                                 __builtin_bit_cast(bf16x8, b[u][t][0]), acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u]),
-                                                                 __builtin_bit_cast(bf16x8, b[u][t][1]), acc[t], 0, 0, 0);
+                const u32x4 bh = b_ptr[(size_t)u * 256 + t * 128], bl = b_ptr[(size_t)u * 256 + t * 128 + 64];
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u]),
+                                                                 __builtin_bit_cast(bf16x8, bh), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u]),
+                                                                 __builtin_bit_cast(bf16x8, bl), acc[t], 0, 0, 0);
             }
+        }
         a_ptr += (size_t)U * 64;
         b_ptr += (size_t)U * 256;
     }
     for (; ks < k1; ++ks) {
-        const u32x4 a = __builtin_nontemporal_load(a_ptr);
+        const u32x4 wv = __builtin_nontemporal_load(a_ptr);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv),
                                                              __builtin_bit_cast(bf16x8, b_ptr[t * 128]), acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv),
                                                              __builtin_bit_cast(bf16x8, b_ptr[t * 128 + 64]), acc[t], 0, 0, 0);
         }
         a_ptr += 64;
@@ -324,19 +441,199 @@ __global__ __launch_bounds__(256) void gemm_bf16(const u32x4* __restrict__ Wt, c
         for (int t = 0; t < NT; ++t) red[wave - 1][t][lane] = acc[t];
     }
     __syncthreads();
-    if (wave == 0) {
-        const int w = desc->w;
-        // D operand layout: lane holds rows 4 * (lane / 16) + r, r = 0..3, of column lane % 16
-        const int n = tile * 16 + (lane >> 4) * 4;
+    if (wave != 0) return;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        acc[t] += red[0][t][lane];
+        acc[t] += red[1][t][lane];
+        acc[t] += red[2][t][lane];
+    }
+    if (S > 1) {
+        f32x4* mine = a.sk_part + (((size_t)tile * S + sp) * 2) * 64;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) mine[t * 64 + lane] = acc[t];
+        __threadfence();
+        unsigned int ticket = 0;
+        if (lane == 0) ticket = atomicAdd(a.sk_count + tile, 1u);
+        ticket = __builtin_amdgcn_readfirstlane(ticket);
+        if (ticket != (unsigned)(S - 1)) return;
+        __threadfence();
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            f32x4 v = acc[t];
-            v += red[0][t][lane];
-            v += red[1][t][lane];
-            v += red[2][t][lane];
-            const int c = t * 16 + (lane & 15);
-            if (c < w && n < N) epi_store4<EPI>(Y, ldy, N, n, c, desc, v);
+            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < S; ++q) sum += a.sk_part[(((size_t)tile * S + q) * 2 + t) * 64 + lane];
+            acc[t] = sum;
         }
+        if (lane == 0) a.sk_count[tile] = 0u;
+        if (kScaled) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) rs[t] = rms_scale(a, t * 16 + cc, g);
+        }
+    }
+    const int w = a.desc->w;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int c = t * 16 + cc;
+        // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
+        if (c < w) epilogue<EPI>(a, tile, g, c, w, acc[t], rs[t]);
+    }
+}
+
+// token embedding: x = E[token]; also the first RMSNorm's operand and sum-of-squares partials.  grid d/16, 64 threads
+template <int NT>
+__global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const PassDesc* desc, float* x, void* xb,
+                                                 const float* gain, float* ss_out, int d, int V) {
+    const int tile = blockIdx.x, lane = threadIdx.x, g = lane >> 4, cc = lane & 15;
+    const int w = desc->w, KS = d >> 5;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int c = t * 16 + cc;
+        if (c >= w) continue;
+        int tok = desc->tok[c];
+        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+        const int n = tile * 16 + g * 4;
+        const size_t idx = ((((size_t)(tok >> 4) * KS + (n >> 5)) * 64) + ((n & 31) >> 3) * 16 + (tok & 15)) * 8 + (n & 7);
+        const uint2 raw = *reinterpret_cast<const uint2*>(embed + idx);
+        const float v[4] = {bf16_to_f32(raw.x & 0xffff), bf16_to_f32(raw.x >> 16), bf16_to_f32(raw.y & 0xffff), bf16_to_f32(raw.y >> 16)};
+        *reinterpret_cast<float4*>(x + (size_t)c * d + n) = make_float4(v[0], v[1], v[2], v[3]);
+        const float4 gn = *reinterpret_cast<const float4*>(gain + n);
+        const float pk[4] = {v[0] * gn.x, v[1] * gn.y, v[2] * gn.z, v[3] * gn.w};
+        pack4(xb, c, n, pk);
+        float ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        ss += __shfl_xor(ss, 16, kWave);
+        ss += __shfl_xor(ss, 32, kWave);
+        if (g == 0) ss_out[tile * 32 + c] = ss;
+    }
+}
+
+// ---- attention, bf16 KV cache, MFMA ---------------------------------------------------------------------
+// grid (KV heads, nsplit_max), 256 threads.  A workgroup owns one KV head and the absolute key range
+// [split * 128, +128); wave j owns the 32 keys [split * 128 + 32 j, +32).  Query rows of the group are
+// rho = token * G + head_in_group, processed 16 at a time:
+//   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 head dims straight from the K page,
+//                  B = queries as bf16 hi + lo from LDS; result lane (g, c): keys 4g..4g+3 of query c
+//   P   = exp(S - max) per query over the wave's 32 keys (masked causally), kept in registers: the result
+//         layout of S^T is exactly the A operand layout of v_mfma_f32_16x16x16bf16_1k
+//   O   = P V      B = 4 consecutive keys of one head dim: one 8-byte load from the transposed V page
+// The four waves' (max, sum, O) are merged through LDS in wave order and written as one partial per split.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDesc* desc, const uint16_t* kv,
+                                                 const int32_t* page_table, float* part, int layer, int L, int H,
+                                                 int KV, int nqkv) {
+    extern __shared__ float lds[];
+    constexpr int KSQ = HD / 32, JT = HD / 16;
+    const int gkv = blockIdx.x, split = blockIdx.y;
+    const int w = desc->w, pos0 = desc->pos0;
+    const int key0 = split * kAttnSplit, kv_max = pos0 + w;
+    if (key0 >= kv_max) return;
+    const int G = H / KV, R = w * G, QT = (R + 15) >> 4;
+    u32x4* qB = reinterpret_cast<u32x4*>(lds);                       // [QT][KSQ][2][64]
+    float* mrg = lds + (size_t)QT * KSQ * 2 * 64 * 4;                // [4 waves][16 queries][HD + 2]
+    const float scale = rsqrtf((float)HD);
+    {   // queries -> bf16 hi / lo B operands (rows beyond R are zero)
+        uint16_t* q16 = reinterpret_cast<uint16_t*>(qB);
+        for (int idx = threadIdx.x; idx < QT * 16 * HD; idx += 256) {
+            const int rho = idx / HD, i = idx % HD;
+            float v = 0.f;
+            if (rho < R) v = qkv[(size_t)(rho / G) * nqkv + (size_t)(gkv * G + rho % G) * HD + i] * scale;
+            const uint16_t hi = f32_to_bf16(v), lo = f32_to_bf16(v - bf16_to_f32(hi));
+            const size_t o = ((((size_t)(rho >> 4) * KSQ + (i >> 5)) * 2) * 64 + ((i & 31) >> 3) * 16 + (rho & 15)) * 8 + (i & 7);
+            q16[o] = hi;
+            q16[o + 512] = lo;
+        }
+    }
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, cq = lane & 15;
+    const int wkey0 = key0 + wave * 32;
+    const bool wave_live = wkey0 < kv_max;
+    // K rows (A operand of S^T) and V^T columns of this wave's 32 keys: all inside one page
+    const int page = page_table[wkey0 / kPage], slot0 = wkey0 % kPage;
+    const uint16_t* Kp = kv + kv_base(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
+    const uint16_t* Vp = kv + kv_base(page, layer, L, gkv, KV, 1, HD) + slot0;
+    for (int qt = 0; qt < QT; ++qt) {
+        float m = -INFINITY, l = 0.f;
+        f32x4 O[JT];
+#pragma unroll
+        for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (wave_live) {
+            f32x4 Sx[2];
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                Sx[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KSQ; ++ks) {
+                    const u32x4 ka = *reinterpret_cast<const u32x4*>(Kp + (size_t)(kt * 16 + cq) * HD + ks * 32 + g * 8);
+                    const u32x4 bh = qB[((size_t)(qt * KSQ + ks) * 2) * 64 + lane], bl = qB[((size_t)(qt * KSQ + ks) * 2 + 1) * 64 + lane];
+                    Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, bh), Sx[kt], 0, 0, 0);
+                    Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, bl), Sx[kt], 0, 0, 0);
+                }
+            }
+            // causal mask: key position <= query position; rows beyond R see nothing
+            const int rho = qt * 16 + cq;
+            const int qpos = rho < R ? pos0 + rho / G : -1;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int kp = wkey0 + kt * 16 + g * 4 + r;
+                    if (kp > qpos) Sx[kt][r] = -INFINITY;
+                    m = fmaxf(m, Sx[kt][r]);
+                }
+            m = fmaxf(m, __shfl_xor(m, 16, kWave));
+            m = fmaxf(m, __shfl_xor(m, 32, kWave));
+            const float msafe = m == -INFINITY ? 0.f : m;
+            typedef __attribute__((ext_vector_type(4))) short s16x4;
+            s16x4 Ph[2], Pl[2];
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float p = expf(Sx[kt][r] - msafe);   // exp(-inf) = 0 for masked keys
+                    l += p;
+                    const uint16_t hi = f32_to_bf16(p);
+                    Ph[kt][r] = (short)hi;
+                    Pl[kt][r] = (short)f32_to_bf16(p - bf16_to_f32(hi));
+                }
+            l += __shfl_xor(l, 16, kWave);
+            l += __shfl_xor(l, 32, kWave);
+#pragma unroll
+            for (int j = 0; j < JT; ++j)
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) {
+                    const uint2 raw = *reinterpret_cast<const uint2*>(Vp + (size_t)(j * 16 + cq) * kPage + kt * 16 + g * 4);
+                    const s16x4 vb = __builtin_bit_cast(s16x4, raw);
+                    O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph[kt], vb, O[j], 0, 0, 0);
+                    O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Pl[kt], vb, O[j], 0, 0, 0);
+                }
+        }
+        // merge the four waves: O lane (g, c) holds queries 4g + r, head dim 16 j + c
+        float* mine = mrg + (size_t)wave * 16 * (HD + 2);
+        if (g == 0) { mine[cq * (HD + 2)] = m; mine[cq * (HD + 2) + 1] = l; }
+#pragma unroll
+        for (int j = 0; j < JT; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[(g * 4 + r) * (HD + 2) + 2 + j * 16 + cq] = O[j][r];
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+            const int qr = idx / HD, i = idx % HD, rho = qt * 16 + qr;
+            if (rho < R) {
+                float M = -INFINITY;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) M = fmaxf(M, mrg[((size_t)v * 16 + qr) * (HD + 2)]);
+                float Ls = 0.f, o = 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float* pr = mrg + ((size_t)v * 16 + qr) * (HD + 2);
+                    const float f = pr[0] == -INFINITY ? 0.f : expf(pr[0] - M);
+                    Ls += pr[1] * f;
+                    o += pr[2 + i] * f;
+                }
+                float* out = part + (((size_t)split * kMaxW + rho / G) * H + gkv * G + rho % G) * (HD + 2);
+                out[2 + i] = o;
+                if (i == 0) { out[0] = M; out[1] = Ls; }
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -411,14 +708,19 @@ Profiler::~Profiler() {
 
 // ---- sizing / init ----------------------------------------------------------------------------------
 static size_t esize(int dtype) { return dtype == PSD_BF16 ? 2 : 4; }
+constexpr int kSplitKMaxTiles = 512;   // split-K across workgroups is only used below this many row tiles
+constexpr int kSplitKMaxUnits = 4096;  // tiles * splits
 static int round16(int n) { return (n + 15) & ~15; }
 
 static int attn_lds_bytes(int hd) { return (2 * kAttnSplit * (hd + 1) + 4 * hd + 4 * kAttnSplit) * (int)sizeof(float); }
 
+static int attn_mfma_lds(int hd, int qt) { return qt * (hd / 32) * 2 * 64 * 16 + 4 * 16 * (hd + 2) * (int)sizeof(float); }
+
 int model_kernels_init(char* err) {
     // attention stages two pages of K and V as fp32 in LDS: up to ~135 KB of the 160 KB a gfx950 CU has
-    PSD_HIP(hipFuncSetAttribute((const void*)attn_partial<uint16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                attn_lds_bytes(128)), err);
+    PSD_HIP(hipFuncSetAttribute((const void*)attn_mfma<32>, hipFuncAttributeMaxDynamicSharedMemorySize, attn_mfma_lds(32, 8)), err);
+    PSD_HIP(hipFuncSetAttribute((const void*)attn_mfma<64>, hipFuncAttributeMaxDynamicSharedMemorySize, attn_mfma_lds(64, 8)), err);
+    PSD_HIP(hipFuncSetAttribute((const void*)attn_mfma<128>, hipFuncAttributeMaxDynamicSharedMemorySize, attn_mfma_lds(128, 8)), err);
     PSD_HIP(hipFuncSetAttribute((const void*)attn_partial<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 attn_lds_bytes(128)), err);
     return PSD_OK;
@@ -448,6 +750,12 @@ static int model_carve(Model& M, Pool& pool) {
     const size_t kmax = std::max((size_t)M.d, (size_t)M.F);
     M.x = (float*)take((size_t)kMaxW * M.d * sizeof(float));
     M.xb = take(kmax * 128);
+    if (M.dtype == PSD_BF16) {
+        M.xb2 = take(kmax * 128);
+        M.ss = (float*)take((size_t)(M.d / 16) * 32 * sizeof(float));
+        M.sk_part = take((size_t)kSplitKMaxUnits * 2 * 64 * 16);
+        M.sk_count = (unsigned int*)take((size_t)kSplitKMaxTiles * sizeof(unsigned int));
+    }
     M.qkv = (float*)take((size_t)kMaxW * M.nqkv * sizeof(float));
     M.gu = (float*)take((size_t)kMaxW * 2 * M.F * sizeof(float));
     M.attn_part = (float*)take((size_t)M.nsplit_max * kMaxW * M.H * (M.hd + 2) * sizeof(float));
@@ -489,6 +797,7 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
         PSD_FAIL(PSD_EINVAL, err, "%s: d %% H, H %% KV, d %% 32 and F %% 32 must all be 0", tag);
     const int hd = m.d_model / m.n_heads;
     if (hd != 16 && hd != 32 && hd != 64 && hd != 128) PSD_FAIL(PSD_EINVAL, err, "%s: head dim %d not in {16,32,64,128}", tag, hd);
+    if (m.dtype == PSD_BF16 && hd == 16) PSD_FAIL(PSD_EINVAL, err, "%s: bf16 models need a head dim of 32, 64 or 128", tag);
     if (!(m.rope_theta > 0.f) || !(m.rms_eps >= 0.f)) PSD_FAIL(PSD_EINVAL, err, "%s: rope_theta / rms_eps", tag);
     if (m.weights_bytes != blob_elems(m) * esize(m.dtype))
         PSD_FAIL(PSD_EINVAL, err, "%s: weights_bytes %zu, shape implies %zu", tag, m.weights_bytes, blob_elems(m) * esize(m.dtype));
@@ -506,12 +815,12 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     struct Guard { void* p; ~Guard() { (void)hipFree(p); } } guard{stage};
     const char* src = (const char*)m.weights;
     // uploads `rows x cols` elements from the blob into dst, re-tiled when bf16
-    auto put_matrix = [&](const void* dst, size_t rows, size_t cols) -> int {
+    auto put_matrix = [&](const void* dst, size_t rows, size_t cols, int mode = 0, int hd_arg = 0) -> int {
         const size_t bytes = rows * cols * es;
         if (bf) {
             PSD_HIP(hipMemcpyAsync(stage, src, bytes, hipMemcpyHostToDevice, stream), err);
             const size_t chunks = (size_t)round16((int)rows) / 16 * (cols / 32) * 64;
-            tile_bf16<<<(unsigned)((chunks + 255) / 256), 256, 0, stream>>>((const uint4*)stage, (uint4*)dst, (int)rows, (int)cols, chunks);
+            tile_bf16<<<(unsigned)((chunks + 255) / 256), 256, 0, stream>>>((const uint4*)stage, (uint4*)dst, (int)rows, (int)cols, chunks, mode, hd_arg);
             PSD_HIP(hipStreamSynchronize(stream), err);  // the staging buffer is reused by the next tensor
         } else {
             PSD_HIP(hipMemcpyAsync((void*)dst, src, bytes, hipMemcpyHostToDevice, stream), err);
@@ -539,10 +848,10 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     for (int l = 0; l < M.L; ++l) {
         LayerW& w = M.layers[l];
         if ((rc = put_norm(w.attn_norm)) != PSD_OK) return rc;
-        if ((rc = put_matrix(w.wqkv, M.nqkv, d)) != PSD_OK) return rc;  // wq, wk, wv are adjacent in the blob
+        if ((rc = put_matrix(w.wqkv, M.nqkv, d, bf ? 1 : 0, M.hd)) != PSD_OK) return rc;  // wq, wk, wv are adjacent in the blob
         if ((rc = put_matrix(w.wo, d, q)) != PSD_OK) return rc;
         if ((rc = put_norm(w.ffn_norm)) != PSD_OK) return rc;
-        if ((rc = put_matrix(w.wgu, 2 * F, d)) != PSD_OK) return rc;   // w_gate, w_up adjacent
+        if ((rc = put_matrix(w.wgu, 2 * F, d, bf ? 2 : 0, (int)F)) != PSD_OK) return rc;   // w_gate, w_up adjacent
         if ((rc = put_matrix(w.wd, d, F)) != PSD_OK) return rc;
     }
     if ((rc = put_norm(M.final_norm)) != PSD_OK) return rc;
@@ -555,6 +864,13 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     PSD_HIP(hipMemsetAsync(M.qkv, 0, (size_t)kMaxW * M.nqkv * sizeof(float), stream), err);
     PSD_HIP(hipMemsetAsync(M.gu, 0, (size_t)kMaxW * 2 * F * sizeof(float), stream), err);
     PSD_HIP(hipMemsetAsync(M.desc, 0, sizeof(PassDesc), stream), err);
+    // KV pages start as zeros: attention may read (and mask) slots of a page that were never written
+    PSD_HIP(hipMemsetAsync(M.kv, 0, (size_t)M.n_pages * M.L * M.KV * 2 * kPage * M.hd * es, stream), err);
+    if (bf) {
+        PSD_HIP(hipMemsetAsync(M.xb2, 0, kmax * 128, stream), err);
+        PSD_HIP(hipMemsetAsync(M.ss, 0, (size_t)(M.d / 16) * 32 * sizeof(float), stream), err);
+        PSD_HIP(hipMemsetAsync(M.sk_count, 0, (size_t)kSplitKMaxTiles * sizeof(unsigned int), stream), err);
+    }
     // page bookkeeping: every logical block unmapped, free list in (optionally scrambled) order
     M.h_page_table.assign(M.n_pages, -1);
     M.free_pages.clear();
@@ -620,74 +936,132 @@ struct Launch {
 };
 }  // namespace
 
+// fp32 models: unfused pipeline, plain VALU GEMM
 template <int EPI>
-static void launch_gemm(Launch& L, const char* family, const void* W, float* Y, int N, int K, int ldy) {
+static void launch_gemm_f32(Launch& L, const char* family, const void* W, float* Y, int N, int K, int ldy) {
     Model& M = L.M;
-    const double bytes = (double)N * K * esize(M.dtype);
-    L.begin(family, bytes);
-    if (M.dtype == PSD_BF16) {
-        const int tiles = round16(N) / 16;
-        if (L.wcls <= 16)
-            gemm_bf16<1, EPI><<<tiles, 256, 0, L.s>>>((const u32x4*)W, (const u32x4*)M.xb, Y, N, K / 32, ldy, M.desc);
-        else
-            gemm_bf16<2, EPI><<<tiles, 256, 0, L.s>>>((const u32x4*)W, (const u32x4*)M.xb, Y, N, K / 32, ldy, M.desc);
-    } else {
-        gemm_f32<EPI><<<(N + 3) / 4, 256, 0, L.s>>>((const float*)W, (const float*)M.xb, Y, N, K, ldy, M.desc);
-    }
+    L.begin(family, (double)N * K * 4);
+    gemm_f32<EPI><<<(N + 3) / 4, 256, 0, L.s>>>((const float*)W, (const float*)M.xb, Y, N, K, ldy, M.desc);
     L.end();
+}
+
+static int forward_f32(Model& M, int wmax, float* logits, Launch& L) {
+    hipStream_t stream = L.s;
+    const int d = M.d, F = M.F, H = M.H, KV = M.KV, hd = M.hd;
+    const double act = (double)wmax * d * 4;
+    L.begin("embed", act);
+    embed_rows<false><<<wmax, 256, 0, stream>>>(M.embed, M.desc, M.x, d, M.V);
+    L.end();
+    const int lds = attn_lds_bytes(hd);
+    for (int l = 0; l < M.L; ++l) {
+        const LayerW& w = M.layers[l];
+        L.begin("rmsnorm", act);
+        rmsnorm_pack<false><<<wmax, 256, 0, stream>>>(M.x, w.attn_norm, M.desc, M.xb, d, M.eps);
+        L.end();
+        launch_gemm_f32<EPI_STORE>(L, "gemm_qkv", w.wqkv, M.qkv, M.nqkv, d, M.nqkv);
+        L.begin("rope_kv", (double)wmax * M.nqkv * 4);
+        rope_kv<float><<<dim3(wmax, H + 2 * KV), hd / 2, 0, stream>>>(M.qkv, M.desc, M.rope, (float*)M.kv, M.page_table, l, M.L, H, KV, hd, M.nqkv);
+        L.end();
+        L.begin("attn", 0);
+        attn_partial<float><<<dim3(H, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const float*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, hd, M.nqkv);
+        L.end();
+        L.begin("attn_combine", act);
+        attn_combine_pack<false><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb, H, hd);
+        L.end();
+        launch_gemm_f32<EPI_RESID>(L, "gemm_o", w.wo, M.x, d, H * hd, d);
+        L.begin("rmsnorm", act);
+        rmsnorm_pack<false><<<wmax, 256, 0, stream>>>(M.x, w.ffn_norm, M.desc, M.xb, d, M.eps);
+        L.end();
+        launch_gemm_f32<EPI_STORE>(L, "gemm_gate_up", w.wgu, M.gu, 2 * F, d, 2 * F);
+        L.begin("swiglu", (double)wmax * 2 * F * 4);
+        swiglu_pack<false><<<dim3(wmax, (F + 255) / 256), 256, 0, stream>>>(M.gu, M.desc, M.xb, F);
+        L.end();
+        launch_gemm_f32<EPI_RESID>(L, "gemm_down", w.wd, M.x, d, F, d);
+    }
+    if (logits) {
+        L.begin("rmsnorm", act);
+        rmsnorm_pack<false><<<wmax, 256, 0, stream>>>(M.x, M.final_norm, M.desc, M.xb, d, M.eps);
+        L.end();
+        launch_gemm_f32<EPI_LOGITS>(L, "gemm_lm_head", M.embed, logits, M.V, d, M.V);
+    }
+    return PSD_OK;
+}
+
+// bf16 models: six launches per layer (q/k/v projection, attention, merge, o, gate/up, down)
+template <int EPI>
+static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
+    Model& M = L.M;
+    const int tiles = round16(a.N) / 16;
+    // few row tiles cannot fill 256 CUs: split K across workgroups as well (deterministic last-arriver sum)
+    int S = 1;
+    if (tiles < kSplitKMaxTiles) {
+        S = std::min({(768 + tiles - 1) / tiles, a.KS / 8, kSplitKMaxUnits / tiles});
+        S = std::max(S, 1);
+    }
+    a.sk_part = (f32x4*)M.sk_part;
+    a.sk_count = M.sk_count;
+    a.desc = M.desc;
+    L.begin(family, (double)a.N * a.KS * 32 * 2);
+    if (L.wcls <= 16) gemm_bf16<1, EPI><<<dim3(tiles, S), 256, 0, L.s>>>(a);
+    else gemm_bf16<2, EPI><<<dim3(tiles, S), 256, 0, L.s>>>(a);
+    L.end();
+}
+
+static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
+    hipStream_t stream = L.s;
+    const int d = M.d, F = M.F, H = M.H, KV = M.KV, hd = M.hd, G = H / KV;
+    const double act = (double)wmax * d * 4;
+    const float inv_d = 1.0f / (float)d;
+    L.begin("embed", act);
+    if (wmax <= 16) embed_pack<1><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, M.xb, M.layers[0].attn_norm, M.ss, d, M.V);
+    else embed_pack<2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, M.xb, M.layers[0].attn_norm, M.ss, d, M.V);
+    L.end();
+    const int qt_max = (wmax * G + 15) / 16;
+    const int lds = attn_mfma_lds(hd, qt_max);
+    GemmArgs base{};
+    base.ss_in = M.ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
+    base.rope = M.rope; base.kv = (uint16_t*)M.kv; base.page_table = M.page_table;
+    base.L = M.L; base.H = H; base.KV = KV; base.hd = hd;
+    for (int l = 0; l < M.L; ++l) {
+        const LayerW& w = M.layers[l];
+        const float* next_gain = l + 1 < M.L ? M.layers[l + 1].attn_norm : M.final_norm;
+        GemmArgs a = base;
+        a.Wt = (const u32x4*)w.wqkv; a.XB = (const u32x4*)M.xb; a.N = M.nqkv; a.KS = d / 32;
+        a.Y = M.qkv; a.ldy = M.nqkv; a.layer = l;
+        launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
+        L.begin("attn", 0);
+        if (hd == 128) attn_mfma<128><<<dim3(KV, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        else if (hd == 64) attn_mfma<64><<<dim3(KV, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        else attn_mfma<32><<<dim3(KV, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        L.end();
+        L.begin("attn_combine", act);
+        attn_combine_pack<true><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb2, H, hd);
+        L.end();
+        a = base;
+        a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)M.xb2; a.N = d; a.KS = (H * hd) / 32;
+        a.Y = M.x; a.ldy = d; a.xb_out = M.xb; a.gain_out = w.ffn_norm; a.ss_out = M.ss;
+        launch_gemm_bf16<EPI_RESID>(L, "gemm_o", a);
+        a = base;
+        a.Wt = (const u32x4*)w.wgu; a.XB = (const u32x4*)M.xb; a.N = 2 * F; a.KS = d / 32; a.xb_out = M.xb2;
+        launch_gemm_bf16<EPI_SWIGLU>(L, "gemm_gate_up", a);
+        a = base;
+        a.Wt = (const u32x4*)w.wd; a.XB = (const u32x4*)M.xb2; a.N = d; a.KS = F / 32;
+        a.Y = M.x; a.ldy = d; a.xb_out = M.xb; a.gain_out = next_gain; a.ss_out = M.ss;
+        launch_gemm_bf16<EPI_RESID>(L, "gemm_down", a);
+    }
+    if (logits) {
+        GemmArgs a = base;
+        a.Wt = (const u32x4*)M.embed; a.XB = (const u32x4*)M.xb; a.N = M.V; a.KS = d / 32; a.Y = logits; a.ldy = M.V;
+        launch_gemm_bf16<EPI_LOGITS>(L, "gemm_lm_head", a);
+    }
+    return PSD_OK;
 }
 
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err) {
     if (wmax != 16 && wmax != 32) PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
     Launch L{M, stream, prof, wmax, {0}};
-    const bool bf = M.dtype == PSD_BF16;
-    const int d = M.d, F = M.F, H = M.H, KV = M.KV, hd = M.hd;
-    const double act = (double)wmax * d * 4;
-    L.begin("embed", act);
-    if (bf) embed_rows<true><<<wmax, 256, 0, stream>>>(M.embed, M.desc, M.x, d, M.V);
-    else embed_rows<false><<<wmax, 256, 0, stream>>>(M.embed, M.desc, M.x, d, M.V);
-    L.end();
-    const int lds = attn_lds_bytes(hd);
-    const double kv_bytes_layer = 0;  // KV traffic depends on the context; attributed by the caller
-    (void)kv_bytes_layer;
-    for (int l = 0; l < M.L; ++l) {
-        const LayerW& w = M.layers[l];
-        L.begin("rmsnorm", act);
-        if (bf) rmsnorm_pack<true><<<wmax, 256, 0, stream>>>(M.x, w.attn_norm, M.desc, M.xb, d, M.eps);
-        else rmsnorm_pack<false><<<wmax, 256, 0, stream>>>(M.x, w.attn_norm, M.desc, M.xb, d, M.eps);
-        L.end();
-        launch_gemm<EPI_STORE>(L, "gemm_qkv", w.wqkv, M.qkv, M.nqkv, d, M.nqkv);
-        L.begin("rope_kv", (double)wmax * M.nqkv * 4);
-        if (bf) rope_kv<uint16_t><<<dim3(wmax, H + 2 * KV), hd / 2, 0, stream>>>(M.qkv, M.desc, M.rope, (uint16_t*)M.kv, M.page_table, l, M.L, H, KV, hd, M.nqkv);
-        else rope_kv<float><<<dim3(wmax, H + 2 * KV), hd / 2, 0, stream>>>(M.qkv, M.desc, M.rope, (float*)M.kv, M.page_table, l, M.L, H, KV, hd, M.nqkv);
-        L.end();
-        L.begin("attn", 0);
-        if (bf) attn_partial<uint16_t><<<dim3(H, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, hd, M.nqkv);
-        else attn_partial<float><<<dim3(H, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const float*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, hd, M.nqkv);
-        L.end();
-        L.begin("attn_combine", act);
-        if (bf) attn_combine_pack<true><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb, H, hd);
-        else attn_combine_pack<false><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb, H, hd);
-        L.end();
-        launch_gemm<EPI_RESID>(L, "gemm_o", w.wo, M.x, d, H * hd, d);
-        L.begin("rmsnorm", act);
-        if (bf) rmsnorm_pack<true><<<wmax, 256, 0, stream>>>(M.x, w.ffn_norm, M.desc, M.xb, d, M.eps);
-        else rmsnorm_pack<false><<<wmax, 256, 0, stream>>>(M.x, w.ffn_norm, M.desc, M.xb, d, M.eps);
-        L.end();
-        launch_gemm<EPI_STORE>(L, "gemm_gate_up", w.wgu, M.gu, 2 * F, d, 2 * F);
-        L.begin("swiglu", (double)wmax * 2 * F * 4);
-        if (bf) swiglu_pack<true><<<dim3(wmax, (F + 255) / 256), 256, 0, stream>>>(M.gu, M.desc, M.xb, F);
-        else swiglu_pack<false><<<dim3(wmax, (F + 255) / 256), 256, 0, stream>>>(M.gu, M.desc, M.xb, F);
-        L.end();
-        launch_gemm<EPI_RESID>(L, "gemm_down", w.wd, M.x, d, F, d);
-    }
-    if (logits) {
-        L.begin("rmsnorm", act);
-        if (bf) rmsnorm_pack<true><<<wmax, 256, 0, stream>>>(M.x, M.final_norm, M.desc, M.xb, d, M.eps);
-        else rmsnorm_pack<false><<<wmax, 256, 0, stream>>>(M.x, M.final_norm, M.desc, M.xb, d, M.eps);
-        L.end();
-        launch_gemm<EPI_LOGITS>(L, "gemm_lm_head", M.embed, logits, M.V, d, M.V);
-    }
+    int rc = M.dtype == PSD_BF16 ? forward_bf16(M, wmax, logits, L) : forward_f32(M, wmax, logits, L);
+    if (rc != PSD_OK) return rc;
     PSD_HIP(hipGetLastError(), err);
     return PSD_OK;
 }
