@@ -88,7 +88,7 @@ def main() -> int:
         ctx.profile(False)
         kernels.sort(key=lambda r: -r["ms_total"])
         tot = sum(r["ms_total"] for r in kernels)
-        for r in kernels[:12]:
+        for r in kernels:
             gbs = r["bytes_total"] / r["ms_total"] / 1e6 if r["ms_total"] > 0 else 0.0
             log(f"[bench]   {r['name']:<34s} {r['launches']:>7d} launches {r['ms_total']:>9.2f} ms "
                 f"({100 * r['ms_total'] / tot:4.1f}%)  {gbs:8.1f} GB/s")
@@ -139,6 +139,10 @@ def main() -> int:
         "accept_rate_q": round(st["accepted_q"] / max(st["proposed_q"], 1), 4),
         "accept_rate_t": round(st["accepted_t"] / max(st["proposed_t"], 1), 4),
         "passes": {"draft": st["passes_d"], "qualifier": st["passes_q"], "target": st["passes_t"]},
+        "ms_per_pass": {"draft": round(st["ms_d"] / max(st["passes_d"], 1), 4),
+                        "qualifier": round(st["ms_q"] / max(st["passes_q"], 1), 4),
+                        "target": round(st["ms_t"] / max(st["passes_t"], 1), 4),
+                        "accept": round(st["ms_accept"] / max(st["passes_q"] + st["passes_t"], 1), 4)},
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "124.13 tok/s PSD_F best, 1.91x over SD, RTX 4090, trained Llama 1B/3B/8B (Tables 2-3)",
     }

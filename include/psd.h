@@ -107,6 +107,8 @@ typedef struct {
     int64_t passes_d, passes_q, passes_t;    /* forward passes of each model during decoding */
     double ms_prefill;                       /* prompt ingestion, all three models */
     double ms_decode;                        /* from the end of prefill to the last token (device time, HIP events) */
+    double ms_d, ms_q, ms_t, ms_accept;      /* device time inside ms_decode spent in draft steps (with sampling),
+                                                qualifier passes, target passes and ACCEPT stages */
 } psd_stats;
 
 /* Builds a context: one device pool holding the three models' re-tiled weights,

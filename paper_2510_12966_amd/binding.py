@@ -38,7 +38,7 @@ class _Params(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("proposed_q", "accepted_q", "fuzzy_q", "proposed_t", "accepted_t", "fuzzy_t",
                                          "passes_d", "passes_q", "passes_t")] + \
-               [("ms_prefill", C.c_double), ("ms_decode", C.c_double)]
+               [(n, C.c_double) for n in ("ms_prefill", "ms_decode", "ms_d", "ms_q", "ms_t", "ms_accept")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

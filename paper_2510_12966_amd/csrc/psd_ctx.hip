@@ -29,6 +29,35 @@ struct GraphSlot {
     hipGraphExec_t exec = nullptr;
 };
 
+// device time per stage of the loop: event pairs recorded in stream order, read once at the end of a call
+struct StageTimer {
+    struct Span { int kind; hipEvent_t a, b; };
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+    void begin(hipStream_t s, int kind) { spans.push_back({kind, get(), get()}); (void)hipEventRecord(spans.back().a, s); }
+    void end(hipStream_t s) { (void)hipEventRecord(spans.back().b, s); }
+    void collect(double ms[4]) {  // call after the stream has been synchronised
+        for (auto& sp : spans) {
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, sp.a, sp.b) == hipSuccess) ms[sp.kind] += t;
+            pool.push_back(sp.a);
+            pool.push_back(sp.b);
+        }
+        spans.clear();
+    }
+    ~StageTimer() {
+        double dummy[4] = {0, 0, 0, 0};
+        collect(dummy);
+        for (auto e : pool) (void)hipEventDestroy(e);
+    }
+};
+
 }  // namespace psd
 
 using namespace psd;
@@ -61,9 +90,10 @@ struct psd_ctx {
     char* stage = nullptr;  // kStageSlots * kStageSlotBytes
     int stage_next = 0, stage_since_sync = 0;
     RoundResult* res = nullptr;
-    // graphs: [model][width class 0/1]
-    GraphSlot graphs[3][2];
+    // graphs: [model][width class 4 / 16 / 32]
+    GraphSlot graphs[3][3];
     Profiler prof;
+    StageTimer timer;
     psd_trace_fn trace = nullptr;
     void* trace_user = nullptr;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -107,7 +137,7 @@ static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
     return PSD_OK;
 }
 
-static int wclass(int w) { return w <= 16 ? 16 : 32; }
+static int wclass(int w) { return w <= 4 ? 4 : (w <= 16 ? 16 : 32); }
 
 // enqueues one pass of model `mi`; the descriptor is already on the device.  with_sample: the draft step
 // also samples its token and advances the chain.
@@ -129,7 +159,7 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
         return PSD_OK;
     };
     if (!use_graph) return enqueue(&c->prof);
-    GraphSlot& g = c->graphs[mi][wcls == 16 ? 0 : 1];
+    GraphSlot& g = c->graphs[mi][wcls == 4 ? 0 : (wcls == 16 ? 1 : 2)];
     if (!g.exec) {
         hipGraph_t graph = nullptr;
         PSD_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal), c->err);
@@ -416,16 +446,22 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             if ((rc = upload(c, D.desc, &dd, sizeof(dd))) != PSD_OK) return rc;
             if ((rc = upload(c, Q.desc, &qd, sizeof(qd))) != PSD_OK) return rc;
             if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
+            c->timer.begin(c->stream, 0);
             for (int i = 0; i < m; ++i)
-                if ((rc = run_pass(c, 0, 16, c->DL, true, true)) != PSD_OK) return rc;
+                if ((rc = run_pass(c, 0, 4, c->DL, true, true)) != PSD_OK) return rc;
+            c->timer.end(c->stream);
             st.passes_d += m;
+            c->timer.begin(c->stream, 1);
             if ((rc = run_pass(c, 1, wclass(hq + m), c->QL, false, true)) != PSD_OK) return rc;
+            c->timer.end(c->stream);
             st.passes_q++;
             const int bonus = nbuf + m < k2;
             if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage1"), (double)(2 * m + 1) * V * 4);
+            c->timer.begin(c->stream, 3);
             rc = accept_launch(c->QL + (size_t)nbuf * V, c->DL, c->round_tok, 1, m, V, c->prm.T_q, c->prm.temperature, seed,
                                (uint32_t)L, 1u, bonus, c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
             if (rc != PSD_OK) return rc;
+            c->timer.end(c->stream);
             if (c->prof.on) c->prof.end(c->stream);
             PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
             PSD_HIP(hipMemcpyAsync(c->res->tok, c->round_tok, m * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
@@ -457,12 +493,16 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         fill_desc(td, seq.data(), T.len, C + k2, 0, k2 + 1, 0);
         if ((rc = upload(c, T.desc, &td, sizeof(td))) != PSD_OK) return rc;
         if ((rc = upload(c, c->win_tok, seq.data() + C, k2 * sizeof(int32_t))) != PSD_OK) return rc;
+        c->timer.begin(c->stream, 2);
         if ((rc = run_pass(c, 2, wclass(wT), c->TL, false, true)) != PSD_OK) return rc;
+        c->timer.end(c->stream);
         st.passes_t++;
         if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k2 + 1) * V * 4);
+        c->timer.begin(c->stream, 3);
         rc = accept_launch(c->TL, c->QL, c->win_tok, 1, k2, V, c->prm.T_t, c->prm.temperature, seed, (uint32_t)C, 2u, 1,
                            c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
         if (rc != PSD_OK) return rc;
+        c->timer.end(c->stream);
         if (c->prof.on) c->prof.end(c->stream);
         PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
         if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, k2 * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
@@ -490,6 +530,9 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     st.ms_prefill = ms;
     PSD_HIP(hipEventElapsedTime(&ms, c->ev[1], c->ev[2]), c->err);
     st.ms_decode = ms;
+    double stage_ms[4] = {0, 0, 0, 0};
+    c->timer.collect(stage_ms);
+    st.ms_d = stage_ms[0]; st.ms_q = stage_ms[1]; st.ms_t = stage_ms[2]; st.ms_accept = stage_ms[3];
     if (n_new > 0) memcpy(out_tokens, seq.data() + n_prompt, (size_t)n_new * sizeof(int32_t));
     if (out_stats) *out_stats = st;
     return PSD_OK;
@@ -519,7 +562,7 @@ extern "C" int psd_generate_plain(psd_ctx* c, int32_t which, const int32_t* prom
         PassDesc d;
         fill_desc(d, seq.data(), M.len, L, 0, 1, 0);
         if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
-        if ((rc = run_pass(c, which, 16, c->HL, false)) != PSD_OK) return rc;
+        if ((rc = run_pass(c, which, 4, c->HL, false)) != PSD_OK) return rc;
         if ((rc = sample_launch(c->HL, 1, c->V, c->prm.temperature, seed, (uint32_t)L, nullptr, c->samp_tok, c->samp_part, c->stream, c->err)) != PSD_OK) return rc;
         PSD_HIP(hipMemcpyAsync(c->res->tok, c->samp_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
         if ((rc = stage_sync(c)) != PSD_OK) return rc;

@@ -91,8 +91,6 @@ struct Model {
     void* xb = nullptr;       // GEMM input operand (bf16 hi/lo tiles, or plain fp32 rows): normalised residual
     void* xb2 = nullptr;      // second operand buffer: attention output / SwiGLU output (bf16 path)
     float* ss = nullptr;      // [d/16][32] partial sums of squares of the residual stream (bf16 path)
-    void* sk_part = nullptr;  // split-K partial tiles (bf16 path)
-    unsigned int* sk_count = nullptr;
     float* qkv = nullptr;     // [32][nqkv]
     float* gu = nullptr;      // [32][2F]
     float* attn_part = nullptr;  // [nsplit_max][32][H][hd + 2]
@@ -111,7 +109,7 @@ int model_init(Model& M, const psd_model_desc& desc, const char* tag, int max_se
 // Makes sure KV pages exist for positions < upto and frees pages wholly beyond `keep`; uploads the table if it changed.
 int model_map_pages(Model& M, int keep, int upto, hipStream_t stream, char* err);
 
-// Enqueues one pass described by *M.desc (already on the device).  wmax: 16 or 32 = widest pass the launch must cover.
+// Enqueues one pass described by *M.desc (already on the device).  wmax: 4, 16 or 32 = widest pass the launch must cover.
 // logits: device [rows][V] destination (may be null when the pass produces none).
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err);
 

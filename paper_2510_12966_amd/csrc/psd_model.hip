@@ -254,6 +254,29 @@ __global__ void attn_combine_pack(const float* part, const PassDesc* desc, void*
     pack_store<BF16>(xb, H * hd, c, h * hd + i, o / Lsum);
 }
 
+// Merge of the split partials of one (token, head): the same arithmetic wherever it is done, so that a token's
+// attention output has the same bits whichever kernel merges it.  Returns the normalised output of head dims
+// i .. i + N - 1.
+template <int N>
+__device__ inline void attn_merge(const float* part, int nsp, int c, int head, int H, int hd, int i, float out[N]) {
+    const size_t stride = (size_t)kMaxW * H * (hd + 2);
+    const float* p0 = part + ((size_t)c * H + head) * (hd + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < nsp; ++s) M = fmaxf(M, p0[s * stride]);
+    float Lsum = 0.f;
+#pragma unroll
+    for (int e = 0; e < N; ++e) out[e] = 0.f;
+    for (int s = 0; s < nsp; ++s) {
+        const float* pr = p0 + s * stride;
+        const float f = expf(pr[0] - M);
+        Lsum = fmaf(pr[1], f, Lsum);
+#pragma unroll
+        for (int e = 0; e < N; ++e) out[e] = fmaf(pr[2 + i + e], f, out[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < N; ++e) out[e] = out[e] / Lsum;
+}
+
 // ---- skinny GEMMs (bf16 weights, MFMA) ---------------------------------------------------------------
 // Epilogues fused into the GEMM that produces the value:
 //   EPI_QKV     rms scale, rotary embedding, q to the query buffer, k / v into the paged KV cache
@@ -284,19 +307,7 @@ struct GemmArgs {
     uint16_t* kv;
     const int32_t* page_table;
     int layer, L, H, KV, hd;
-    // split-K across workgroups (gridDim.y > 1)
-    f32x4* sk_part;        // [tile][S][2][64]
-    unsigned int* sk_count;  // [tile], zero between launches
 };
-
-__device__ inline float rms_scale(const GemmArgs& a, int c, int g) {
-    // every lane sums the tiles congruent to g mod 4 in order, then a fixed butterfly over g
-    float s = 0.f;
-    for (int t = g; t < a.ss_tiles; t += 4) s += a.ss_in[t * 32 + c];
-    s += __shfl_xor(s, 16, kWave);
-    s += __shfl_xor(s, 32, kWave);
-    return rsqrtf(s * a.inv_d + a.eps);
-}
 
 // stores 4 (or 2) consecutive features of column c into a packed operand
 __device__ inline void pack4(void* xb, int c, int f0, const float v[4]) {
@@ -380,102 +391,108 @@ __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w
     }
 }
 
-// One workgroup (4 waves) per 16 output rows and K range; the waves split that range and are summed in wave
-// order; with gridDim.y > 1 the K ranges of different workgroups are summed in range order by whichever
-// workgroup finishes last (no waiting: the others leave their partial tile and go).
-template <int NT, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16(const GemmArgs a) {
-    __shared__ f32x4 red[3][NT][64];
-    const int tile = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int S = gridDim.y, sp = blockIdx.y;
-    const int kb = (int)(((long)a.KS * sp) / S), ke = (int)(((long)a.KS * (sp + 1)) / S);
-    const int k0 = kb + (((ke - kb) * wave) >> 2), k1 = kb + (((ke - kb) * (wave + 1)) >> 2);
+// One workgroup of NW waves per RT tiles of 16 output rows; the waves split K and are summed in wave order.
+// A wave multiplies RT row tiles by the same activation operand, which is loaded once per K step (the operand
+// comes from L2 and would otherwise cost twice the weight bytes) and only by the lanes whose column is in use.
+// Small projections get more waves and fewer tiles per workgroup so that enough loads are in flight.
+// The rms scale of the input is gathered on the side: every thread loads a few sum-of-squares partials before
+// the K loop and they are folded through LDS, in a fixed order, when the loop is done.
+template <int NT, int NW, int RT, int EPI>
+__global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
+    __shared__ f32x4 red[NW - 1][RT][NT][64];
+    __shared__ float ssp[4 * NW][16 * NT];
+    const int tile0 = blockIdx.x * RT, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int k0 = (int)(((long)a.KS * wave) / NW), k1 = (int)(((long)a.KS * (wave + 1)) / NW);
     const int g = lane >> 4, cc = lane & 15;
+    const int w = a.desc->w;
     constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
-    float rs[NT];
+    float ss_mine[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) rs[t] = 1.f;
-    if (kScaled && wave == 0 && S == 1) {
+    for (int t = 0; t < NT; ++t) ss_mine[t] = 0.f;
+    if constexpr (kScaled) {
+        const int gi = wave * 4 + g;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) rs[t] = rms_scale(a, t * 16 + cc, g);
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll 8
+            for (int st = gi; st < a.ss_tiles; st += 4 * NW) ss_mine[t] += a.ss_in[st * 32 + t * 16 + cc];
+        }
     }
-    const u32x4* a_ptr = a.Wt + ((size_t)tile * a.KS + k0) * 64 + lane;
+    const u32x4* a_ptr = a.Wt + ((size_t)tile0 * a.KS + k0) * 64 + lane;
+    const size_t tile_stride = (size_t)a.KS * 64;
     const u32x4* b_ptr = a.XB + (size_t)k0 * 256 + lane;
-    f32x4 acc[NT];
+    bool col_live[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = 8;
-    int ks = k0;
-    for (; ks + U <= k1; ks += U) {
-        u32x4 wv[U];
+    for (int t = 0; t < NT; ++t) col_live[t] = t * 16 + cc < w;
+    f32x4 acc[RT][NT];
 #pragma unroll
-        for (int u = 0; u < U; ++u) wv[u] = __builtin_nontemporal_load(a_ptr + (size_t)u * 64);
+    for (int r = 0; r < RT; ++r)
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int U = RT >= 4 ? 2 : (RT == 2 ? 4 : 8);
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const u32x4 bh = b_ptr[(size_t)u * 256 + t * 128], bl = b_ptr[(size_t)u * 256 + t * 128 + 64];
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u]),
-                                                                 __builtin_bit_cast(bf16x8, bh), acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u]),
-                                                                 __builtin_bit_cast(bf16x8, bl), acc[t], 0, 0, 0);
+        for (int t = 0; t < NT; ++t) {
+            u32x4 bh = zero, bl = zero;
+            if (col_live[t]) { bh = bp[t * 128]; bl = bp[t * 128 + 64]; }
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
+                                                                    __builtin_bit_cast(bf16x8, bh), acc[r][t], 0, 0, 0);
+                acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
+                                                                    __builtin_bit_cast(bf16x8, bl), acc[r][t], 0, 0, 0);
             }
         }
+    };
+    int ks = k0;
+    for (; ks + U <= k1; ks += U) {
+        u32x4 wv[U][RT];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+#pragma unroll
+        for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * 256);
         a_ptr += (size_t)U * 64;
         b_ptr += (size_t)U * 256;
     }
     for (; ks < k1; ++ks) {
-        const u32x4 wv = __builtin_nontemporal_load(a_ptr);
+        u32x4 wv[RT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv),
-                                                             __builtin_bit_cast(bf16x8, b_ptr[t * 128]), acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv),
-                                                             __builtin_bit_cast(bf16x8, b_ptr[t * 128 + 64]), acc[t], 0, 0, 0);
-        }
+        for (int r = 0; r < RT; ++r) wv[r] = __builtin_nontemporal_load(a_ptr + r * tile_stride);
+        step(wv, b_ptr);
         a_ptr += 64;
         b_ptr += 256;
     }
     if (wave > 0) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) red[wave - 1][t][lane] = acc[t];
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) red[wave - 1][r][t][lane] = acc[r][t];
+    }
+    if constexpr (kScaled) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) ssp[wave * 4 + g][t * 16 + cc] = ss_mine[t];
     }
     __syncthreads();
     if (wave != 0) return;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        acc[t] += red[0][t][lane];
-        acc[t] += red[1][t][lane];
-        acc[t] += red[2][t][lane];
-    }
-    if (S > 1) {
-        f32x4* mine = a.sk_part + (((size_t)tile * S + sp) * 2) * 64;
+        float rs = 1.f;
+        if constexpr (kScaled) {
+            float ssum = 0.f;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) mine[t * 64 + lane] = acc[t];
-        __threadfence();
-        unsigned int ticket = 0;
-        if (lane == 0) ticket = atomicAdd(a.sk_count + tile, 1u);
-        ticket = __builtin_amdgcn_readfirstlane(ticket);
-        if (ticket != (unsigned)(S - 1)) return;
-        __threadfence();
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int q = 0; q < S; ++q) sum += a.sk_part[(((size_t)tile * S + q) * 2 + t) * 64 + lane];
-            acc[t] = sum;
+            for (int v = 0; v < 4 * NW; ++v) ssum += ssp[v][t * 16 + cc];
+            rs = rsqrtf(ssum * a.inv_d + a.eps);
         }
-        if (lane == 0) a.sk_count[tile] = 0u;
-        if (kScaled) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t) rs[t] = rms_scale(a, t * 16 + cc, g);
-        }
-    }
-    const int w = a.desc->w;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
         const int c = t * 16 + cc;
-        // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
-        if (c < w) epilogue<EPI>(a, tile, g, c, w, acc[t], rs[t]);
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+#pragma unroll
+            for (int v = 0; v < NW - 1; ++v) acc[r][t] += red[v][r][t][lane];
+            // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
+            if (c < w) epilogue<EPI>(a, tile0 + r, g, c, w, acc[r][t], rs);
+        }
     }
 }
 
@@ -507,134 +524,159 @@ __global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const Pa
 }
 
 // ---- attention, bf16 KV cache, MFMA ---------------------------------------------------------------------
-// grid (KV heads, nsplit_max), 256 threads.  A workgroup owns one KV head and the absolute key range
-// [split * 128, +128); wave j owns the 32 keys [split * 128 + 32 j, +32).  Query rows of the group are
-// rho = token * G + head_in_group, processed 16 at a time:
+// grid (KV heads, nsplit_max, query tiles), 256 threads.  A workgroup owns one KV head, the absolute key range
+// [split * 128, +128) and 16 query rows rho = token * G + head_in_group; wave j owns the 32 keys
+// [split * 128 + 32 j, +32):
 //   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 head dims straight from the K page,
-//                  B = queries as bf16 hi + lo from LDS; result lane (g, c): keys 4g..4g+3 of query c
+//                  B = queries as bf16 hi + lo built in registers; result lane (g, c): keys 4g..4g+3 of query c
 //   P   = exp(S - max) per query over the wave's 32 keys (masked causally), kept in registers: the result
 //         layout of S^T is exactly the A operand layout of v_mfma_f32_16x16x16bf16_1k
 //   O   = P V      B = 4 consecutive keys of one head dim: one 8-byte load from the transposed V page
 // The four waves' (max, sum, O) are merged through LDS in wave order and written as one partial per split.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
 template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDesc* desc, const uint16_t* kv,
                                                  const int32_t* page_table, float* part, int layer, int L, int H,
                                                  int KV, int nqkv) {
-    extern __shared__ float lds[];
     constexpr int KSQ = HD / 32, JT = HD / 16;
-    const int gkv = blockIdx.x, split = blockIdx.y;
+    __shared__ float mrg[4][16][HD + 2];
+    const int gkv = blockIdx.x, split = blockIdx.y, qt = blockIdx.z;
     const int w = desc->w, pos0 = desc->pos0;
     const int key0 = split * kAttnSplit, kv_max = pos0 + w;
-    if (key0 >= kv_max) return;
-    const int G = H / KV, R = w * G, QT = (R + 15) >> 4;
-    u32x4* qB = reinterpret_cast<u32x4*>(lds);                       // [QT][KSQ][2][64]
-    float* mrg = lds + (size_t)QT * KSQ * 2 * 64 * 4;                // [4 waves][16 queries][HD + 2]
-    const float scale = rsqrtf((float)HD);
-    {   // queries -> bf16 hi / lo B operands (rows beyond R are zero)
-        uint16_t* q16 = reinterpret_cast<uint16_t*>(qB);
-        for (int idx = threadIdx.x; idx < QT * 16 * HD; idx += 256) {
-            const int rho = idx / HD, i = idx % HD;
-            float v = 0.f;
-            if (rho < R) v = qkv[(size_t)(rho / G) * nqkv + (size_t)(gkv * G + rho % G) * HD + i] * scale;
-            const uint16_t hi = f32_to_bf16(v), lo = f32_to_bf16(v - bf16_to_f32(hi));
-            const size_t o = ((((size_t)(rho >> 4) * KSQ + (i >> 5)) * 2) * 64 + ((i & 31) >> 3) * 16 + (rho & 15)) * 8 + (i & 7);
-            q16[o] = hi;
-            q16[o + 512] = lo;
-        }
-    }
-    __syncthreads();
+    const int G = H / KV, R = w * G;
+    if (key0 >= kv_max || qt * 16 >= R) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, cq = lane & 15;
     const int wkey0 = key0 + wave * 32;
     const bool wave_live = wkey0 < kv_max;
-    // K rows (A operand of S^T) and V^T columns of this wave's 32 keys: all inside one page
-    const int page = page_table[wkey0 / kPage], slot0 = wkey0 % kPage;
-    const uint16_t* Kp = kv + kv_base(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
-    const uint16_t* Vp = kv + kv_base(page, layer, L, gkv, KV, 1, HD) + slot0;
-    for (int qt = 0; qt < QT; ++qt) {
-        float m = -INFINITY, l = 0.f;
-        f32x4 O[JT];
+    const int rho = qt * 16 + cq;
+    float m = -INFINITY, l = 0.f;
+    f32x4 O[JT];
 #pragma unroll
-        for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (wave_live) {
-            f32x4 Sx[2];
+    for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (wave_live) {
+        // this wave's 32 keys sit inside one page: K rows are the A operand of S^T, V^T columns the B operand of P V
+        const int page = page_table[wkey0 / kPage], slot0 = wkey0 % kPage;
+        const uint16_t* Kp = kv + kv_base(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
+        const uint16_t* Vp = kv + kv_base(page, layer, L, gkv, KV, 1, HD) + slot0;
+        u32x4 ka[2][KSQ];
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                Sx[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int ks = 0; ks < KSQ; ++ks) {
-                    const u32x4 ka = *reinterpret_cast<const u32x4*>(Kp + (size_t)(kt * 16 + cq) * HD + ks * 32 + g * 8);
-                    const u32x4 bh = qB[((size_t)(qt * KSQ + ks) * 2) * 64 + lane], bl = qB[((size_t)(qt * KSQ + ks) * 2 + 1) * 64 + lane];
-                    Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, bh), Sx[kt], 0, 0, 0);
-                    Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, bl), Sx[kt], 0, 0, 0);
-                }
-            }
-            // causal mask: key position <= query position; rows beyond R see nothing
-            const int rho = qt * 16 + cq;
-            const int qpos = rho < R ? pos0 + rho / G : -1;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int kp = wkey0 + kt * 16 + g * 4 + r;
-                    if (kp > qpos) Sx[kt][r] = -INFINITY;
-                    m = fmaxf(m, Sx[kt][r]);
-                }
-            m = fmaxf(m, __shfl_xor(m, 16, kWave));
-            m = fmaxf(m, __shfl_xor(m, 32, kWave));
-            const float msafe = m == -INFINITY ? 0.f : m;
-            typedef __attribute__((ext_vector_type(4))) short s16x4;
-            s16x4 Ph[2], Pl[2];
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float p = expf(Sx[kt][r] - msafe);   // exp(-inf) = 0 for masked keys
-                    l += p;
-                    const uint16_t hi = f32_to_bf16(p);
-                    Ph[kt][r] = (short)hi;
-                    Pl[kt][r] = (short)f32_to_bf16(p - bf16_to_f32(hi));
-                }
-            l += __shfl_xor(l, 16, kWave);
-            l += __shfl_xor(l, 32, kWave);
-#pragma unroll
-            for (int j = 0; j < JT; ++j)
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt) {
-                    const uint2 raw = *reinterpret_cast<const uint2*>(Vp + (size_t)(j * 16 + cq) * kPage + kt * 16 + g * 4);
-                    const s16x4 vb = __builtin_bit_cast(s16x4, raw);
-                    O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph[kt], vb, O[j], 0, 0, 0);
-                    O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Pl[kt], vb, O[j], 0, 0, 0);
-                }
-        }
-        // merge the four waves: O lane (g, c) holds queries 4g + r, head dim 16 j + c
-        float* mine = mrg + (size_t)wave * 16 * (HD + 2);
-        if (g == 0) { mine[cq * (HD + 2)] = m; mine[cq * (HD + 2) + 1] = l; }
+            for (int ks = 0; ks < KSQ; ++ks)
+                ka[kt][ks] = *reinterpret_cast<const u32x4*>(Kp + (size_t)(kt * 16 + cq) * HD + ks * 32 + g * 8);
+        uint2 vraw[JT][2];
 #pragma unroll
         for (int j = 0; j < JT; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) mine[(g * 4 + r) * (HD + 2) + 2 + j * 16 + cq] = O[j][r];
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
-            const int qr = idx / HD, i = idx % HD, rho = qt * 16 + qr;
+            for (int kt = 0; kt < 2; ++kt)
+                vraw[j][kt] = *reinterpret_cast<const uint2*>(Vp + (size_t)(j * 16 + cq) * kPage + kt * 16 + g * 4);
+        // query row rho as B operand: lane (g, c) holds head dims 32 ks + 8 g .. + 8 of row c, scaled by 1/sqrt(hd)
+        const float scale = rsqrtf((float)HD);
+        u32x4 qh[KSQ], ql[KSQ];
+        const float* qrow = qkv + (size_t)(rho / G) * nqkv + (size_t)(gkv * G + rho % G) * HD;
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) {
+            float v[8];
             if (rho < R) {
-                float M = -INFINITY;
+                const float4 a0 = *reinterpret_cast<const float4*>(qrow + ks * 32 + g * 8);
+                const float4 a1 = *reinterpret_cast<const float4*>(qrow + ks * 32 + g * 8 + 4);
+                v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+            } else {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) M = fmaxf(M, mrg[((size_t)v * 16 + qr) * (HD + 2)]);
-                float Ls = 0.f, o = 0.f;
+                for (int e = 0; e < 8; ++e) v[e] = 0.f;
+            }
+            uint32_t hw[4], lw[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float* pr = mrg + ((size_t)v * 16 + qr) * (HD + 2);
-                    const float f = pr[0] == -INFINITY ? 0.f : expf(pr[0] - M);
-                    Ls += pr[1] * f;
-                    o += pr[2 + i] * f;
-                }
-                float* out = part + (((size_t)split * kMaxW + rho / G) * H + gkv * G + rho % G) * (HD + 2);
-                out[2 + i] = o;
-                if (i == 0) { out[0] = M; out[1] = Ls; }
+            for (int e = 0; e < 4; ++e) {
+                const float x0 = v[2 * e] * scale, x1 = v[2 * e + 1] * scale;
+                const uint16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+                hw[e] = h0 | ((uint32_t)h1 << 16);
+                lw[e] = f32_to_bf16(x0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(x1 - bf16_to_f32(h1)) << 16);
+            }
+            qh[ks] = u32x4{hw[0], hw[1], hw[2], hw[3]};
+            ql[ks] = u32x4{lw[0], lw[1], lw[2], lw[3]};
+        }
+        f32x4 Sx[2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            Sx[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KSQ; ++ks) {
+                Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt][ks]), __builtin_bit_cast(bf16x8, qh[ks]), Sx[kt], 0, 0, 0);
+                Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt][ks]), __builtin_bit_cast(bf16x8, ql[ks]), Sx[kt], 0, 0, 0);
             }
         }
-        __syncthreads();
+        // causal mask: key position <= query position; rows beyond R see nothing
+        const int qpos = rho < R ? pos0 + rho / G : -1;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int kp = wkey0 + kt * 16 + g * 4 + r;
+                if (kp > qpos) Sx[kt][r] = -INFINITY;
+                m = fmaxf(m, Sx[kt][r]);
+            }
+        m = fmaxf(m, __shfl_xor(m, 16, kWave));
+        m = fmaxf(m, __shfl_xor(m, 32, kWave));
+        const float msafe = m == -INFINITY ? 0.f : m;
+        s16x4 Ph[2], Pl[2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = expf(Sx[kt][r] - msafe);   // exp(-inf) = 0 for masked keys
+                l += p;
+                const uint16_t hi = f32_to_bf16(p);
+                Ph[kt][r] = (short)hi;
+                Pl[kt][r] = (short)f32_to_bf16(p - bf16_to_f32(hi));
+            }
+        l += __shfl_xor(l, 16, kWave);
+        l += __shfl_xor(l, 32, kWave);
+#pragma unroll
+        for (int j = 0; j < JT; ++j)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                const s16x4 vb = __builtin_bit_cast(s16x4, vraw[j][kt]);
+                O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph[kt], vb, O[j], 0, 0, 0);
+                O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Pl[kt], vb, O[j], 0, 0, 0);
+            }
     }
+    // merge the four waves: O lane (g, c) holds queries 4g + r, head dim 16 j + c
+    if (g == 0) { mrg[wave][cq][0] = m; mrg[wave][cq][1] = l; }
+#pragma unroll
+    for (int j = 0; j < JT; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mrg[wave][g * 4 + r][2 + j * 16 + cq] = O[j][r];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+        const int qr = idx / HD, i = idx % HD, rr = qt * 16 + qr;
+        if (rr < R) {
+            float M = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) M = fmaxf(M, mrg[v][qr][0]);
+            float Ls = 0.f, o = 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float f = mrg[v][qr][0] == -INFINITY ? 0.f : expf(mrg[v][qr][0] - M);
+                Ls = fmaf(mrg[v][qr][1], f, Ls);
+                o = fmaf(mrg[v][qr][2 + i], f, o);
+            }
+            float* out = part + (((size_t)split * kMaxW + rr / G) * H + gkv * G + rr % G) * (HD + 2);
+            out[2 + i] = o;
+            if (i == 0) { out[0] = M; out[1] = Ls; }
+        }
+    }
+}
+
+// grid (wmax, H), block hd: merges the split partials and writes the O-projection's input operand (wide passes)
+__global__ void attn_combine_bf16(const float* part, const PassDesc* desc, void* xb, int H, int hd) {
+    const int c = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+    if (c >= desc->w) return;
+    const int nsp = (desc->pos0 + c + kAttnSplit) / kAttnSplit;  // splits holding keys <= pos0 + c
+    float o[1];
+    attn_merge<1>(part, nsp, c, h, H, hd, i, o);
+    pack_store<true>(xb, H * hd, c, h * hd + i, o[0]);
 }
 
 // fp32 weights, row-major [N][K]; X fp32 rows [c][K].  One wave per output row.
@@ -708,19 +750,13 @@ Profiler::~Profiler() {
 
 // ---- sizing / init ----------------------------------------------------------------------------------
 static size_t esize(int dtype) { return dtype == PSD_BF16 ? 2 : 4; }
-constexpr int kSplitKMaxTiles = 512;   // split-K across workgroups is only used below this many row tiles
-constexpr int kSplitKMaxUnits = 4096;  // tiles * splits
+
 static int round16(int n) { return (n + 15) & ~15; }
 
 static int attn_lds_bytes(int hd) { return (2 * kAttnSplit * (hd + 1) + 4 * hd + 4 * kAttnSplit) * (int)sizeof(float); }
 
-static int attn_mfma_lds(int hd, int qt) { return qt * (hd / 32) * 2 * 64 * 16 + 4 * 16 * (hd + 2) * (int)sizeof(float); }
-
 int model_kernels_init(char* err) {
     // attention stages two pages of K and V as fp32 in LDS: up to ~135 KB of the 160 KB a gfx950 CU has
-    PSD_HIP(hipFuncSetAttribute((const void*)attn_mfma<32>, hipFuncAttributeMaxDynamicSharedMemorySize, attn_mfma_lds(32, 8)), err);
-    PSD_HIP(hipFuncSetAttribute((const void*)attn_mfma<64>, hipFuncAttributeMaxDynamicSharedMemorySize, attn_mfma_lds(64, 8)), err);
-    PSD_HIP(hipFuncSetAttribute((const void*)attn_mfma<128>, hipFuncAttributeMaxDynamicSharedMemorySize, attn_mfma_lds(128, 8)), err);
     PSD_HIP(hipFuncSetAttribute((const void*)attn_partial<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 attn_lds_bytes(128)), err);
     return PSD_OK;
@@ -753,8 +789,6 @@ static int model_carve(Model& M, Pool& pool) {
     if (M.dtype == PSD_BF16) {
         M.xb2 = take(kmax * 128);
         M.ss = (float*)take((size_t)(M.d / 16) * 32 * sizeof(float));
-        M.sk_part = take((size_t)kSplitKMaxUnits * 2 * 64 * 16);
-        M.sk_count = (unsigned int*)take((size_t)kSplitKMaxTiles * sizeof(unsigned int));
     }
     M.qkv = (float*)take((size_t)kMaxW * M.nqkv * sizeof(float));
     M.gu = (float*)take((size_t)kMaxW * 2 * M.F * sizeof(float));
@@ -869,7 +903,6 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     if (bf) {
         PSD_HIP(hipMemsetAsync(M.xb2, 0, kmax * 128, stream), err);
         PSD_HIP(hipMemsetAsync(M.ss, 0, (size_t)(M.d / 16) * 32 * sizeof(float), stream), err);
-        PSD_HIP(hipMemsetAsync(M.sk_count, 0, (size_t)kSplitKMaxTiles * sizeof(unsigned int), stream), err);
     }
     // page bookkeeping: every logical block unmapped, free list in (optionally scrambled) order
     M.h_page_table.assign(M.n_pages, -1);
@@ -992,18 +1025,23 @@ template <int EPI>
 static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     Model& M = L.M;
     const int tiles = round16(a.N) / 16;
-    // few row tiles cannot fill 256 CUs: split K across workgroups as well (deterministic last-arriver sum)
-    int S = 1;
-    if (tiles < kSplitKMaxTiles) {
-        S = std::min({(768 + tiles - 1) / tiles, a.KS / 8, kSplitKMaxUnits / tiles});
-        S = std::max(S, 1);
-    }
-    a.sk_part = (f32x4*)M.sk_part;
-    a.sk_count = M.sk_count;
     a.desc = M.desc;
     L.begin(family, (double)a.N * a.KS * 32 * 2);
-    if (L.wcls <= 16) gemm_bf16<1, EPI><<<dim3(tiles, S), 256, 0, L.s>>>(a);
-    else gemm_bf16<2, EPI><<<dim3(tiles, S), 256, 0, L.s>>>(a);
+    // Waves per workgroup (the K split, hence the summation order) follow from the number of row tiles only, never
+    // from the pass width: a token's result must not depend on the width of the pass that computes it.  Row tiles
+    // per wave do not change the arithmetic and are picked per width class.
+    const bool wide = L.wcls > 16, narrow = L.wcls <= 4;
+#define PSD_GEMM(NT_, NW_, RT_) gemm_bf16<NT_, NW_, RT_, EPI><<<tiles / RT_, 64 * NW_, 0, L.s>>>(a)
+    if (tiles <= 512) {
+        if (wide) PSD_GEMM(2, 16, 1); else PSD_GEMM(1, 16, 1);
+    } else if (tiles <= 2048) {
+        if (narrow || tiles % 4) { if (wide) PSD_GEMM(2, 4, 1); else PSD_GEMM(1, 4, 1); }
+        else { if (wide) PSD_GEMM(2, 4, 4); else PSD_GEMM(1, 4, 4); }
+    } else {
+        if (tiles % 2) { if (wide) PSD_GEMM(2, 8, 1); else PSD_GEMM(1, 8, 1); }
+        else { if (wide) PSD_GEMM(2, 8, 2); else PSD_GEMM(1, 8, 2); }
+    }
+#undef PSD_GEMM
     L.end();
 }
 
@@ -1017,7 +1055,6 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     else embed_pack<2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, M.xb, M.layers[0].attn_norm, M.ss, d, M.V);
     L.end();
     const int qt_max = (wmax * G + 15) / 16;
-    const int lds = attn_mfma_lds(hd, qt_max);
     GemmArgs base{};
     base.ss_in = M.ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
     base.rope = M.rope; base.kv = (uint16_t*)M.kv; base.page_table = M.page_table;
@@ -1030,12 +1067,13 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         a.Y = M.qkv; a.ldy = M.nqkv; a.layer = l;
         launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
         L.begin("attn", 0);
-        if (hd == 128) attn_mfma<128><<<dim3(KV, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
-        else if (hd == 64) attn_mfma<64><<<dim3(KV, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
-        else attn_mfma<32><<<dim3(KV, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        const dim3 agrid(KV, M.nsplit_max, qt_max);
+        if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
         L.end();
         L.begin("attn_combine", act);
-        attn_combine_pack<true><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb2, H, hd);
+        attn_combine_bf16<<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb2, H, hd);
         L.end();
         a = base;
         a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)M.xb2; a.N = d; a.KS = (H * hd) / 32;
@@ -1058,7 +1096,7 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
 }
 
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err) {
-    if (wmax != 16 && wmax != 32) PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
+    if (wmax != 4 && wmax != 16 && wmax != 32) PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
     Launch L{M, stream, prof, wmax, {0}};
     int rc = M.dtype == PSD_BF16 ? forward_bf16(M, wmax, logits, L) : forward_f32(M, wmax, logits, L);
     if (rc != PSD_OK) return rc;

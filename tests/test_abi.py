@@ -48,7 +48,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(b._ModelDesc) == 6 * 4 + 2 * 4 + 2 * 4 + 8 + 8
     assert b._ModelDesc.weights.offset == 40 and b._ModelDesc.weights_bytes.offset == 48
     assert ctypes.sizeof(b._Params) == 8 * 4 + 8 and b._Params.pool_bytes.offset == 32
-    assert ctypes.sizeof(b.Stats) == 9 * 8 + 2 * 8
+    assert ctypes.sizeof(b.Stats) == 9 * 8 + 6 * 8
     assert ctypes.sizeof(b.KernelStat) == 48 + 8 + 8 + 8
 
 
