@@ -20,6 +20,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by a copy kernel of known size);
+# the runs are summarised in profiles/gemm_gate_up_paper_hbm_counters.md.  Keyed by kernel family and model.
+MEASURED_TRAFFIC_BYTES = {
+    ("paper", "gemm_gate_up draft"): 67.89e6,
+    ("paper", "gemm_gate_up target"): 238.0e6,
+    ("paper", "gemm_gate_up qualifier"): 101.7e6,
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -35,6 +43,9 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
+                         "hardware counters read under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs the batch-1 loop on ONE GPU; --gpus N with N > 1 is not supported "
@@ -59,6 +70,11 @@ def main() -> int:
                       temperature=cfg.temperature, flags=0 if args.no_graph else psd.FLAG_GRAPH)
     log(f"[bench] context created (weights uploaded and re-tiled) in {time.time() - t0:.1f} s")
 
+    if args.calibrate_copy:
+        a, b = psd.DeviceBuffer(256 << 20), psd.DeviceBuffer(256 << 20)
+        psd.lib().psd_dev_copy(b.data_ptr(), a.data_ptr(), 256 << 20, 2)
+        psd.dev_sync()
+        a.free(); b.free()
     for i in range(args.warmup):
         out, st = ctx.generate(prompt, n_new, cfg.sample_seed)
         log(f"[bench] warmup {i}: decode {st['ms_decode']:.1f} ms, prefill {st['ms_prefill']:.1f} ms")
@@ -95,7 +111,8 @@ def main() -> int:
         dom = kernels[0]
         ach = dom["bytes_total"] / dom["ms_total"] / 1e6
         roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom["name"].rsplit(" w<=", 1)[0])),
                     "avg_launch_us": round(dom["ms_total"] / dom["launches"] * 1e3, 2),
                     "bytes_per_launch": round(dom["bytes_total"] / dom["launches"]),
                     "all_gemm_GBps": None}
