@@ -79,8 +79,8 @@ struct Model {
     std::vector<LayerW> layers;
     const float* final_norm = nullptr;
     const float2* rope = nullptr;  // [max_seq][hd/2] (cos, sin)
-    // KV cache: page p, layer l, kv head g, k/v -> kPage * hd elements of dtype; K is [slot][hd];
-    // V is [slot][hd] for fp32 models and transposed, [hd][slot], for bf16 models (MFMA operand order)
+    // KV cache, 4 bytes per element.  fp32 models: page p, layer l, kv head g, k/v -> [slot][hd] floats.
+    // bf16 models: four bf16 planes per (p, l, g): K hi [slot][hd], K lo, V hi [hd][slot] (MFMA operand order), V lo
     void* kv = nullptr;
     int32_t* page_table = nullptr;  // device, [n_pages] logical block -> physical page
     std::vector<int32_t> h_page_table;

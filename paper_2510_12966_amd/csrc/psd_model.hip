@@ -136,6 +136,13 @@ __device__ inline float kv_load<float>(const float* p) { return *p; }
 template <>
 __device__ inline float kv_load<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
 
+// bf16 models keep every K and V element as a bf16 hi + lo pair (value = hi + lo to 2^-17) in four planes per
+// (page, layer, kv head): K hi [slot][hd], K lo, V hi [hd][slot] (transposed), V lo.  One bf16 rounding of the
+// cache alone would put ~0.1 % * sqrt(layers) of noise on the logits, which at 32 layers is past the tolerance.
+__device__ inline size_t kv_plane(int page, int layer, int L, int g, int KV, int plane, int hd) {
+    return ((((size_t)page * L + layer) * KV + g) * 4 + plane) * (size_t)kPage * hd;
+}
+
 __device__ inline size_t kv_base(int page, int layer, int L, int g, int KV, int which, int hd) {
     return ((((size_t)page * L + layer) * KV + g) * 2 + which) * (size_t)kPage * hd;
 }
@@ -291,6 +298,7 @@ struct GemmArgs {
     const u32x4* Wt;       // tiled weights [Npad/16][KS][64] x 16 B
     const u32x4* XB;       // packed activations [KS][2][2][64] x 16 B
     int N, KS;
+    int wcap;              // widest pass this launch is meant for (4, 16 or 32): operand columns >= wcap are not loaded
     const PassDesc* desc;
     // rms scale of the input (EPI_QKV, EPI_SWIGLU, EPI_LOGITS): partial sums of squares [d/16][32]
     const float* ss_in;
@@ -378,14 +386,22 @@ __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w
                 float* q = a.Y + (size_t)c * a.ldy + (size_t)head * hd;
                 q[j] = x0;
                 q[j + half] = x1;
-            } else if (head < a.H + a.KV) {   // K page: [slot][hd]
-                uint16_t* k = a.kv + kv_base(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
-                k[j] = f32_to_bf16(x0);
-                k[j + half] = f32_to_bf16(x1);
-            } else {                          // V page, transposed: [hd][slot]
-                uint16_t* vv = a.kv + kv_base(page, a.layer, a.L, head - a.H - a.KV, a.KV, 1, hd);
-                vv[(size_t)j * kPage + slot] = f32_to_bf16(x0);
-                vv[(size_t)(j + half) * kPage + slot] = f32_to_bf16(x1);
+            } else if (head < a.H + a.KV) {   // K planes: [slot][hd]
+                uint16_t* kh = a.kv + kv_plane(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
+                uint16_t* kl = kh + (size_t)kPage * hd;
+                const uint16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+                kh[j] = h0;
+                kh[j + half] = h1;
+                kl[j] = f32_to_bf16(x0 - bf16_to_f32(h0));
+                kl[j + half] = f32_to_bf16(x1 - bf16_to_f32(h1));
+            } else {                          // V planes, transposed: [hd][slot]
+                uint16_t* vh = a.kv + kv_plane(page, a.layer, a.L, head - a.H - a.KV, a.KV, 2, hd);
+                uint16_t* vl = vh + (size_t)kPage * hd;
+                const uint16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+                vh[(size_t)j * kPage + slot] = h0;
+                vh[(size_t)(j + half) * kPage + slot] = h1;
+                vl[(size_t)j * kPage + slot] = f32_to_bf16(x0 - bf16_to_f32(h0));
+                vl[(size_t)(j + half) * kPage + slot] = f32_to_bf16(x1 - bf16_to_f32(h1));
             }
         }
     }
@@ -404,7 +420,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     const int tile0 = blockIdx.x * RT, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int k0 = (int)(((long)a.KS * wave) / NW), k1 = (int)(((long)a.KS * (wave + 1)) / NW);
     const int g = lane >> 4, cc = lane & 15;
-    const int w = a.desc->w;
     constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
     float ss_mine[NT];
 #pragma unroll
@@ -422,13 +437,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     const u32x4* b_ptr = a.XB + (size_t)k0 * 256 + lane;
     bool col_live[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) col_live[t] = t * 16 + cc < w;
+    for (int t = 0; t < NT; ++t) col_live[t] = t * 16 + cc < a.wcap;   // known at launch: nothing waits for the descriptor
     f32x4 acc[RT][NT];
 #pragma unroll
     for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = RT >= 4 ? 2 : (RT == 2 ? 4 : 8);
+    constexpr int U = 16 / RT;   // 16 weight loads of 16 bytes in flight per lane
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
     auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp) {
 #pragma unroll
@@ -476,6 +491,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     }
     __syncthreads();
     if (wave != 0) return;
+    const int w = a.desc->w;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         float rs = 1.f;
@@ -527,7 +543,7 @@ __global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const Pa
 // grid (KV heads, nsplit_max, query tiles), 256 threads.  A workgroup owns one KV head, the absolute key range
 // [split * 128, +128) and 16 query rows rho = token * G + head_in_group; wave j owns the 32 keys
 // [split * 128 + 32 j, +32):
-//   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 head dims straight from the K page,
+//   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 head dims straight from the K planes (hi, lo),
 //                  B = queries as bf16 hi + lo built in registers; result lane (g, c): keys 4g..4g+3 of query c
 //   P   = exp(S - max) per query over the wave's 32 keys (masked causally), kept in registers: the result
 //         layout of S^T is exactly the A operand layout of v_mfma_f32_16x16x16bf16_1k
@@ -557,20 +573,27 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
     if (wave_live) {
         // this wave's 32 keys sit inside one page: K rows are the A operand of S^T, V^T columns the B operand of P V
         const int page = page_table[wkey0 / kPage], slot0 = wkey0 % kPage;
-        const uint16_t* Kp = kv + kv_base(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
-        const uint16_t* Vp = kv + kv_base(page, layer, L, gkv, KV, 1, HD) + slot0;
-        u32x4 ka[2][KSQ];
+        constexpr size_t kPlane = (size_t)kPage * HD;
+        const uint16_t* Kp = kv + kv_plane(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
+        const uint16_t* Vp = kv + kv_plane(page, layer, L, gkv, KV, 2, HD) + slot0;
+        u32x4 ka[2][KSQ], kb[2][KSQ];   // hi and lo halves
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int ks = 0; ks < KSQ; ++ks)
-                ka[kt][ks] = *reinterpret_cast<const u32x4*>(Kp + (size_t)(kt * 16 + cq) * HD + ks * 32 + g * 8);
-        uint2 vraw[JT][2];
+            for (int ks = 0; ks < KSQ; ++ks) {
+                const uint16_t* p = Kp + (size_t)(kt * 16 + cq) * HD + ks * 32 + g * 8;
+                ka[kt][ks] = *reinterpret_cast<const u32x4*>(p);
+                kb[kt][ks] = *reinterpret_cast<const u32x4*>(p + kPlane);
+            }
+        uint2 vraw[JT][2], vlow[JT][2];
 #pragma unroll
         for (int j = 0; j < JT; ++j)
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-                vraw[j][kt] = *reinterpret_cast<const uint2*>(Vp + (size_t)(j * 16 + cq) * kPage + kt * 16 + g * 4);
+            for (int kt = 0; kt < 2; ++kt) {
+                const uint16_t* p = Vp + (size_t)(j * 16 + cq) * kPage + kt * 16 + g * 4;
+                vraw[j][kt] = *reinterpret_cast<const uint2*>(p);
+                vlow[j][kt] = *reinterpret_cast<const uint2*>(p + kPlane);
+            }
         // query row rho as B operand: lane (g, c) holds head dims 32 ks + 8 g .. + 8 of row c, scaled by 1/sqrt(hd)
         const float scale = rsqrtf((float)HD);
         u32x4 qh[KSQ], ql[KSQ];
@@ -603,8 +626,10 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
             Sx[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KSQ; ++ks) {
+                // (k_hi + k_lo)(q_hi + q_lo) without the lo * lo term (2^-18 relative)
                 Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt][ks]), __builtin_bit_cast(bf16x8, qh[ks]), Sx[kt], 0, 0, 0);
                 Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt][ks]), __builtin_bit_cast(bf16x8, ql[ks]), Sx[kt], 0, 0, 0);
+                Sx[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kt][ks]), __builtin_bit_cast(bf16x8, qh[ks]), Sx[kt], 0, 0, 0);
             }
         }
         // causal mask: key position <= query position; rows beyond R see nothing
@@ -637,9 +662,10 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
         for (int j = 0; j < JT; ++j)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const s16x4 vb = __builtin_bit_cast(s16x4, vraw[j][kt]);
+                const s16x4 vb = __builtin_bit_cast(s16x4, vraw[j][kt]), vl = __builtin_bit_cast(s16x4, vlow[j][kt]);
                 O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph[kt], vb, O[j], 0, 0, 0);
                 O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Pl[kt], vb, O[j], 0, 0, 0);
+                O[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph[kt], vl, O[j], 0, 0, 0);
             }
     }
     // merge the four waves: O lane (g, c) holds queries 4g + r, head dim 16 j + c
@@ -781,7 +807,7 @@ static int model_carve(Model& M, Pool& pool) {
     }
     M.final_norm = (const float*)take(M.d * sizeof(float));
     M.rope = (const float2*)take((size_t)M.max_seq * (M.hd / 2) * sizeof(float2));
-    M.kv = take((size_t)M.n_pages * M.L * M.KV * 2 * kPage * M.hd * es);
+    M.kv = take((size_t)M.n_pages * M.L * M.KV * 2 * kPage * M.hd * 4);   // fp32, or bf16 hi + lo
     M.page_table = (int32_t*)take((size_t)M.n_pages * sizeof(int32_t));
     const size_t kmax = std::max((size_t)M.d, (size_t)M.F);
     M.x = (float*)take((size_t)kMaxW * M.d * sizeof(float));
@@ -899,7 +925,7 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     PSD_HIP(hipMemsetAsync(M.gu, 0, (size_t)kMaxW * 2 * F * sizeof(float), stream), err);
     PSD_HIP(hipMemsetAsync(M.desc, 0, sizeof(PassDesc), stream), err);
     // KV pages start as zeros: attention may read (and mask) slots of a page that were never written
-    PSD_HIP(hipMemsetAsync(M.kv, 0, (size_t)M.n_pages * M.L * M.KV * 2 * kPage * M.hd * es, stream), err);
+    PSD_HIP(hipMemsetAsync(M.kv, 0, (size_t)M.n_pages * M.L * M.KV * 2 * kPage * M.hd * 4, stream), err);
     if (bf) {
         PSD_HIP(hipMemsetAsync(M.xb2, 0, kmax * 128, stream), err);
         PSD_HIP(hipMemsetAsync(M.ss, 0, (size_t)(M.d / 16) * 32 * sizeof(float), stream), err);
@@ -1026,20 +1052,19 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     Model& M = L.M;
     const int tiles = round16(a.N) / 16;
     a.desc = M.desc;
+    a.wcap = L.wcls;
     L.begin(family, (double)a.N * a.KS * 32 * 2);
     // Waves per workgroup (the K split, hence the summation order) follow from the number of row tiles only, never
     // from the pass width: a token's result must not depend on the width of the pass that computes it.  Row tiles
     // per wave do not change the arithmetic and are picked per width class.
-    const bool wide = L.wcls > 16, narrow = L.wcls <= 4;
+    const bool wide = L.wcls > 16;
 #define PSD_GEMM(NT_, NW_, RT_) gemm_bf16<NT_, NW_, RT_, EPI><<<tiles / RT_, 64 * NW_, 0, L.s>>>(a)
-    if (tiles <= 512) {
+    if (tiles <= 256) {
         if (wide) PSD_GEMM(2, 16, 1); else PSD_GEMM(1, 16, 1);
-    } else if (tiles <= 2048) {
-        if (narrow || tiles % 4) { if (wide) PSD_GEMM(2, 4, 1); else PSD_GEMM(1, 4, 1); }
-        else { if (wide) PSD_GEMM(2, 4, 4); else PSD_GEMM(1, 4, 4); }
+    } else if (tiles % 2 == 0) {
+        if (wide) PSD_GEMM(2, 8, 2); else PSD_GEMM(1, 8, 2);
     } else {
-        if (tiles % 2) { if (wide) PSD_GEMM(2, 8, 1); else PSD_GEMM(1, 8, 1); }
-        else { if (wide) PSD_GEMM(2, 8, 2); else PSD_GEMM(1, 8, 2); }
+        if (wide) PSD_GEMM(2, 8, 1); else PSD_GEMM(1, 8, 1);
     }
 #undef PSD_GEMM
     L.end();

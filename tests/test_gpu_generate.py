@@ -160,3 +160,36 @@ def test_generate_argument_errors(tiny_stack):
     out, _ = ctx.generate(prompt, 0, 1)
     assert out.size == 0
     ctx.close()
+
+
+def test_paper_shapes_sampled_parity():
+    """Full-size models (1B / 3B / 8B shapes, vocabulary 128256) in the launch configuration bench.py times
+    (graph replay): every ACCEPT and every draft sample of a short run is replayed through the oracle on the GPU's
+    own logits, and one teacher-forced pass per model is compared with the oracle's forward."""
+    cfg = synth.CONFIGS["paper"]
+    d, q, t, prompt = synth.build_stack(cfg)
+    n_prompt, n_new = 24, 40
+    ctx = _ctx(cfg, (d, q, t), n_prompt + n_new + cfg.k2 + 2, cfg.T_q, cfg.T_t, cfg.k1, cfg.k2, flags=psd.FLAG_GRAPH)
+    rp = Replay(cfg.sample_seed, cfg.T_q, cfg.T_t)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt[:n_prompt], n_new, cfg.sample_seed)
+    print("paper stack:", st, "ties", rp.ties, "max div err", rp.max_div_err, flush=True)
+    assert rp.ties <= 1 and rp.events >= 10
+    # thresholds inside this stack's divergence range, so that rejections and resampling run at full size too
+    ctx.set_decoding(0.1, 0.12, cfg.k1, cfg.k2)
+    rp = Replay(5, 0.1, 0.12)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt[:n_prompt], n_new, 5)
+    ctx.set_trace(None)
+    print("paper stack, tighter thresholds:", st, "ties", rp.ties, flush=True)
+    assert rp.ties <= 1
+    toks = prompt[:12]
+    shapes, blobs = (cfg.draft, cfg.qualifier, cfg.target), (d, q, t)
+    for which in range(3):
+        om = oracle.Model(shapes[which], blobs[which], cfg.dtype, cfg.rope_theta, 16)
+        ref = om.forward(toks, 0)
+        got = np.concatenate([ctx.forward(which, toks[:1], 0), ctx.forward(which, toks[1:12], 1)])
+        err = float(np.abs(got - ref).max())
+        print(f"paper model {which}: max |logit err| {err:.3e}, logit std {ref.std():.3f}", flush=True)
+        assert err <= 3e-2
+    ctx.close()
