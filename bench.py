@@ -33,6 +33,73 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def accept_microbench(psd, synth) -> int:
+    """Stand-alone ACCEPT stage on batched trials: achieved GB/s (algorithmic bytes: every logit read once) and
+    accept-length histogram parity with the oracle on the same trials."""
+    import math
+
+    import oracle
+
+    V, seed, B, reps = 128256, 7, 48, 5
+    rows = []
+    for k in (4, 8, 16, 32):
+        for rho in (0.5, 0.8, 0.95):
+            P, Q, X = [], [], []
+            for b in range(B):
+                t, q, _ = synth.accept_logits(seed, b, k, V, rho)     # stage "target <- qualifier"
+                x = np.array([oracle.sample_row(q[i], 1.0, seed + b, 1000 + i)[0] for i in range(k)], dtype=np.int32)
+                P.append(t); Q.append(q[:k]); X.append(x)
+            dp, dq, dx = (psd.DeviceBuffer.from_numpy(np.stack(a)) for a in (P, Q, X))
+            na, nt, dv = psd.DeviceBuffer(4 * B), psd.DeviceBuffer(4 * B), psd.DeviceBuffer(4 * B * k)
+            wsb = psd.accept_workspace_bytes(B, k, V)
+            ws = psd.DeviceBuffer(wsb)
+            for T in (0.0, 0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, math.log(2)):
+                psd.accept_batch(dp, dq, dx, B, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
+                psd.dev_sync()
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    psd.accept_batch(dp, dq, dx, B, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
+                psd.dev_sync()
+                dt = (time.perf_counter() - t0) / reps
+                gbs = B * (2 * k + 1) * V * 4 / dt / 1e9
+                hist = np.bincount(na.to_numpy(np.int32, B), minlength=k + 1)
+                row = {"k": k, "rho": rho, "T": round(T, 4), "GBps": round(gbs, 1), "us_per_trial": round(dt / B * 1e6, 2),
+                       "hist": hist.tolist()}
+                if T in (0.0, 0.2):   # oracle on every trial of two thresholds per (k, rho)
+                    oh = np.zeros(k + 1, dtype=np.int64)
+                    for b in range(B):
+                        res, _ = oracle.accept(P[b], Q[b], X[b], T, 1.0, 100 + b, 50, 2, True)
+                        oh[res.n_accepted] += 1
+                    row["oracle_hist"] = oh.tolist()
+                    row["hist_equal"] = bool(np.array_equal(oh, hist))
+                rows.append(row)
+                log(f"[accept] k={k:2d} rho={rho:.2f} T={T:.3f}: {gbs:7.1f} GB/s, {dt / B * 1e6:7.2f} us/trial, hist {hist.tolist()}"
+                    + (f" oracle {row['oracle_hist']}" if "oracle_hist" in row else ""))
+            for b_ in (dp, dq, dx, na, nt, dv, ws):
+                b_.free()
+    best = max(r["GBps"] for r in rows)
+    print(json.dumps({"metric": "stand-alone ACCEPT stage, achieved GB/s (logits read once)", "value": best, "unit": "GB/s",
+                      "peak": HBM_PEAK_GBS, "frac": round(best / HBM_PEAK_GBS, 4), "trials_per_launch": B,
+                      "histograms_equal": all(r.get("hist_equal", True) for r in rows), "rows": rows}), flush=True)
+    return 0
+
+
+def sweep(ctx, cfg, prompt, n_new) -> int:
+    """k1 x k2 x T_q x T_t grid on one context (k1, k2 up to the configuration's own values)."""
+    grid_k = [(3, 6), (5, 10)] if cfg.k2 < 16 else [(3, 6), (5, 10), (8, 16)]
+    print("k1 k2 T_q T_t decode_tok_s accept_q accept_t ms_d ms_q ms_t passes_d passes_q passes_t", flush=True)
+    for (k1, k2) in grid_k:
+        for T_q in (0.2, 0.5, 0.8):
+            for T_t in (0.0, 0.3, 0.6):
+                ctx.set_decoding(T_q, T_t, k1, k2, cfg.temperature)
+                out, st = ctx.generate(prompt, n_new, cfg.sample_seed)
+                print(f"{k1} {k2} {T_q} {T_t} {n_new / st['ms_decode'] * 1e3:.1f} "
+                      f"{st['accepted_q'] / max(st['proposed_q'], 1):.3f} {st['accepted_t'] / max(st['proposed_t'], 1):.3f} "
+                      f"{st['ms_d'] / max(st['passes_d'], 1):.3f} {st['ms_q'] / max(st['passes_q'], 1):.3f} "
+                      f"{st['ms_t'] / max(st['passes_t'], 1):.3f} {st['passes_d']} {st['passes_q']} {st['passes_t']}", flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,6 +110,11 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--accept-microbench", action="store_true",
+                    help="instead of the loop: time the stand-alone batched ACCEPT stage (vocab 128256, k in 4/8/16/32, "
+                         "correlated synthetic logits) and check accept-length histograms against the oracle")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the timed steps: sweep k1 x k2 x T_q x T_t on the chosen configuration and print a table")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
                          "hardware counters read under rocprofv3 --pmc)")
@@ -55,6 +127,8 @@ def main() -> int:
     import paper_2510_12966_amd as psd
     from paper_2510_12966_amd import synth
 
+    if args.accept_microbench:
+        return accept_microbench(psd, synth)
     cfg = synth.CONFIGS[args.config]
     n_new = args.n_new or cfg.n_new
     t0 = time.time()
@@ -75,6 +149,8 @@ def main() -> int:
         psd.lib().psd_dev_copy(b.data_ptr(), a.data_ptr(), 256 << 20, 2)
         psd.dev_sync()
         a.free(); b.free()
+    if args.sweep:
+        return sweep(ctx, cfg, prompt, n_new)
     for i in range(args.warmup):
         out, st = ctx.generate(prompt, n_new, cfg.sample_seed)
         log(f"[bench] warmup {i}: decode {st['ms_decode']:.1f} ms, prefill {st['ms_prefill']:.1f} ms")

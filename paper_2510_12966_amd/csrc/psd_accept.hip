@@ -219,7 +219,7 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
                   hipStream_t stream, char* errbuf) {
     if (!logits_p || (k > 0 && (!logits_q || !tokens)) || !out || !workspace)
         PSD_FAIL(PSD_EINVAL, errbuf, "accept: null pointer");
-    if (k < 0 || k > PSD_MAX_WIDTH - 1 || vocab < 1 || n_trials < 1 || n_trials > 65535)
+    if (k < 0 || k > PSD_MAX_WIDTH || vocab < 1 || n_trials < 1 || n_trials > 65535)
         PSD_FAIL(PSD_EINVAL, errbuf, "accept: k=%d vocab=%d n_trials=%d out of range", k, vocab, n_trials);
     if (!(T >= 0.f) || !(temperature > 0.f)) PSD_FAIL(PSD_EINVAL, errbuf, "accept: T=%g temperature=%g", T, temperature);
     if (workspace_bytes < accept_workspace_bytes(n_trials, k, vocab))

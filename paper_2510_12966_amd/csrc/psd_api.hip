@@ -46,7 +46,7 @@ extern "C" int psd_accept(const float* logits_p, const float* logits_q, const in
     char* err = tls_error();
     if (!logits_p || !n_accepted || !next_token || (k > 0 && (!logits_q || !tokens)))
         PSD_FAIL(PSD_EINVAL, err, "psd_accept: null pointer");
-    if (k < 0 || k > PSD_MAX_WIDTH - 1 || vocab < 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: k=%d vocab=%d", k, vocab);
+    if (k < 0 || k > PSD_MAX_WIDTH || vocab < 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: k=%d vocab=%d", k, vocab);
     if (stage != 1 && stage != 2) PSD_FAIL(PSD_EINVAL, err, "psd_accept: stage must be 1 or 2");
     if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: where must be 0 or 1");
     if (!(T >= 0.f) || !(temperature > 0.f)) PSD_FAIL(PSD_EINVAL, err, "psd_accept: T=%g temperature=%g", T, temperature);
