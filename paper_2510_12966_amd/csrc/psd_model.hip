@@ -268,17 +268,41 @@ template <int N>
 __device__ inline void attn_merge(const float* part, int nsp, int c, int head, int H, int hd, int i, float out[N]) {
     const size_t stride = (size_t)kMaxW * H * (hd + 2);
     const float* p0 = part + ((size_t)c * H + head) * (hd + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < nsp; ++s) M = fmaxf(M, p0[s * stride]);
-    float Lsum = 0.f;
+    float M = -INFINITY, Lsum = 0.f;
 #pragma unroll
     for (int e = 0; e < N; ++e) out[e] = 0.f;
-    for (int s = 0; s < nsp; ++s) {
-        const float* pr = p0 + s * stride;
-        const float f = expf(pr[0] - M);
-        Lsum = fmaf(pr[1], f, Lsum);
+    if (nsp <= 8) {
+        // all partials in flight at once (one memory round trip); the arithmetic below is the general loop's
+        float m[8], l[8], o[8][N];
 #pragma unroll
-        for (int e = 0; e < N; ++e) out[e] = fmaf(pr[2 + i + e], f, out[e]);
+        for (int s = 0; s < 8; ++s)
+            if (s < nsp) {
+                const float* pr = p0 + s * stride;
+                m[s] = pr[0];
+                l[s] = pr[1];
+#pragma unroll
+                for (int e = 0; e < N; ++e) o[s][e] = pr[2 + i + e];
+            }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            if (s < nsp) M = fmaxf(M, m[s]);
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            if (s < nsp) {
+                const float f = expf(m[s] - M);
+                Lsum = fmaf(l[s], f, Lsum);
+#pragma unroll
+                for (int e = 0; e < N; ++e) out[e] = fmaf(o[s][e], f, out[e]);
+            }
+    } else {
+        for (int s = 0; s < nsp; ++s) M = fmaxf(M, p0[s * stride]);
+        for (int s = 0; s < nsp; ++s) {
+            const float* pr = p0 + s * stride;
+            const float f = expf(pr[0] - M);
+            Lsum = fmaf(pr[1], f, Lsum);
+#pragma unroll
+            for (int e = 0; e < N; ++e) out[e] = fmaf(pr[2 + i + e], f, out[e]);
+        }
     }
 #pragma unroll
     for (int e = 0; e < N; ++e) out[e] = out[e] / Lsum;
@@ -510,6 +534,56 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             if (c < w) epilogue<EPI>(a, tile0 + r, g, c, w, acc[r][t], rs);
         }
     }
+}
+
+// o projection of a narrow pass (<= 4 tokens, K <= 2048, one row tile per workgroup): the merge of the attention
+// split partials, otherwise a kernel of its own, is done here while the weight blocks are in flight; the merged
+// rows go to LDS in B-operand order.  Same K split, MFMA order and reduction as gemm_bf16<1, 16, 1, EPI_RESID>, and
+// the same merge arithmetic as attn_combine_bf16, so the result has the same bits as the two-kernel route.
+__global__ __launch_bounds__(1024) void gemm_o_narrow(const GemmArgs a, const float* __restrict__ attn_part) {
+    constexpr int NW = 16, KSMAX = 64;
+    __shared__ f32x4 red[NW - 1][64];
+    __shared__ u32x4 sB[KSMAX * 2 * 4 * 4];   // [k step][hi, lo][g][column < 4]
+    const int tile = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int k0 = (int)(((long)a.KS * wave) / NW), k1 = (int)(((long)a.KS * (wave + 1)) / NW);
+    const int g = lane >> 4, cc = lane & 15;
+    const u32x4* a_ptr = a.Wt + ((size_t)tile * a.KS + k0) * 64 + lane;
+    u32x4 wv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (k0 + u < k1) wv[u] = __builtin_nontemporal_load(a_ptr + (size_t)u * 64);
+    const int w = a.desc->w, pos0 = a.desc->pos0, K = a.KS * 32;
+    uint16_t* sB16 = reinterpret_cast<uint16_t*>(sB);
+    // pairs of adjacent head dims: for one token that is exactly one pair per thread, i.e. one memory round trip
+    for (int pidx = threadIdx.x; pidx < 2 * K; pidx += 1024) {
+        const int c = pidx / (K >> 1), k = (pidx % (K >> 1)) * 2;
+        float v[2] = {0.f, 0.f};
+        if (c < w) attn_merge<2>(attn_part, (pos0 + c + kAttnSplit) / kAttnSplit, c, k / a.hd, a.H, a.hd, k % a.hd, v);
+        const uint16_t h0 = f32_to_bf16(v[0]), h1 = f32_to_bf16(v[1]);
+        const uint16_t l0 = f32_to_bf16(v[0] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[1] - bf16_to_f32(h1));
+        const int ks = k >> 5, gq = (k & 31) >> 3, e = k & 7;
+        *reinterpret_cast<uint32_t*>(sB16 + ((((ks * 2 + 0) * 4 + gq) * 4 + c) << 3) + e) = h0 | ((uint32_t)h1 << 16);
+        *reinterpret_cast<uint32_t*>(sB16 + ((((ks * 2 + 1) * 4 + gq) * 4 + c) << 3) + e) = l0 | ((uint32_t)l1 << 16);
+    }
+    __syncthreads();
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    auto step = [&](const u32x4 wblk, int ks) {
+        u32x4 bh = zero, bl = zero;
+        if (cc < 4) { bh = sB[((ks * 2 + 0) * 4 + g) * 4 + cc]; bl = sB[((ks * 2 + 1) * 4 + g) * 4 + cc]; }
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wblk), __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wblk), __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+    };
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (k0 + u < k1) step(wv[u], k0 + u);
+    for (int ks = k0 + 4; ks < k1; ++ks) step(__builtin_nontemporal_load(a_ptr + (size_t)(ks - k0) * 64), ks);
+    if (wave > 0) red[wave - 1][lane] = acc;
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int v = 0; v < NW - 1; ++v) acc += red[v][lane];
+    if (cc < w) epilogue<EPI_RESID>(a, tile, g, cc, w, acc, 1.f);
 }
 
 // token embedding: x = E[token]; also the first RMSNorm's operand and sum-of-squares partials.  grid d/16, 64 threads
@@ -1080,6 +1154,8 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     else embed_pack<2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, M.xb, M.layers[0].attn_norm, M.ss, d, M.V);
     L.end();
     const int qt_max = (wmax * G + 15) / 16;
+    // narrow passes of small models: the o projection merges the attention split partials itself (one launch less)
+    const bool fold_merge = wmax <= 4 && d <= 2048 && d / 16 <= 256 && H * hd == d;
     GemmArgs base{};
     base.ss_in = M.ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
     base.rope = M.rope; base.kv = (uint16_t*)M.kv; base.page_table = M.page_table;
@@ -1097,13 +1173,20 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
         else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
         L.end();
-        L.begin("attn_combine", act);
-        attn_combine_bf16<<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb2, H, hd);
-        L.end();
         a = base;
         a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)M.xb2; a.N = d; a.KS = (H * hd) / 32;
         a.Y = M.x; a.ldy = d; a.xb_out = M.xb; a.gain_out = w.ffn_norm; a.ss_out = M.ss;
-        launch_gemm_bf16<EPI_RESID>(L, "gemm_o", a);
+        if (fold_merge) {
+            a.desc = M.desc; a.wcap = 4;
+            L.begin("gemm_o", (double)d * d * 2);
+            gemm_o_narrow<<<d / 16, 1024, 0, stream>>>(a, M.attn_part);
+            L.end();
+        } else {
+            L.begin("attn_combine", act);
+            attn_combine_bf16<<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb2, H, hd);
+            L.end();
+            launch_gemm_bf16<EPI_RESID>(L, "gemm_o", a);
+        }
         a = base;
         a.Wt = (const u32x4*)w.wgu; a.XB = (const u32x4*)M.xb; a.N = 2 * F; a.KS = d / 32; a.xb_out = M.xb2;
         launch_gemm_bf16<EPI_SWIGLU>(L, "gemm_gate_up", a);
