@@ -171,12 +171,23 @@ int psd_accept(const float* logits_p, const float* logits_q, const int32_t* toke
  *   logits_p [n_trials][k+1][vocab], logits_q [n_trials][k][vocab], tokens [n_trials][k]
  *   n_accepted, next_token [n_trials]; div_out [n_trials][k] (may be NULL)
  *   workspace: device scratch of at least psd_accept_workspace_bytes(n_trials, k, vocab) bytes
- *   stream: a hipStream_t passed as void* (NULL = the default stream); the call only enqueues work. */
+ *   stream: a hipStream_t passed as void* (NULL = the default stream); the call only enqueues work.
+ * Logits must be finite or -inf (-inf entries have probability 0).  The kernels of one row wait for each
+ * other inside one launch; that wait is bounded by a clock, and if it ever expires (it cannot while the
+ * device runs the launch alone) n_accepted[b] = -1 for every trial of the call: psd_accept and psd_generate
+ * turn that into PSD_EHIP. */
 size_t psd_accept_workspace_bytes(int32_t n_trials, int32_t k, int32_t vocab);
 int psd_accept_batch(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t n_trials,
                      int32_t k, int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
                      uint32_t stage, int32_t take_bonus, int32_t* n_accepted, int32_t* next_token, float* div_out,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* How the ACCEPT stage sweeps the logits (Section 3.2 divergence), process-wide; for measurement and tests.
+ *   0  automatic: one launch that reads every logit once when a row has at most 256 chunks of 2048 entries,
+ *      else two launches that read the logits twice
+ *   1  always two launches     2  same as 0
+ * Both give bit-identical results.  Not thread-safe against running calls.  Returns PSD_EINVAL otherwise. */
+int psd_set_accept_path(int32_t path);
 
 /* Fresh sample from softmax(logits / temperature) by the exponential race (how the
  * draft proposes, Figure 1): rows [n_rows][vocab], row r is decided for position position0 + r.

@@ -68,6 +68,7 @@ def lib():
         L.psd_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_float,
                                  C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.c_void_p]
+        L.psd_set_accept_path.argtypes = [C.c_int32]
         L.psd_accept_workspace_bytes.restype = C.c_size_t
         L.psd_accept_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         L.psd_accept_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
@@ -171,6 +172,10 @@ def accept(logits_p, logits_q, tokens, T, temperature=1.0, seed=0, position0=0, 
                             temperature, seed, position0, stage, int(take_bonus), 0, C.byref(n), C.byref(t),
                             div.ctypes.data))
     return n.value, t.value, div[:k]
+
+
+def set_accept_path(path):
+    _check(lib().psd_set_accept_path(path))
 
 
 def accept_workspace_bytes(n_trials, k, vocab):

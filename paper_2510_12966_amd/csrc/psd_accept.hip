@@ -2,23 +2,48 @@
 // rows, Jensen-Shannon divergence per position, threshold / coin / first-reject scan and the
 // replacement draw (Sections 3.1-3.2 and the fallback rule named in Section 3.4).
 //
-// Three kernels, all bandwidth-shaped (each logit is read with coalesced 16-byte loads):
-//   accept_lse      per (trial, position, chunk): running max and sum of exponentials of both rows
-//   accept_div      per (trial, position, chunk): divergence partial, race partials, p(x), q(x)
-//   accept_decide   per trial: fixed-order reduction of the partials, coins, scan, token choice
-// The second sweep over the rows normally hits L2 / Infinity Cache because it follows the first
-// one immediately.  No atomics: every partial has its own slot, reductions run in index order.
+// Every logit of the k judged positions is read from HBM once.  Kernels, per call:
+//   accept_clear   marks the per-chunk result slots "not written"
+//   accept_sweep   one workgroup per (trial, position, chunk).  It keeps its chunk of both rows in
+//                  registers, publishes the chunk's (max, sum of exponentials), waits until the other
+//                  chunks of the same row have done so (they are launched next to it, so the wait is
+//                  short; it is bounded by a clock and reports expiry instead of spinning on), then
+//                  finishes the divergence partial from the registers.
+//   accept_decide  per trial: divergence per position (fixed-order sums), coins, first-reject scan
+//   accept_race    per (trial, chunk): exponential race over the ONE row that needs a replacement
+//                  token: the residual max(0, p - q) of the first rejected position, or the verifier's
+//                  last row for the bonus token.  Only this kernel draws vocabulary-wide random numbers.
+//   accept_pick    per trial: winner of the race
+// Bulk arithmetic runs in base 2 on the hardware exp2 / log2 units; the two probabilities the coin
+// compares are evaluated with the accurate library functions.  No floating-point atomics: every
+// partial has its own slot, reductions run in a fixed order, so results never depend on scheduling.
+// When a row has more chunks than may safely wait on each other, the sweep runs as two launches
+// (partials, then divergence) with the same arithmetic.
 #include "psd_device.h"
 #include "psd_host.h"
+
+// Every fused multiply-add in this file is written out: the compiler may not fuse a product into a
+// neighbouring sum on its own, so variants of one kernel round identically.
+#pragma clang fp contract(off)
 
 namespace psd {
 
 constexpr int kAccThreads = 256;
-constexpr int kQuadsPerThread = kAcceptChunk / 4 / kAccThreads;  // 4
+constexpr int kQuadsPerThread = kAcceptChunk / 4 / kAccThreads;  // 2 (sampling and race kernels)
+constexpr int kSweepQuads = 5, kSweepChunk = kSweepQuads * 4 * kAccThreads, kSweepWaves = kAccThreads / 64;
+constexpr int kSweepMaxSlots = 256;    // per-wave results of a row that workgroups wait for in the one-launch sweep
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.69314718055994531f;
+constexpr float kBig = 1e30f;
+constexpr unsigned long long kWaitTicks = 5000000ull;  // 50 ms of the 100 MHz wall clock
+constexpr uint32_t kUnwritten = 0xffffffffu;           // a NaN pattern no maximum can have
 
-struct LsePart { float mp, sp, mq, sq; };
-struct DivPart { float jsd; float key; int idx; float key_fb; int idx_fb; int pad0, pad1, pad2; };
+static int g_accept_path = 0;   // 0 automatic, 1 two-launch sweep, 2 one-launch sweep where it is allowed
+
+// base-2 maximum of a chunk and its sum of 2^(z - m), for the verifier row (p) and the proposer row (q);
+// each half is published with one 64-bit store and is valid once its m is not the unwritten pattern
+struct RowPart { float mp, sp, mq, sq; };
 struct TokProb { float px, qx; };
+struct RacePart { float key; int idx; float key_fb; int idx_fb; };
 
 // loads entries v .. v+3 of a row (entries >= V read as -inf: they carry no probability)
 __device__ inline void load4(const float* row, int v, int V, bool vec, float out[4]) {
@@ -30,193 +55,403 @@ __device__ inline void load4(const float* row, int v, int V, bool vec, float out
         for (int e = 0; e < 4; ++e) out[e] = (v + e < V) ? row[v + e] : -INFINITY;
     }
 }
+// the same, streaming: the sweep reads every entry exactly once
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ inline void load4_stream(const float* row, int v, int V, bool vec, float out[4]) {
+    if (vec && v + 3 < V) {
+        f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + v));
+        out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = (v + e < V) ? row[v + e] : -INFINITY;
+    }
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// ---- wave reductions on the data-parallel-primitive lanes (no LDS traffic) ----------------------
+// xor 1, xor 2, mirror within 8, mirror within 16: every lane of a row of 16 then holds the row's
+// result; two row broadcasts carry it to the last row, whose lane 63 is read out.  Fixed shape, so a
+// sum has fixed rounding.  Results are wave-uniform.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ inline float dpp_move(float old, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, BOUND));
+}
+__device__ inline float wave_sum_dpp(float v) {
+    v = v + dpp_move<0xB1, 0xf, true>(0.f, v);    // quad_perm [1,0,3,2]
+    v = v + dpp_move<0x4E, 0xf, true>(0.f, v);    // quad_perm [2,3,0,1]
+    v = v + dpp_move<0x141, 0xf, true>(0.f, v);   // row_half_mirror
+    v = v + dpp_move<0x140, 0xf, true>(0.f, v);   // row_mirror
+    v = v + dpp_move<0x142, 0xa, false>(0.f, v);  // row_bcast15 into rows 1 and 3
+    v = v + dpp_move<0x143, 0xc, false>(0.f, v);  // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// the same shape for the maximum; written as instructions because the generic maximum would re-quiet
+// both operands at every step (s_nop 1: a lane-crossing read must not follow the write of its source directly)
+__device__ inline float wave_max_dpp(float v) {
+    asm volatile(
+        "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+struct RowStats { float Mp, Sp, Mq, Sq; };  // base 2: p_v = 2^(z_v c2 - Mp) / Sp
 
 struct AcceptShape {
     const float* lp;  // [B][k+1][V]
     const float* lq;  // [B][k][V]
     const int32_t* tokens;  // [B][k]
-    int k, V, nch;
+    int k, V, nch;          // nch: chunks of kAcceptChunk entries (sampling and race kernels)
     float inv_temp;
+    int nsl;                // result slots per row of the sweep kernel: one per wave, 4 per workgroup
 };
 
-__global__ __launch_bounds__(kAccThreads) void accept_lse(AcceptShape s, LsePart* parts, TokProb* tokprob) {
-    __shared__ float sm[4];
-    const int ch = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
+struct AcceptWs {  // carved out of the caller's workspace
+    RowPart* part;       // [B*k][nsl]
+    float* jsd;          // [B*k][nsl]
+    RowStats* stats;     // [B*k] row maxima and sums, written by the row's first chunk
+    RacePart* race;      // [B][nch]
+    uint32_t* expired;   // [1] set when a bounded wait ran out
+};
+
+__device__ inline void st_agent64(void* p, float lo, float hi) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+                       (unsigned long long)__float_as_uint(lo) | ((unsigned long long)__float_as_uint(hi) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline unsigned long long ld_agent64(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Row maxima and sums S = sum_c s_c 2^(m_c - M) of both rows from the per-wave partials.  Thread t folds
+// slots t, t + 256, ... in increasing order, each wave reduces its share with the fixed tree, and the four
+// wave results are combined in wave order: every workgroup that evaluates a row gets the same bits.
+// WAIT: the partials come from workgroups of the running kernel; each thread polls its slot until both
+// halves are written, or the clock runs out: then false is returned in every thread.  One barrier.
+template <bool WAIT, int T>
+__device__ inline bool row_stats(const RowPart* parts, int nsl, float4* lds, RowStats& r) {
+    constexpr int NW = T / 64;
+    float mp = -INFINITY, mq = -INFINITY, sp = 0.f, sq = 0.f;
+    const int wave = threadIdx.x >> 6;
+    if (WAIT) {  // nsl <= 256: at most one slot per thread
+        RowPart me{-INFINITY, 0.f, -INFINITY, 0.f};
+        if ((int)threadIdx.x < nsl) {
+            const RowPart* src = parts + threadIdx.x;
+            const unsigned long long t0 = wall_clock64();
+            for (;;) {
+                const unsigned long long u0 = ld_agent64(&src->mp), u1 = ld_agent64(&src->mq);
+                if ((uint32_t)u0 != kUnwritten && (uint32_t)u1 != kUnwritten) {
+                    me = RowPart{__uint_as_float((uint32_t)u0), __uint_as_float((uint32_t)(u0 >> 32)),
+                                 __uint_as_float((uint32_t)u1), __uint_as_float((uint32_t)(u1 >> 32))};
+                    break;
+                }
+                if (wall_clock64() - t0 > kWaitTicks) { me.mp = INFINITY; break; }  // +inf marks the expiry
+                __builtin_amdgcn_s_sleep(32);
+            }
+        }
+        if (wave * 64 < nsl) {
+            mp = wave_max_dpp(me.mp);
+            mq = wave_max_dpp(me.mq);
+            sp = wave_sum_dpp(me.sp * fast_exp2(me.mp - mp));
+            sq = wave_sum_dpp(me.sq * fast_exp2(me.mq - mq));
+        }
+    } else {
+        for (int c = threadIdx.x; c < nsl; c += T) { mp = fmaxf(mp, parts[c].mp); mq = fmaxf(mq, parts[c].mq); }
+        mp = wave_max_dpp(mp);
+        mq = wave_max_dpp(mq);
+        for (int c = threadIdx.x; c < nsl; c += T) {
+            const RowPart t = parts[c];
+            sp = sp + t.sp * fast_exp2(t.mp - mp);
+            sq = sq + t.sq * fast_exp2(t.mq - mq);
+        }
+        sp = wave_sum_dpp(sp);
+        sq = wave_sum_dpp(sq);
+    }
+    if ((threadIdx.x & 63) == 0) lds[wave] = make_float4(mp, sp, mq, sq);
+    __syncthreads();
+    r.Mp = -INFINITY; r.Mq = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) { r.Mp = fmaxf(r.Mp, lds[i].x); r.Mq = fmaxf(r.Mq, lds[i].z); }
+    if (WAIT && r.Mp == INFINITY) return false;
+    r.Sp = 0.f; r.Sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const float4 wv = lds[i];
+        r.Sp = r.Sp + wv.y * fast_exp2(wv.x - r.Mp);
+        r.Sq = r.Sq + wv.w * fast_exp2(wv.z - r.Mq);
+    }
+    return true;
+}
+
+__global__ void accept_clear(AcceptWs w, size_t n_parts) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_parts) w.part[i] = RowPart{__uint_as_float(kUnwritten), 0.f, __uint_as_float(kUnwritten), 0.f};
+    if (i == 0) *w.expired = 0u;
+}
+
+enum { SWEEP_ONE_LAUNCH = 0, SWEEP_PARTIALS = 1, SWEEP_DIVERGENCE = 2 };
+
+// kSweepQuads quads of 4 logits per thread and row stay in registers between the two halves (40 registers);
+// the exponentials of the first half are evaluated again in the second, which keeps the kernel at 8 waves
+// per SIMD.  Every wave keeps its own maximum, sum and divergence partial: the only barrier is the one
+// inside row_stats.
+template <int MODE>
+__global__ __launch_bounds__(kAccThreads, 8) void accept_sweep(AcceptShape s, AcceptWs w) {
+    constexpr int T = kAccThreads, QUADS = kSweepQuads, kChunk = kSweepChunk;
+    __shared__ float4 lds[T / 64];
+    // workgroup id = (trial * k + position) * chunks + chunk: the chunks of a row are neighbours in launch
+    // order, and consecutive ids go round the 8 accelerator dies (keeping a row on one die was slower)
+    constexpr int NW = T / 64;
+    const int nsw = s.nsl / NW;
+    const int ch = blockIdx.x % nsw;
+    const int pair = blockIdx.x / nsw;  // trial * k + position
+    const int b = pair / s.k, i = pair - b * s.k;
     const float* prow = s.lp + ((size_t)b * (s.k + 1) + i) * s.V;
-    const bool has_q = i < s.k;
-    const float* qrow = has_q ? s.lq + ((size_t)b * s.k + i) * s.V : prow;
+    const float* qrow = s.lq + (size_t)pair * s.V;
     const bool vec = (s.V & 3) == 0;
-    float a[kQuadsPerThread][4], c[kQuadsPerThread][4];
-    float mp = -INFINITY, mq = -INFINITY;
+    const float c2 = s.inv_temp * kLog2e;  // logit -> base-2 exponent
+    float a[QUADS][4], c[QUADS][4];
+    if (vec && (ch + 1) * kChunk <= s.V) {  // the whole chunk lies inside the row: no per-quad checks
 #pragma unroll
-    for (int j = 0; j < kQuadsPerThread; ++j) {
-        int v = ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j);
-        load4(prow, v, s.V, vec, a[j]);
-        if (has_q) load4(qrow, v, s.V, vec, c[j]);
+        for (int j = 0; j < QUADS; ++j) {
+            const int v = ch * kChunk + 4 * (threadIdx.x + T * j);
+            const f32x4 ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(prow + v));
+            const f32x4 tc = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(qrow + v));
+            a[j][0] = ta.x; a[j][1] = ta.y; a[j][2] = ta.z; a[j][3] = ta.w;
+            c[j][0] = tc.x; c[j][1] = tc.y; c[j][2] = tc.z; c[j][3] = tc.w;
+        }
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            a[j][e] *= s.inv_temp;
-            mp = fmaxf(mp, a[j][e]);
-            if (has_q) { c[j][e] *= s.inv_temp; mq = fmaxf(mq, c[j][e]); }
+        for (int j = 0; j < QUADS; ++j) {
+            const int v = ch * kChunk + 4 * (threadIdx.x + T * j);
+            load4_stream(prow, v, s.V, vec, a[j]);
+            load4_stream(qrow, v, s.V, vec, c[j]);
         }
     }
-    mp = block_max<4>(mp, sm);
-    if (has_q) mq = block_max<4>(mq, sm);
+    float ma = -INFINITY, mc = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < QUADS; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { ma = fmaxf(ma, a[j][e]); mc = fmaxf(mc, c[j][e]); }
+    // masked entries only: a finite floor, so that -inf logits give 2^(-inf) = 0 and not NaN
+    const float mp = fmaxf(wave_max_dpp(ma) * c2, -kBig), mq = fmaxf(wave_max_dpp(mc) * c2, -kBig);
     float sp = 0.f, sq = 0.f;
 #pragma unroll
-    for (int j = 0; j < kQuadsPerThread; ++j)
+    for (int j = 0; j < QUADS; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            sp += expf(a[j][e] - mp);  // exp(-inf) = 0 for padding
-            if (has_q) sq += expf(c[j][e] - mq);
+            sp = sp + fast_exp2(fmaf(a[j][e], c2, -mp));
+            sq = sq + fast_exp2(fmaf(c[j][e], c2, -mq));
         }
-    sp = block_sum<4>(sp, sm);
-    if (has_q) sq = block_sum<4>(sq, sm);
-    if (threadIdx.x == 0) {
-        parts[((size_t)b * (s.k + 1) + i) * s.nch + ch] = LsePart{mp, sp, has_q ? mq : 0.f, has_q ? sq : 1.f};
-        // default for a proposed id outside the vocabulary: probability 0 under the verifier -> rejected
-        if (ch == 0) tokprob[(size_t)b * (s.k + 1) + i] = TokProb{0.f, 1.f};
+    sp = wave_sum_dpp(sp);
+    sq = wave_sum_dpp(sq);
+    const int slot = ch * NW + (threadIdx.x >> 6);
+    RowPart* parts = w.part + (size_t)pair * s.nsl;
+    if (MODE != SWEEP_DIVERGENCE && (threadIdx.x & 63) == 0) {
+        st_agent64(&parts[slot].mp, mp, sp);
+        st_agent64(&parts[slot].mq, mq, sq);
     }
+    if (MODE == SWEEP_PARTIALS) return;
+    RowStats R;
+    if (!row_stats<MODE == SWEEP_ONE_LAUNCH, T>(parts, s.nsl, lds, R)) {
+        // the decision kernel reports the expiry; nothing below is waited for by anyone
+        if (threadIdx.x == 0) __hip_atomic_store(w.expired, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    // p_v = 2^(a_v c2 - lp), q_v = 2^(c_v c2 - lq);  t = log2 q_v - log2 p_v = (c_v - a_v) c2 + dl
+    const float lSp = log2f(R.Sp), lSq = log2f(R.Sq);
+    const float lp = R.Mp + lSp, lq = R.Mq + lSq;   // base-2 log-sum-exp of the rows
+    const float dl = (R.Mp - R.Mq) + (lSp - lSq);
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < QUADS; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float p = fast_exp2(fmaf(a[j][e], c2, -lp));
+            const float q = fast_exp2(fmaf(c[j][e], c2, -lq));
+            // log2(p/m) = 1 - sp2(t), log2(q/m) = 1 - sp2(-t) with m = (p + q) / 2 and
+            // sp2(y) = log2(1 + 2^y) = max(y, 0) + log2(1 + 2^-|y|).
+            // Clamped: masked entries (t = +-inf or inf - inf) then contribute 0 * finite.
+            const float t = __builtin_amdgcn_fmed3f(fmaf(c[j][e] - a[j][e], c2, dl), -kBig, kBig);
+            const float u = 1.f - fast_log2(1.f + fast_exp2(-fabsf(t)));
+            acc = fmaf(p, u - fmaxf(t, 0.f), acc);
+            acc = fmaf(q, u - fmaxf(-t, 0.f), acc);
+        }
+    acc = wave_sum_dpp(acc);
+    if ((threadIdx.x & 63) == 0) w.jsd[(size_t)pair * s.nsl + slot] = (0.5f * kLn2) * acc;
+    if (ch == 0 && threadIdx.x == 0) w.stats[pair] = R;
 }
 
-// log-sum-exp of a row from its chunk partials, summed in chunk order
-__device__ inline void row_lse(const LsePart* parts, int nch, float& lse_p, float& lse_q) {
-    float mp = -INFINITY, mq = -INFINITY;
-    for (int c = 0; c < nch; ++c) { mp = fmaxf(mp, parts[c].mp); mq = fmaxf(mq, parts[c].mq); }
-    float sp = 0.f, sq = 0.f;
-    for (int c = 0; c < nch; ++c) { sp += parts[c].sp * expf(parts[c].mp - mp); sq += parts[c].sq * expf(parts[c].mq - mq); }
-    lse_p = mp + logf(sp);
-    lse_q = mq + logf(sq);
-}
-
-__global__ __launch_bounds__(kAccThreads) void accept_div(AcceptShape s, const LsePart* lse_parts, DivPart* parts,
-                                                          TokProb* tokprob, uint64_t seed, uint32_t position0,
-                                                          uint32_t stage) {
-    __shared__ float sm[4];
-    __shared__ KeyIdx smk[4];
-    __shared__ float s_lse[2];
-    const int ch = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
-    const size_t row_id = (size_t)b * (s.k + 1) + i;
-    const float* prow = s.lp + row_id * s.V;
-    const bool has_q = i < s.k;
-    const float* qrow = has_q ? s.lq + ((size_t)b * s.k + i) * s.V : prow;
-    const bool vec = (s.V & 3) == 0;
-    if (threadIdx.x == 0) {
-        float lp_, lq_;
-        row_lse(lse_parts + row_id * s.nch, s.nch, lp_, lq_);
-        s_lse[0] = lp_; s_lse[1] = lq_;
+// One workgroup of 16 waves per trial: wave r sums the divergence partials of positions r, r + 16 (lane c
+// takes chunks c, c + 64, ... in increasing order, then a fixed tree), thread i tosses the coin of position i.
+__global__ __launch_bounds__(1024) void accept_decide(AcceptShape s, AcceptWs w, float T, uint64_t seed,
+                                                      uint32_t position0, uint32_t stage, AcceptOut* out,
+                                                      float* div_out, int32_t* n_out, int32_t* tok_out) {
+    __shared__ float s_div[PSD_MAX_WIDTH];
+    __shared__ int s_pass[PSD_MAX_WIDTH];
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = wave; i < s.k; i += 16) {
+        const float* pr = w.jsd + ((size_t)b * s.k + i) * s.nsl;
+        float d = 0.f;
+        for (int c = lane; c < s.nsl; c += 64) d = d + pr[c];
+        d = wave_sum_dpp(d);
+        if (lane == 0) s_div[i] = d;
     }
     __syncthreads();
-    const float lse_p = s_lse[0], lse_q = s_lse[1];
+    const int i = threadIdx.x;
+    if (i < s.k) {
+        const float d = s_div[i];
+        if (div_out) div_out[(size_t)b * s.k + i] = d;
+        int pass = 2;  // 2: within the threshold, 1: the coin accepted, 0: rejected
+        if (!(d <= T)) {
+            const uint64_t sd = seed + (uint64_t)b;
+            U4 r = philox4x32_10(U4{0u, position0 + (uint32_t)i, DRAW_COIN, stage}, (uint32_t)sd, (uint32_t)(sd >> 32));
+            // The coin compares p(x) and q(x): accurate exponentials of the natural-log probabilities.
+            // An id outside the vocabulary has probability 0 under the verifier -> rejected.
+            const size_t pair = (size_t)b * s.k + i;
+            const int x = s.tokens[pair];
+            TokProb tp{0.f, 1.f};
+            if (x >= 0 && x < s.V) {
+                const RowStats R = w.stats[pair];
+                const float lse_p = (R.Mp + log2f(R.Sp)) * kLn2, lse_q = (R.Mq + log2f(R.Sq)) * kLn2;
+                const float zp = s.lp[((size_t)b * (s.k + 1) + i) * s.V + x], zq = s.lq[pair * s.V + x];
+                tp = TokProb{expf(fmaxf(zp, -kBig) * s.inv_temp - lse_p), expf(fmaxf(zq, -kBig) * s.inv_temp - lse_q)};
+            }
+            pass = (u01(r.x) * tp.qx < tp.px) ? 1 : 0;  // u < p(x)/q(x)
+        }
+        s_pass[i] = pass;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int n = 0, fuzzy = 0;
+        for (; n < s.k && s_pass[n]; ++n) fuzzy += s_pass[n] == 2;
+        AcceptOut o;
+        o.n_accepted = *w.expired ? -1 : n;  // -1: the sweep's bounded wait expired
+        o.n_fuzzy = fuzzy;
+        o.pad = 0;
+        o.next_token = -1;
+        out[b] = o;
+        if (n_out) { n_out[b] = o.n_accepted; tok_out[b] = -1; }
+    }
+}
+
+// Replacement draw, one row per trial.  First rejected position n < k: race r_v / E_v over the residual
+// r = max(0, p - q) (and p_v / E_v beside it, used when the residual has no mass at all).  n == k and a
+// bonus token is wanted: race over the verifier's last row in log form, z_v / temperature - ln E_v, which
+// needs no normalisation.  E_v = -ln u_v.
+__global__ __launch_bounds__(kAccThreads) void accept_race(AcceptShape s, AcceptWs w, const AcceptOut* out,
+                                                           uint64_t seed, uint32_t position0, uint32_t stage,
+                                                           int take_bonus) {
+    __shared__ KeyIdx smk[4];
+    const int ch = blockIdx.x, b = blockIdx.y;
+    const int n = out[b].n_accepted;
+    if (n < 0 || (n == s.k && !take_bonus)) return;
     const uint64_t sd = seed + (uint64_t)b;
-    const uint32_t pos = position0 + (uint32_t)i;
-    const int x = has_q ? s.tokens[(size_t)b * s.k + i] : -1;
-    float jsd = 0.f;
-    // residual keys are positive; keys of the bonus race are logs and can have any sign
-    KeyIdx best{has_q ? -1.f : -INFINITY, 0x7fffffff}, best_fb{-1.f, 0x7fffffff};
+    const uint32_t pos = position0 + (uint32_t)n;
+    const float* prow = s.lp + ((size_t)b * (s.k + 1) + n) * s.V;
+    const bool vec = (s.V & 3) == 0;
+    KeyIdx best{-INFINITY, 0x7fffffff}, best_fb{-1.f, 0x7fffffff};
+    if (n == s.k) {
 #pragma unroll
-    for (int j = 0; j < kQuadsPerThread; ++j) {
-        const int v = ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j);
-        if (v >= s.V) continue;
-        float a[4], c[4], u[4];
-        load4(prow, v, s.V, vec, a);
-        if (has_q) {
+        for (int j = 0; j < kQuadsPerThread; ++j) {
+            const int v = ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j);
+            if (v >= s.V) continue;
+            float a[4], u[4];
+            load4(prow, v, s.V, vec, a);
+            draw4(sd, (uint32_t)(v >> 2), pos, DRAW_SAMPLE, 0u, u);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (v + e >= s.V) continue;
+                const float E = -kLn2 * fast_log2(u[e]);
+                best = better(best, KeyIdx{fmaf(a[e], s.inv_temp, -kLn2 * fast_log2(E)), v + e});
+            }
+        }
+    } else {
+        const int pair = b * s.k + n;
+        const float* qrow = s.lq + (size_t)pair * s.V;
+        const RowStats R = w.stats[pair];
+        const float c2 = s.inv_temp * kLog2e, ip = 1.f / R.Sp, iq = 1.f / R.Sq;
+        best.key = -1.f;  // residual keys are positive
+#pragma unroll
+        for (int j = 0; j < kQuadsPerThread; ++j) {
+            const int v = ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j);
+            if (v >= s.V) continue;
+            float a[4], c[4], u[4];
+            load4(prow, v, s.V, vec, a);
             load4(qrow, v, s.V, vec, c);
             draw4(sd, (uint32_t)(v >> 2), pos, DRAW_RESAMPLE, stage, u);
-        } else {
-            draw4(sd, (uint32_t)(v >> 2), pos, DRAW_SAMPLE, 0u, u);
-        }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (v + e >= s.V) continue;
-            const float za = a[e] * s.inv_temp - lse_p;  // ln p
-            const float p = expf(za);
-            const float E = -logf(u[e]);
-            if (has_q) {
-                const float zb = c[e] * s.inv_temp - lse_q;  // ln q
-                const float q = expf(zb);
-                // ln(p/m) = ln 2 - softplus(zb - za), ln(q/m) = ln 2 - softplus(za - zb)
-                const float t = zb - za, at = fabsf(t);
-                const float l1 = log1pf(expf(-at));
-                const float sp_pos = at + l1, sp_neg = l1;  // softplus(|t|), softplus(-|t|)
-                const float sp_t = t >= 0.f ? sp_pos : sp_neg, sp_mt = t >= 0.f ? sp_neg : sp_pos;
-                float term = 0.f;
-                if (p > 0.f) term += p * (0.69314718055994531f - sp_t);
-                if (q > 0.f) term += q * (0.69314718055994531f - sp_mt);
-                jsd += 0.5f * term;
+            for (int e = 0; e < 4; ++e) {
+                if (v + e >= s.V) continue;
+                const float p = fast_exp2(fmaf(a[e], c2, -R.Mp)) * ip;  // -inf logits: 2^(-inf) = 0
+                const float q = fast_exp2(fmaf(c[e], c2, -R.Mq)) * iq;
+                const float iE = __builtin_amdgcn_rcpf(-kLn2 * fast_log2(u[e]));
                 const float r = p - q;
-                if (r > 0.f) best = better(best, KeyIdx{r / E, v + e});
-                if (p > 0.f) best_fb = better(best_fb, KeyIdx{p / E, v + e});
-                if (v + e == x) tokprob[row_id] = TokProb{p, q};
-            } else {
-                // bonus row: race on ln p - ln E (same argmax as p / E)
-                best = better(best, KeyIdx{za - logf(E), v + e});
+                if (r > 0.f) best = better(best, KeyIdx{r * iE, v + e});
+                if (p > 0.f) best_fb = better(best_fb, KeyIdx{p * iE, v + e});
             }
         }
     }
-    jsd = block_sum<4>(jsd, sm);
     best = block_best<4>(best, smk);
     best_fb = block_best<4>(best_fb, smk);
-    if (threadIdx.x == 0) parts[row_id * s.nch + ch] = DivPart{jsd, best.key, best.idx, best_fb.key, best_fb.idx, 0, 0, 0};
+    if (threadIdx.x == 0) w.race[(size_t)b * s.nch + ch] = RacePart{best.key, best.idx, best_fb.key, best_fb.idx};
 }
 
-__global__ __launch_bounds__(64) void accept_decide(AcceptShape s, const DivPart* parts, const TokProb* tokprob,
-                                                    float T, uint64_t seed, uint32_t position0, uint32_t stage,
-                                                    int take_bonus, AcceptOut* out, float* div_out) {
-    __shared__ float s_div[PSD_MAX_WIDTH];
-    __shared__ int s_tok[PSD_MAX_WIDTH + 1];
+__global__ __launch_bounds__(kAccThreads) void accept_pick(AcceptShape s, AcceptWs w, int take_bonus, AcceptOut* out,
+                                                           int32_t* tok_out) {
+    __shared__ KeyIdx smk[4];
     const int b = blockIdx.x;
-    const int i = threadIdx.x;
-    if (i <= s.k) {
-        const DivPart* pr = parts + ((size_t)b * (s.k + 1) + i) * s.nch;
-        float d = 0.f;
-        const bool bonus_row = i == s.k;
-        KeyIdx best{bonus_row ? -INFINITY : -1.f, 0x7fffffff}, fb{-1.f, 0x7fffffff};
-        for (int c = 0; c < s.nch; ++c) {
-            d += pr[c].jsd;
-            best = better(best, KeyIdx{pr[c].key, pr[c].idx});
-            fb = better(fb, KeyIdx{pr[c].key_fb, pr[c].idx_fb});
-        }
-        // no residual mass at all (cannot happen in exact arithmetic): draw from p instead
-        if (!bonus_row && !(best.key > 0.f)) best = fb;
-        s_tok[i] = best.idx == 0x7fffffff ? -1 : best.idx;
-        if (i < s.k) {
-            s_div[i] = d;
-            if (div_out) div_out[(size_t)b * s.k + i] = d;
-        }
+    const int n = out[b].n_accepted;
+    if (n < 0 || (n == s.k && !take_bonus)) return;  // next_token stays -1
+    const bool bonus_row = n == s.k;
+    KeyIdx best{bonus_row ? -INFINITY : -1.f, 0x7fffffff}, fb{-1.f, 0x7fffffff};
+    for (int c = threadIdx.x; c < s.nch; c += kAccThreads) {
+        const RacePart r = w.race[(size_t)b * s.nch + c];
+        best = better(best, KeyIdx{r.key, r.idx});
+        fb = better(fb, KeyIdx{r.key_fb, r.idx_fb});
     }
-    __syncthreads();
-    if (i == 0) {
-        const uint64_t sd = seed + (uint64_t)b;
-        int n = 0, fuzzy = 0;
-        for (; n < s.k; ++n) {
-            if (s_div[n] <= T) { ++fuzzy; continue; }
-            U4 r = philox4x32_10(U4{0u, position0 + (uint32_t)n, DRAW_COIN, stage}, (uint32_t)sd, (uint32_t)(sd >> 32));
-            const float u = u01(r.x);
-            const TokProb tp = tokprob[(size_t)b * (s.k + 1) + n];
-            if (u * tp.qx < tp.px) continue;  // u < p(x)/q(x)
-            break;
-        }
-        AcceptOut o;
-        o.n_accepted = n;
-        o.n_fuzzy = fuzzy;
-        o.pad = 0;
-        o.next_token = (n < s.k) ? s_tok[n] : (take_bonus ? s_tok[s.k] : -1);
-        out[b] = o;
+    best = block_best<4>(best, smk);
+    fb = block_best<4>(fb, smk);
+    // no residual mass at all (cannot happen in exact arithmetic): draw from p instead
+    if (!bonus_row && !(best.key > 0.f)) best = fb;
+    if (threadIdx.x == 0) {
+        const int tok = best.idx == 0x7fffffff ? -1 : best.idx;
+        out[b].next_token = tok;
+        if (tok_out) tok_out[b] = tok;
     }
 }
 
 static inline size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
 
-size_t accept_workspace_bytes(int n_trials, int k, int vocab) {
-    size_t rows = (size_t)n_trials * (k + 1), nch = accept_chunks(vocab);
-    return align16(rows * nch * sizeof(LsePart)) + align16(rows * nch * sizeof(DivPart)) + align16(rows * sizeof(TokProb));
+static int sweep_chunks(int vocab) { return (vocab + kSweepChunk - 1) / kSweepChunk; }
+
+static size_t carve(AcceptWs* w, void* base, int n_trials, int k, int vocab) {
+    const size_t pairs = (size_t)n_trials * k;
+    const int nsw_max = kSweepWaves * sweep_chunks(vocab), nch = accept_chunks(vocab);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = (char*)base + off; off += align16(bytes); return (void*)p; };
+    RowPart* part = (RowPart*)take(pairs * nsw_max * sizeof(RowPart));
+    float* jsd = (float*)take(pairs * nsw_max * sizeof(float));
+    RowStats* st = (RowStats*)take(pairs * sizeof(RowStats));
+    RacePart* race = (RacePart*)take((size_t)n_trials * nch * sizeof(RacePart));
+    uint32_t* expired = (uint32_t*)take(sizeof(uint32_t));
+    if (w) *w = AcceptWs{part, jsd, st, race, expired};
+    return off;
 }
+
+size_t accept_workspace_bytes(int n_trials, int k, int vocab) { return carve(nullptr, nullptr, n_trials, k, vocab); }
 
 int accept_launch(const float* logits_p, const float* logits_q, const int32_t* tokens, int n_trials, int k,
                   int vocab, float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
                   int take_bonus, AcceptOut* out, float* div_out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream, char* errbuf) {
+                  hipStream_t stream, char* errbuf, int32_t* n_accepted_out, int32_t* next_token_out) {
     if (!logits_p || (k > 0 && (!logits_q || !tokens)) || !out || !workspace)
         PSD_FAIL(PSD_EINVAL, errbuf, "accept: null pointer");
     if (k < 0 || k > PSD_MAX_WIDTH || vocab < 1 || n_trials < 1 || n_trials > 65535)
@@ -227,16 +462,27 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
                  accept_workspace_bytes(n_trials, k, vocab));
     if (((uintptr_t)workspace & 15) || ((uintptr_t)logits_p & 15) || ((uintptr_t)logits_q & 15))
         PSD_FAIL(PSD_EINVAL, errbuf, "accept: logits and workspace must be 16-byte aligned");
-    const int nch = accept_chunks(vocab);
-    const size_t rows = (size_t)n_trials * (k + 1);
-    LsePart* lse = (LsePart*)workspace;
-    DivPart* dv = (DivPart*)((char*)lse + align16(rows * nch * sizeof(LsePart)));
-    TokProb* tp = (TokProb*)((char*)dv + align16(rows * nch * sizeof(DivPart)));
-    AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature};
-    dim3 grid(nch, k + 1, n_trials);
-    accept_lse<<<grid, kAccThreads, 0, stream>>>(s, lse, tp);
-    accept_div<<<grid, kAccThreads, 0, stream>>>(s, lse, dv, tp, seed, position0, stage);
-    accept_decide<<<n_trials, 64, 0, stream>>>(s, dv, tp, T, seed, position0, stage, take_bonus, out, div_out);
+    const int nch = accept_chunks(vocab), nsw = sweep_chunks(vocab);
+    const int pairs = n_trials * k;
+    if ((long long)pairs * nsw > 0x7fffffffLL) PSD_FAIL(PSD_EINVAL, errbuf, "accept: n_trials * k * chunks overflows the grid");
+    AcceptWs w;
+    carve(&w, workspace, n_trials, k, vocab);
+    AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw};
+    const size_t n_parts = (size_t)pairs * nsw * kSweepWaves;
+    accept_clear<<<(unsigned)((n_parts + 256) / 256), 256, 0, stream>>>(w, n_parts);
+    if (pairs > 0) {
+        const int grid = pairs * nsw;
+        if (g_accept_path != 1 && kSweepWaves * nsw <= kSweepMaxSlots) {
+            accept_sweep<SWEEP_ONE_LAUNCH><<<grid, kAccThreads, 0, stream>>>(s, w);
+        } else {
+            accept_sweep<SWEEP_PARTIALS><<<grid, kAccThreads, 0, stream>>>(s, w);
+            accept_sweep<SWEEP_DIVERGENCE><<<grid, kAccThreads, 0, stream>>>(s, w);
+        }
+    }
+    accept_decide<<<n_trials, 1024, 0, stream>>>(s, w, T, seed, position0, stage, out, div_out, n_accepted_out,
+                                                 next_token_out);
+    accept_race<<<dim3(nch, n_trials), kAccThreads, 0, stream>>>(s, w, out, seed, position0, stage, take_bonus);
+    accept_pick<<<n_trials, kAccThreads, 0, stream>>>(s, w, take_bonus, out, next_token_out);
     PSD_HIP(hipGetLastError(), errbuf);
     return PSD_OK;
 }
@@ -298,14 +544,15 @@ int sample_launch(const float* logits, int n_rows, int vocab, float temperature,
 // ---- C ABI --------------------------------------------------------------------------------------
 using namespace psd;
 
+extern "C" int psd_set_accept_path(int32_t path) {
+    if (path < 0 || path > 2) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_accept_path: path=%d", path);
+    g_accept_path = path;
+    return PSD_OK;
+}
+
 extern "C" size_t psd_accept_workspace_bytes(int32_t n_trials, int32_t k, int32_t vocab) {
     if (n_trials < 1 || k < 0 || vocab < 1) return 0;
     return accept_workspace_bytes(n_trials, k, vocab) + align16((size_t)n_trials * sizeof(AcceptOut));
-}
-
-__global__ void unpack_accept(const AcceptOut* o, int n, int32_t* n_accepted, int32_t* next_token) {
-    int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < n) { n_accepted[b] = o[b].n_accepted; next_token[b] = o[b].next_token; }
 }
 
 extern "C" int psd_accept_batch(const float* logits_p, const float* logits_q, const int32_t* tokens,
@@ -324,9 +571,6 @@ extern "C" int psd_accept_batch(const float* logits_p, const float* logits_q, co
     AcceptOut* out = (AcceptOut*)((char*)workspace + inner);
     hipStream_t st = (hipStream_t)stream;
     int rc = accept_launch(logits_p, logits_q, tokens, n_trials, k, vocab, T, temperature, seed, position0, stage,
-                           take_bonus, out, div_out, workspace, inner, st, err);
-    if (rc != PSD_OK) return rc;
-    unpack_accept<<<(n_trials + 255) / 256, 256, 0, st>>>(out, n_trials, n_accepted, next_token);
-    PSD_HIP(hipGetLastError(), err);
-    return PSD_OK;
+                           take_bonus, out, div_out, workspace, inner, st, err, n_accepted, next_token);
+    return rc;
 }

@@ -82,9 +82,10 @@ extern "C" int psd_accept(const float* logits_p, const float* logits_q, const in
                               dv, ws.p, ws_bytes, nullptr);
     if (rc != PSD_OK) return rc;
     PSD_HIP(hipDeviceSynchronize(), err);
+    int32_t h[2];
+    PSD_HIP(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost), err);
+    if (h[0] < 0) PSD_FAIL(PSD_EHIP, err, "psd_accept: the kernels' bounded wait for each other expired");
     if (where == 0) {
-        int32_t h[2];
-        PSD_HIP(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost), err);
         *n_accepted = h[0];
         *next_token = h[1];
         if (div_out && k > 0) PSD_HIP(hipMemcpy(div_out, dv, k * sizeof(float), hipMemcpyDeviceToHost), err);

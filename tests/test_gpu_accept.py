@@ -135,3 +135,54 @@ def test_accept_histogram_matches_oracle_on_batched_trials():
     assert ties <= 1
     if ties == 0:
         assert np.array_equal(hist_g, hist_o)
+
+
+def _batched(P, Q, X, T, temp, seed, pos0, stage, bonus):
+    B, k, V = len(P), Q[0].shape[0], P[0].shape[1]
+    dp = psd.DeviceBuffer.from_numpy(np.stack(P)); dq = psd.DeviceBuffer.from_numpy(np.stack(Q))
+    dx = psd.DeviceBuffer.from_numpy(np.stack(X))
+    na = psd.DeviceBuffer(4 * B); nt = psd.DeviceBuffer(4 * B); dv = psd.DeviceBuffer(4 * B * k)
+    wsb = psd.accept_workspace_bytes(B, k, V)
+    ws = psd.DeviceBuffer(wsb)
+    psd.accept_batch(dp, dq, dx, B, k, V, T, temp, seed, pos0, stage, bonus, na, nt, dv, ws, wsb, None)
+    psd.dev_sync()
+    return na.to_numpy(np.int32, B), nt.to_numpy(np.int32, B), dv.to_numpy(np.float32, (B, k))
+
+
+@pytest.mark.parametrize("V,k,B", [(128256, 4, 6), (4099, 7, 40), (300, 32, 5), (2048, 1, 3), (2049, 2, 3)])
+def test_one_launch_and_two_launch_sweeps_agree_bit_for_bit(V, k, B):
+    rng = np.random.default_rng(V + k)
+    P = [rng.normal(0, 3, (k + 1, V)).astype(np.float32) for _ in range(B)]
+    Q = [(0.9 * p[:k] + 0.44 * rng.normal(0, 3, (k, V))).astype(np.float32) for p in P]
+    X = [rng.integers(0, V, k).astype(np.int32) for _ in range(B)]
+    try:
+        psd.set_accept_path(1)
+        two = _batched(P, Q, X, 0.15, 0.9, 3, 17, 1, True)
+        psd.set_accept_path(0)
+        one = _batched(P, Q, X, 0.15, 0.9, 3, 17, 1, True)
+    finally:
+        psd.set_accept_path(0)
+    assert np.array_equal(one[0], two[0]) and np.array_equal(one[1], two[1])
+    assert np.array_equal(one[2].view(np.uint32), two[2].view(np.uint32))
+    assert (one[0] >= 0).all()
+    # and both are the oracle's answer
+    for b in range(min(B, 4)):
+        res, odiv = oracle.accept(P[b], Q[b], X[b], 0.15, 0.9, 3 + b, 17, 1, True)
+        assert np.abs(one[2][b] - odiv).max() <= DIV_TOL
+        if one[0][b] != res.n_accepted or one[1][b] != res.next_token:
+            assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN or res.margin_race < TIE_RACE
+
+
+def test_accept_masked_entries():
+    """-inf logits carry probability zero, in one row or in both."""
+    rng = np.random.default_rng(9)
+    V, k = 5000, 3
+    lp = rng.normal(0, 2, (k + 1, V)).astype(np.float32)
+    lq = (0.8 * lp[:k] + 0.6 * rng.normal(0, 2, (k, V))).astype(np.float32)
+    lp[:, 100:2300] = -np.inf
+    lq[:, 1500:3000] = -np.inf
+    lp[:, V - 3:] = -np.inf
+    lq[:, V - 3:] = -np.inf
+    for x in ([50, 3500, 4000], [200, 2500, 4999]):
+        for T in (0.0, 0.3, 1.0):
+            _compare(lp, lq, np.array(x, np.int32), T, 1.0, 4, 7, 2, True)
