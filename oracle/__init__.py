@@ -73,6 +73,13 @@ def lib():
         L.orc_generate.restype = C.c_int
         L.orc_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.c_void_p, C.c_int,
                                    C.c_int, C.c_uint64, C.c_void_p, C.POINTER(Stats)]
+        L.orc_accept_assisted.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_uint64, C.c_uint32,
+                                          C.c_uint32, C.c_int, C.c_void_p]
+        L.orc_generate_assisted.restype = C.c_int
+        L.orc_generate_assisted.argtypes = L.orc_generate.argtypes
+        L.orc_generate_sd.restype = C.c_int
+        L.orc_generate_sd.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_double, C.c_double, C.c_void_p, C.c_int,
+                                      C.c_int, C.c_uint64, C.c_void_p, C.c_void_p]
         L.orc_generate_plain.restype = C.c_int
         L.orc_generate_plain.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_int, C.c_int, C.c_uint64,
                                          C.c_void_p]
@@ -142,6 +149,18 @@ def accept(logits_p, logits_q, x, T, temperature=1.0, seed=0, position0=0, stage
     return res, div[:k]
 
 
+def accept_assisted(logits_p, x, temperature=1.0, seed=0, position0=0, stage=1, take_bonus=True):
+    """Assisted stage (Section 3.4): strict token match against the verifier's argmax, fallback draw from the verifier."""
+    lp = np.ascontiguousarray(logits_p, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    k, V = lp.shape[0] - 1, lp.shape[1]
+    assert x.size == k
+    res = AcceptResult()
+    lib().orc_accept_assisted(lp.ctypes.data, x.ctypes.data, k, V, temperature, seed, position0, stage,
+                              int(take_bonus), C.byref(res))
+    return res
+
+
 def sample_row(logits, temperature, seed, position, purpose=DRAW_SAMPLE, stage=0):
     lg = np.ascontiguousarray(logits, dtype=np.float32)
     gap = C.c_double(0)
@@ -189,6 +208,30 @@ def generate(D, Q, T, prompt, n_new, seed, k1, k2, T_q, T_t, temperature=1.0):
                             C.byref(st))
     if rc != 0:
         raise ValueError(f"orc_generate failed: {rc}")
+    return out, st.as_dict()
+
+
+def generate_assisted(D, Q, T, prompt, n_new, seed, k1, k2, T_t, temperature=1.0):
+    prm = Params(0.0, T_t, temperature, k1, k2)
+    pr = np.ascontiguousarray(prompt, dtype=np.int32)
+    out = np.empty(n_new, dtype=np.int32)
+    st = Stats()
+    rc = lib().orc_generate_assisted(D.h, Q.h, T.h, C.byref(prm), pr.ctypes.data, pr.size, n_new, seed,
+                                     out.ctypes.data, C.byref(st))
+    if rc != 0:
+        raise ValueError(f"orc_generate_assisted failed: {rc}")
+    return out, st.as_dict()
+
+
+def generate_sd(P, T, prompt, n_new, seed, k, tau, temperature=1.0):
+    """Two-model speculative decoding: P proposes k tokens, T verifies with threshold tau (0 = standard SD)."""
+    pr = np.ascontiguousarray(prompt, dtype=np.int32)
+    out = np.empty(n_new, dtype=np.int32)
+    st = Stats()
+    rc = lib().orc_generate_sd(P.h, T.h, k, tau, temperature, pr.ctypes.data, pr.size, n_new, seed, out.ctypes.data,
+                               C.byref(st))
+    if rc != 0:
+        raise ValueError(f"orc_generate_sd failed: {rc}")
     return out, st.as_dict()
 
 

@@ -205,6 +205,36 @@ void orc_accept(const float* logits_p, const float* logits_q, const int32_t* x, 
     free(p); free(q); free(u);
 }
 
+int orc_sample_row(const float* logits, int V, double temperature, uint64_t seed, uint32_t position,
+                   uint32_t purpose, uint32_t stage, double* gap);
+
+/* Assisted stage (Section 3.4; strict matching as described in Sections 3.1-3.2):
+ * proposal i is accepted iff it equals the verifier's top prediction
+ * argmax_v logits_p[i][v] (lowest index among equal maxima); no threshold, no
+ * coin.  At the first mismatch n the replacement token is drawn from the
+ * verifier's own distribution softmax(logits_p[n] / temperature), not from a
+ * residual; a fully accepted run takes the bonus token from row k as in the
+ * fuzzy stage.  The draws are addressed like those of orc_accept. */
+void orc_accept_assisted(const float* logits_p, const int32_t* x, int k, int V, double temperature, uint64_t seed,
+                         uint32_t position0, uint32_t stage, int take_bonus, orc_accept_result* res) {
+    res->margin_div = INFINITY; res->margin_coin = INFINITY; res->margin_race = 1.0;
+    res->n_fuzzy = 0; res->pad = 0; res->next_token = -1;
+    int n = 0;
+    for (; n < k; ++n) {
+        const float* row = logits_p + (size_t)n * V;
+        int top = 0;
+        for (int v = 1; v < V; ++v) if (row[v] > row[top]) top = v;
+        if (x[n] != top) break;
+    }
+    res->n_accepted = n;
+    if (n < k)
+        res->next_token = orc_sample_row(logits_p + (size_t)n * V, V, temperature, seed, position0 + (uint32_t)n,
+                                         ORC_DRAW_RESAMPLE, stage, &res->margin_race);
+    else if (take_bonus)
+        res->next_token = orc_sample_row(logits_p + (size_t)k * V, V, temperature, seed, position0 + (uint32_t)k,
+                                         ORC_DRAW_SAMPLE, 0u, &res->margin_race);
+}
+
 /* Draft proposal: token ~ softmax(logits / temperature) by the race. */
 int orc_sample_row(const float* logits, int V, double temperature, uint64_t seed, uint32_t position,
                    uint32_t purpose, uint32_t stage, double* gap) {
@@ -427,8 +457,9 @@ static int run_model(orc_model* m, const int32_t* seq, int* len, int upto, int n
  *     replacement / bonus token is committed.
  *   After each ACCEPT every cache is cut back to the tokens that survived.
  */
-int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
-                 int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
+static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, int assisted,
+                         const int32_t* prompt, int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens,
+                         orc_stats* st) {
     int V = T->vocab, k1 = prm->k1, k2 = prm->k2;
     if (D->vocab != V || Q->vocab != V || k1 < 1 || k2 < 1 || n_prompt < 1 || n_new < 0) return -1;
     int cap = n_prompt + n_new + k2 + 2;
@@ -461,7 +492,10 @@ int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm
             rc |= run_model(Q, seq, &lenQ, L + m, m + 1, ql);
             st->passes_q++;
             int bonus = nbuf + m < k2;
-            orc_accept(ql, dl, seq + L, m, V, prm->T_q, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar, NULL);
+            if (assisted)
+                orc_accept_assisted(ql, seq + L, m, V, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar);
+            else
+                orc_accept(ql, dl, seq + L, m, V, prm->T_q, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar, NULL);
             int n = ar.n_accepted, has_y = ar.next_token >= 0;
             memcpy(qrows + (size_t)nbuf * V, ql, (size_t)(n + has_y) * V * sizeof(float));
             if (has_y) seq[L + n] = ar.next_token;
@@ -481,6 +515,65 @@ int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm
     }
     if (rc == 0) memcpy(out_tokens, seq + n_prompt, (size_t)n_new * sizeof(int32_t));
     free(seq); free(dl); free(ql); free(qrows); free(tl);
+    return rc;
+}
+
+int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
+                 int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
+    return generate_loop(D, Q, T, prm, 0, prompt, n_prompt, n_new, seed, out_tokens, st);
+}
+
+/* The assisted variant of the loop (Section 3.4): the qualifier stage matches tokens
+ * strictly and falls back to the qualifier's own distribution; tau_Q is unused.  The
+ * target stage is unchanged. */
+int orc_generate_assisted(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
+                          int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
+    return generate_loop(D, Q, T, prm, 1, prompt, n_prompt, n_new, seed, out_tokens, st);
+}
+
+/* Two-model speculative decoding, the comparison the speed-up is quoted against
+ * (Section 3.3, first equation, and its fuzzy extension): model P proposes k tokens one
+ * at a time, the target scores them in one pass, ACCEPT with threshold tau (tau = 0:
+ * standard speculative sampling; tau > 0: fuzzy speculative decoding), the accepted
+ * prefix plus the replacement / bonus token is committed.  Draw addressing is that of
+ * the three-model loop's target stage (stage 2), so a three-model run whose qualifier
+ * stage accepts everything and whose draft equals its qualifier gives the same tokens.
+ * passes_d counts the proposer's steps. */
+int orc_generate_sd(orc_model* P, orc_model* T, int k, double tau, double temperature, const int32_t* prompt,
+                    int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
+    int V = T->vocab;
+    if (P->vocab != V || k < 1 || n_prompt < 1 || n_new < 0) return -1;
+    int cap = n_prompt + n_new + k + 2;
+    if (cap > P->max_seq || cap > T->max_seq) return -3;
+    int32_t* seq = (int32_t*)malloc((size_t)cap * sizeof(int32_t));
+    float* pl = (float*)malloc((size_t)k * V * sizeof(float));
+    float* tl = (float*)malloc((size_t)(k + 1) * V * sizeof(float));
+    memcpy(seq, prompt, (size_t)n_prompt * sizeof(int32_t));
+    memset(st, 0, sizeof(*st));
+    int C = n_prompt, lenP = 0, lenT = 0, rc = 0;
+    if (C > 1) {
+        rc |= run_model(P, seq, &lenP, C - 1, 0, NULL);
+        rc |= run_model(T, seq, &lenT, C - 1, 0, NULL);
+    }
+    orc_accept_result ar;
+    while (rc == 0 && C - n_prompt < n_new) {
+        for (int i = 0; i < k; ++i) {
+            rc |= run_model(P, seq, &lenP, C + i, 1, pl + (size_t)i * V);
+            st->passes_d++;
+            seq[C + i] = orc_sample_row(pl + (size_t)i * V, V, temperature, seed, (uint32_t)(C + i), ORC_DRAW_SAMPLE,
+                                        0u, NULL);
+        }
+        rc |= run_model(T, seq, &lenT, C + k, k + 1, tl);
+        st->passes_t++;
+        orc_accept(tl, pl, seq + C, k, V, tau, temperature, seed, (uint32_t)C, 2u, 1, &ar, NULL);
+        int n = ar.n_accepted;
+        seq[C + n] = ar.next_token;
+        lenT = imin(lenT, C + n); lenP = imin(lenP, C + n);
+        C += n + 1;
+        st->proposed_t += k; st->accepted_t += n; st->fuzzy_t += ar.n_fuzzy;
+    }
+    if (rc == 0) memcpy(out_tokens, seq + n_prompt, (size_t)n_new * sizeof(int32_t));
+    free(seq); free(pl); free(tl);
     return rc;
 }
 
