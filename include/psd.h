@@ -88,6 +88,9 @@ typedef struct {
 enum {
     PSD_FLAG_GRAPH = 1,             /* replay captured hipGraphs for the decoding loop's passes instead of
                                        launching kernel by kernel */
+    PSD_FLAG_ASSISTED = 2,          /* qualifier stage of psd_generate as in Section 3.4: a draft token passes iff it is
+                                       the qualifier's top prediction, a rejected one is replaced by a sample of the
+                                       qualifier's own distribution; T_q is unused */
     PSD_FLAG_SCRAMBLE_PAGES = 0x100 /* test aid: hand out physical KV pages in a shuffled order */
 };
 
@@ -140,6 +143,20 @@ int psd_set_decoding(psd_ctx* ctx, float T_q, float T_t, int32_t k1, int32_t k2,
 int psd_generate(psd_ctx* ctx, const int32_t* prompt, int32_t n_prompt, int32_t n_new, uint64_t seed,
                  int32_t* out_tokens, psd_stats* out_stats);
 
+/* Two-model speculative decoding through the same scheduler, the comparison the paper's speed-up is quoted
+ * against (Section 3.3, first equation): model `proposer` (0 draft, 1 qualifier) proposes k tokens one step at a
+ * time, the target verifies them in one pass with threshold tau (0: standard speculative sampling; > 0: fuzzy
+ * speculative decoding), the accepted prefix plus the replacement or bonus token is committed.  Random draws
+ * are addressed as in the target stage of psd_generate.  1 <= k <= the k2 the context was created with.
+ * Stats: proposed_t / accepted_t / fuzzy_t, passes_t, and the proposer's steps in passes_d or passes_q.
+ * Errors: PSD_EINVAL, PSD_ESHAPE (n_prompt + n_new + k + 2 > max_seq), PSD_EHIP. */
+int psd_generate_sd(psd_ctx* ctx, int32_t proposer, int32_t k, float tau, const int32_t* prompt, int32_t n_prompt,
+                    int32_t n_new, uint64_t seed, int32_t* out_tokens, psd_stats* out_stats);
+
+/* Switches the qualifier stage of psd_generate between the fuzzy rule (0) and the assisted rule of
+ * Section 3.4 (1), as PSD_FLAG_ASSISTED does at creation. */
+int psd_set_assisted(psd_ctx* ctx, int32_t on);
+
 /* Plain autoregressive sampling from one model (0 draft, 1 qualifier, 2 target)
  * with the same fresh-sample draws: the no-speculation baseline. */
 int psd_generate_plain(psd_ctx* ctx, int32_t which, const int32_t* prompt, int32_t n_prompt, int32_t n_new,
@@ -165,6 +182,14 @@ int psd_forward(psd_ctx* ctx, int32_t which, const int32_t* tokens, int32_t w, i
 int psd_accept(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k, int32_t vocab,
                float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage, int32_t take_bonus,
                int32_t where, int32_t* n_accepted, int32_t* next_token, float* div_out);
+
+/* ACCEPT of the assisted stage (Section 3.4) on its own: proposal i passes iff tokens[i] is the top
+ * prediction of verifier row i (lowest index among equal maxima); at the first mismatch n the replacement is
+ * drawn from softmax(logits_p[n] / temperature); a fully accepted run takes the bonus token from row k.
+ * Arguments as for psd_accept (no proposer rows, no threshold, no divergences). */
+int psd_accept_assisted(const float* logits_p, const int32_t* tokens, int32_t k, int32_t vocab, float temperature,
+                        uint64_t seed, uint32_t position0, uint32_t stage, int32_t take_bonus, int32_t where,
+                        int32_t* n_accepted, int32_t* next_token);
 
 /* Batched ACCEPT for throughput measurement: n_trials independent stages of equal k in one launch
  * sequence.  All pointers are DEVICE memory; trial b uses seed + b.
@@ -197,7 +222,7 @@ int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float tempera
 
 /* Trace hook for tests: when set, psd_generate copies the inputs of every draft
  * sample (kind 0, k = 0, logits_p = the draft row) and every ACCEPT (kind 1 / 2 =
- * stage) back to the host and calls fn after the step has been decided.  All
+ * stage; kind 3 = stage 1 under the assisted rule) back to the host and calls fn after the step has been decided.  All
  * pointers are host memory valid during the callback only.  Slow; tests only. */
 typedef void (*psd_trace_fn)(void* user, int32_t kind, uint32_t position0, int32_t k, int32_t take_bonus,
                              const float* logits_p, const float* logits_q, const int32_t* tokens,

@@ -10,6 +10,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 F32, BF16 = 0, 1
 FLAG_GRAPH = 1
+FLAG_ASSISTED = 2
 MAX_WIDTH = 32
 
 
@@ -91,6 +92,11 @@ def lib():
                                    C.POINTER(Stats)]
         L.psd_generate_plain.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
                                          C.c_void_p, C.POINTER(Stats)]
+        L.psd_generate_sd.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_int32, C.c_int32,
+                                      C.c_uint64, C.c_void_p, C.POINTER(Stats)]
+        L.psd_set_assisted.argtypes = [C.c_void_p, C.c_int32]
+        L.psd_accept_assisted.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
+                                          C.c_uint32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.psd_forward.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.psd_set_trace.argtypes = [C.c_void_p, TRACE_FN, C.c_void_p]
         L.psd_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -174,6 +180,18 @@ def accept(logits_p, logits_q, tokens, T, temperature=1.0, seed=0, position0=0, 
     return n.value, t.value, div[:k]
 
 
+def accept_assisted(logits_p, tokens, temperature=1.0, seed=0, position0=0, stage=1, take_bonus=True):
+    """psd_accept_assisted on host numpy arrays.  Returns (n_accepted, next_token)."""
+    lp = np.ascontiguousarray(logits_p, dtype=np.float32)
+    tk = np.ascontiguousarray(tokens, dtype=np.int32)
+    k, V = tk.size, lp.shape[-1]
+    n = C.c_int32(0)
+    t = C.c_int32(0)
+    _check(lib().psd_accept_assisted(lp.ctypes.data, tk.ctypes.data if k else None, k, V, temperature, seed, position0,
+                                     stage, int(take_bonus), 0, C.byref(n), C.byref(t)))
+    return n.value, t.value
+
+
 def set_accept_path(path):
     _check(lib().psd_set_accept_path(path))
 
@@ -254,6 +272,18 @@ class Context:
         st = Stats()
         _check(lib().psd_generate(self._h, pr.ctypes.data, pr.size, n_new, seed, out.ctypes.data, C.byref(st)), self._h)
         return out, st.as_dict()
+
+    def generate_sd(self, proposer, k, tau, prompt, n_new, seed):
+        """Two-model speculative decoding: model `proposer` (0 draft, 1 qualifier) -> target, threshold tau."""
+        pr = np.ascontiguousarray(prompt, dtype=np.int32)
+        out = np.empty(n_new, dtype=np.int32)
+        st = Stats()
+        _check(lib().psd_generate_sd(self._h, proposer, k, tau, pr.ctypes.data, pr.size, n_new, seed, out.ctypes.data,
+                                     C.byref(st)), self._h)
+        return out, st.as_dict()
+
+    def set_assisted(self, on: bool):
+        _check(lib().psd_set_assisted(self._h, int(on)), self._h)
 
     def generate_plain(self, which, prompt, n_new, seed):
         pr = np.ascontiguousarray(prompt, dtype=np.int32)

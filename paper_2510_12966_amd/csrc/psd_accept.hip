@@ -19,6 +19,9 @@
 // partial has its own slot, reductions run in a fixed order, so results never depend on scheduling.
 // When a row has more chunks than may safely wait on each other, the sweep runs as two launches
 // (partials, then divergence) with the same arithmetic.
+// The assisted stage (Section 3.4) needs no softmax at all: accept_top finds the verifier's top prediction
+// per position, accept_decide_assisted compares tokens, and the replacement draw races over the verifier's
+// own row in log form.
 #include "psd_device.h"
 #include "psd_host.h"
 
@@ -118,6 +121,7 @@ struct AcceptWs {  // carved out of the caller's workspace
     float* jsd;          // [B*k][nsl]
     RowStats* stats;     // [B*k] row maxima and sums, written by the row's first chunk
     RacePart* race;      // [B][nch]
+    KeyIdx* top;         // [B*k][nch] per-chunk maximum logit of the verifier rows (assisted stage)
     uint32_t* expired;   // [1] set when a bounded wait ran out
 };
 
@@ -342,13 +346,59 @@ __global__ __launch_bounds__(1024) void accept_decide(AcceptShape s, AcceptWs w,
     }
 }
 
+// ---- assisted stage: strict match against the verifier's top prediction ---------------------------------
+__global__ __launch_bounds__(kAccThreads) void accept_top(AcceptShape s, AcceptWs w) {
+    __shared__ KeyIdx smk[4];
+    const int ch = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
+    const float* prow = s.lp + ((size_t)b * (s.k + 1) + i) * s.V;
+    const bool vec = (s.V & 3) == 0;
+    KeyIdx best{-INFINITY, 0x7fffffff};
+#pragma unroll
+    for (int j = 0; j < kQuadsPerThread; ++j) {
+        const int v = ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j);
+        if (v >= s.V) continue;
+        float a[4];
+        load4(prow, v, s.V, vec, a);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (v + e < s.V) best = better(best, KeyIdx{a[e], v + e});  // equal maxima: lowest index
+    }
+    best = block_best<4>(best, smk);
+    if (threadIdx.x == 0) w.top[((size_t)b * s.k + i) * s.nch + ch] = best;
+}
+
+// one workgroup of 16 waves per trial: wave r reduces the chunk maxima of positions r, r + 16
+__global__ __launch_bounds__(1024) void accept_decide_assisted(AcceptShape s, AcceptWs w, AcceptOut* out, float* div_out,
+                                                               int32_t* n_out, int32_t* tok_out) {
+    __shared__ int s_pass[PSD_MAX_WIDTH];
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = wave; i < s.k; i += 16) {
+        const KeyIdx* pr = w.top + ((size_t)b * s.k + i) * s.nch;
+        KeyIdx best{-INFINITY, 0x7fffffff};
+        for (int c = lane; c < s.nch; c += 64) best = better(best, pr[c]);
+        best = wave_best(best);
+        if (lane == 0) {
+            s_pass[i] = s.tokens[(size_t)b * s.k + i] == best.idx;
+            if (div_out) div_out[(size_t)b * s.k + i] = -1.f;  // no divergence is evaluated in this stage
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int n = 0;
+        while (n < s.k && s_pass[n]) ++n;
+        out[b] = AcceptOut{n, -1, 0, 0};
+        if (n_out) { n_out[b] = n; tok_out[b] = -1; }
+    }
+}
+
 // Replacement draw, one row per trial.  First rejected position n < k: race r_v / E_v over the residual
 // r = max(0, p - q) (and p_v / E_v beside it, used when the residual has no mass at all).  n == k and a
 // bonus token is wanted: race over the verifier's last row in log form, z_v / temperature - ln E_v, which
-// needs no normalisation.  E_v = -ln u_v.
+// needs no normalisation.  E_v = -ln u_v.  Assisted stage: the draw at a rejection is from the verifier's
+// row itself, in the same log form but with the replacement stream's random numbers.
 __global__ __launch_bounds__(kAccThreads) void accept_race(AcceptShape s, AcceptWs w, const AcceptOut* out,
                                                            uint64_t seed, uint32_t position0, uint32_t stage,
-                                                           int take_bonus) {
+                                                           int take_bonus, int assisted) {
     __shared__ KeyIdx smk[4];
     const int ch = blockIdx.x, b = blockIdx.y;
     const int n = out[b].n_accepted;
@@ -358,14 +408,15 @@ __global__ __launch_bounds__(kAccThreads) void accept_race(AcceptShape s, Accept
     const float* prow = s.lp + ((size_t)b * (s.k + 1) + n) * s.V;
     const bool vec = (s.V & 3) == 0;
     KeyIdx best{-INFINITY, 0x7fffffff}, best_fb{-1.f, 0x7fffffff};
-    if (n == s.k) {
+    if (n == s.k || assisted) {
+        const uint32_t purpose = n == s.k ? (uint32_t)DRAW_SAMPLE : (uint32_t)DRAW_RESAMPLE, stg = n == s.k ? 0u : stage;
 #pragma unroll
         for (int j = 0; j < kQuadsPerThread; ++j) {
             const int v = ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j);
             if (v >= s.V) continue;
             float a[4], u[4];
             load4(prow, v, s.V, vec, a);
-            draw4(sd, (uint32_t)(v >> 2), pos, DRAW_SAMPLE, 0u, u);
+            draw4(sd, (uint32_t)(v >> 2), pos, purpose, stg, u);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (v + e >= s.V) continue;
@@ -404,13 +455,13 @@ __global__ __launch_bounds__(kAccThreads) void accept_race(AcceptShape s, Accept
     if (threadIdx.x == 0) w.race[(size_t)b * s.nch + ch] = RacePart{best.key, best.idx, best_fb.key, best_fb.idx};
 }
 
-__global__ __launch_bounds__(kAccThreads) void accept_pick(AcceptShape s, AcceptWs w, int take_bonus, AcceptOut* out,
-                                                           int32_t* tok_out) {
+__global__ __launch_bounds__(kAccThreads) void accept_pick(AcceptShape s, AcceptWs w, int take_bonus, int assisted,
+                                                           AcceptOut* out, int32_t* tok_out) {
     __shared__ KeyIdx smk[4];
     const int b = blockIdx.x;
     const int n = out[b].n_accepted;
     if (n < 0 || (n == s.k && !take_bonus)) return;  // next_token stays -1
-    const bool bonus_row = n == s.k;
+    const bool bonus_row = n == s.k || assisted;  // keys in log form: any sign, and never without mass
     KeyIdx best{bonus_row ? -INFINITY : -1.f, 0x7fffffff}, fb{-1.f, 0x7fffffff};
     for (int c = threadIdx.x; c < s.nch; c += kAccThreads) {
         const RacePart r = w.race[(size_t)b * s.nch + c];
@@ -441,8 +492,9 @@ static size_t carve(AcceptWs* w, void* base, int n_trials, int k, int vocab) {
     float* jsd = (float*)take(pairs * nsw_max * sizeof(float));
     RowStats* st = (RowStats*)take(pairs * sizeof(RowStats));
     RacePart* race = (RacePart*)take((size_t)n_trials * nch * sizeof(RacePart));
+    KeyIdx* top = (KeyIdx*)take(pairs * nch * sizeof(KeyIdx));
     uint32_t* expired = (uint32_t*)take(sizeof(uint32_t));
-    if (w) *w = AcceptWs{part, jsd, st, race, expired};
+    if (w) *w = AcceptWs{part, jsd, st, race, top, expired};
     return off;
 }
 
@@ -451,8 +503,8 @@ size_t accept_workspace_bytes(int n_trials, int k, int vocab) { return carve(nul
 int accept_launch(const float* logits_p, const float* logits_q, const int32_t* tokens, int n_trials, int k,
                   int vocab, float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
                   int take_bonus, AcceptOut* out, float* div_out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream, char* errbuf, int32_t* n_accepted_out, int32_t* next_token_out) {
-    if (!logits_p || (k > 0 && (!logits_q || !tokens)) || !out || !workspace)
+                  hipStream_t stream, char* errbuf, int32_t* n_accepted_out, int32_t* next_token_out, int assisted) {
+    if (!logits_p || (k > 0 && ((!logits_q && !assisted) || !tokens)) || !out || !workspace)
         PSD_FAIL(PSD_EINVAL, errbuf, "accept: null pointer");
     if (k < 0 || k > PSD_MAX_WIDTH || vocab < 1 || n_trials < 1 || n_trials > 65535)
         PSD_FAIL(PSD_EINVAL, errbuf, "accept: k=%d vocab=%d n_trials=%d out of range", k, vocab, n_trials);
@@ -469,6 +521,14 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     carve(&w, workspace, n_trials, k, vocab);
     AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw};
     const size_t n_parts = (size_t)pairs * nsw * kSweepWaves;
+    if (assisted) {
+        if (pairs > 0) accept_top<<<dim3(nch, k, n_trials), kAccThreads, 0, stream>>>(s, w);
+        accept_decide_assisted<<<n_trials, 1024, 0, stream>>>(s, w, out, div_out, n_accepted_out, next_token_out);
+        accept_race<<<dim3(nch, n_trials), kAccThreads, 0, stream>>>(s, w, out, seed, position0, stage, take_bonus, 1);
+        accept_pick<<<n_trials, kAccThreads, 0, stream>>>(s, w, take_bonus, 1, out, next_token_out);
+        PSD_HIP(hipGetLastError(), errbuf);
+        return PSD_OK;
+    }
     accept_clear<<<(unsigned)((n_parts + 256) / 256), 256, 0, stream>>>(w, n_parts);
     if (pairs > 0) {
         const int grid = pairs * nsw;
@@ -481,8 +541,8 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     }
     accept_decide<<<n_trials, 1024, 0, stream>>>(s, w, T, seed, position0, stage, out, div_out, n_accepted_out,
                                                  next_token_out);
-    accept_race<<<dim3(nch, n_trials), kAccThreads, 0, stream>>>(s, w, out, seed, position0, stage, take_bonus);
-    accept_pick<<<n_trials, kAccThreads, 0, stream>>>(s, w, take_bonus, out, next_token_out);
+    accept_race<<<dim3(nch, n_trials), kAccThreads, 0, stream>>>(s, w, out, seed, position0, stage, take_bonus, 0);
+    accept_pick<<<n_trials, kAccThreads, 0, stream>>>(s, w, take_bonus, 0, out, next_token_out);
     PSD_HIP(hipGetLastError(), errbuf);
     return PSD_OK;
 }

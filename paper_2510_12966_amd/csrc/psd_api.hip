@@ -39,17 +39,18 @@ extern "C" const char* psd_strerror(int code) {
     }
 }
 
-extern "C" int psd_accept(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k,
-                          int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
-                          uint32_t stage, int32_t take_bonus, int32_t where, int32_t* n_accepted,
-                          int32_t* next_token, float* div_out) {
+// shared body of psd_accept and psd_accept_assisted: stages host inputs on the device when asked to
+static int accept_once(const char* who, const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k,
+                       int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
+                       int32_t take_bonus, int32_t where, int32_t* n_accepted, int32_t* next_token, float* div_out,
+                       int assisted) {
     char* err = tls_error();
-    if (!logits_p || !n_accepted || !next_token || (k > 0 && (!logits_q || !tokens)))
-        PSD_FAIL(PSD_EINVAL, err, "psd_accept: null pointer");
-    if (k < 0 || k > PSD_MAX_WIDTH || vocab < 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: k=%d vocab=%d", k, vocab);
-    if (stage != 1 && stage != 2) PSD_FAIL(PSD_EINVAL, err, "psd_accept: stage must be 1 or 2");
-    if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept: where must be 0 or 1");
-    if (!(T >= 0.f) || !(temperature > 0.f)) PSD_FAIL(PSD_EINVAL, err, "psd_accept: T=%g temperature=%g", T, temperature);
+    if (!logits_p || !n_accepted || !next_token || (k > 0 && ((!logits_q && !assisted) || !tokens)))
+        PSD_FAIL(PSD_EINVAL, err, "%s: null pointer", who);
+    if (k < 0 || k > PSD_MAX_WIDTH || vocab < 1) PSD_FAIL(PSD_EINVAL, err, "%s: k=%d vocab=%d", who, k, vocab);
+    if (stage != 1 && stage != 2) PSD_FAIL(PSD_EINVAL, err, "%s: stage must be 1 or 2", who);
+    if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "%s: where must be 0 or 1", who);
+    if (!(T >= 0.f) || !(temperature > 0.f)) PSD_FAIL(PSD_EINVAL, err, "%s: T=%g temperature=%g", who, T, temperature);
     const size_t ws_bytes = psd_accept_workspace_bytes(1, k, vocab);
     const size_t np = (size_t)(k + 1) * vocab, nq = (size_t)k * vocab;
     DevBuf ws, dp, dq, dt, dres, ddiv;
@@ -63,11 +64,13 @@ extern "C" int psd_accept(const float* logits_p, const float* logits_q, const in
         PSD_HIP(hipMemcpy(dp.p, logits_p, np * sizeof(float), hipMemcpyHostToDevice), err);
         p = (const float*)dp.p;
         if (k > 0) {
-            PSD_HIP(hipMalloc(&dq.p, nq * sizeof(float)), err);
-            PSD_HIP(hipMemcpy(dq.p, logits_q, nq * sizeof(float), hipMemcpyHostToDevice), err);
+            if (!assisted) {
+                PSD_HIP(hipMalloc(&dq.p, nq * sizeof(float)), err);
+                PSD_HIP(hipMemcpy(dq.p, logits_q, nq * sizeof(float), hipMemcpyHostToDevice), err);
+                q = (const float*)dq.p;
+            }
             PSD_HIP(hipMalloc(&dt.p, k * sizeof(int32_t)), err);
             PSD_HIP(hipMemcpy(dt.p, tokens, k * sizeof(int32_t), hipMemcpyHostToDevice), err);
-            q = (const float*)dq.p;
             t = (const int32_t*)dt.p;
             if (div_out) {
                 PSD_HIP(hipMalloc(&ddiv.p, k * sizeof(float)), err);
@@ -78,13 +81,14 @@ extern "C" int psd_accept(const float* logits_p, const float* logits_q, const in
         }
     }
     int32_t* res = (int32_t*)dres.p;
-    int rc = psd_accept_batch(p, q, t, 1, k, vocab, T, temperature, seed, position0, stage, take_bonus, res, res + 1,
-                              dv, ws.p, ws_bytes, nullptr);
+    const size_t inner = accept_workspace_bytes(1, k, vocab);
+    int rc = accept_launch(p, q, t, 1, k, vocab, T, temperature, seed, position0, stage, take_bonus,
+                           (AcceptOut*)((char*)ws.p + inner), dv, ws.p, inner, nullptr, err, res, res + 1, assisted);
     if (rc != PSD_OK) return rc;
     PSD_HIP(hipDeviceSynchronize(), err);
     int32_t h[2];
     PSD_HIP(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost), err);
-    if (h[0] < 0) PSD_FAIL(PSD_EHIP, err, "psd_accept: the kernels' bounded wait for each other expired");
+    if (h[0] < 0) PSD_FAIL(PSD_EHIP, err, "%s: the kernels' bounded wait for each other expired", who);
     if (where == 0) {
         *n_accepted = h[0];
         *next_token = h[1];
@@ -94,6 +98,21 @@ extern "C" int psd_accept(const float* logits_p, const float* logits_q, const in
         PSD_HIP(hipMemcpy(next_token, res + 1, sizeof(int32_t), hipMemcpyDeviceToDevice), err);
     }
     return PSD_OK;
+}
+
+extern "C" int psd_accept(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k,
+                          int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
+                          uint32_t stage, int32_t take_bonus, int32_t where, int32_t* n_accepted,
+                          int32_t* next_token, float* div_out) {
+    return accept_once("psd_accept", logits_p, logits_q, tokens, k, vocab, T, temperature, seed, position0, stage,
+                       take_bonus, where, n_accepted, next_token, div_out, 0);
+}
+
+extern "C" int psd_accept_assisted(const float* logits_p, const int32_t* tokens, int32_t k, int32_t vocab,
+                                   float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
+                                   int32_t take_bonus, int32_t where, int32_t* n_accepted, int32_t* next_token) {
+    return accept_once("psd_accept_assisted", logits_p, nullptr, tokens, k, vocab, 0.f, temperature, seed, position0,
+                       stage, take_bonus, where, n_accepted, next_token, nullptr, 1);
 }
 
 extern "C" int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float temperature, uint64_t seed,

@@ -92,6 +92,7 @@ struct psd_ctx {
     RoundResult* res = nullptr;
     // graphs: [model][width class 4 / 16 / 32]
     GraphSlot graphs[3][3];
+    GraphSlot chain_graphs[3][3];  // sampling steps: [proposer][model whose pass descriptor receives the tokens]
     Profiler prof;
     StageTimer timer;
     psd_trace_fn trace = nullptr;
@@ -141,7 +142,8 @@ static int wclass(int w) { return w <= 4 ? 4 : (w <= 16 ? 16 : 32); }
 
 // enqueues one pass of model `mi`; the descriptor is already on the device.  with_sample: the draft step
 // also samples its token and advances the chain.
-static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sample, bool allow_graph = false) {
+static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sample, bool allow_graph = false,
+                    int verifier = 1) {
     Model& M = c->M[mi];
     // only the decoding loop's three pass shapes are captured; prefill, the test hook and plain generation stay eager
     const bool use_graph = allow_graph && (c->prm.flags & PSD_FLAG_GRAPH) && !c->prof.on;
@@ -153,13 +155,13 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
             rc = sample_launch(logits, 1, c->V, c->prm.temperature, 0, 0, c->chain, c->samp_tok, c->samp_part,
                                c->stream, c->err);
             if (rc != PSD_OK) return rc;
-            draft_advance<<<1, 64, 0, c->stream>>>(c->samp_tok, c->chain, c->M[0].desc, c->M[1].desc, c->round_tok);
+            draft_advance<<<1, 64, 0, c->stream>>>(c->samp_tok, c->chain, M.desc, c->M[verifier].desc, c->round_tok);
             if (prof && prof->on) prof->end(c->stream);
         }
         return PSD_OK;
     };
     if (!use_graph) return enqueue(&c->prof);
-    GraphSlot& g = c->graphs[mi][wcls == 4 ? 0 : (wcls == 16 ? 1 : 2)];
+    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier] : c->graphs[mi][wcls == 4 ? 0 : (wcls == 16 ? 1 : 2)];
     if (!g.exec) {
         hipGraph_t graph = nullptr;
         PSD_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal), c->err);
@@ -176,6 +178,9 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
 
 static void drop_graphs(psd_ctx* c) {
     for (auto& row : c->graphs)
+        for (auto& g : row)
+            if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+    for (auto& row : c->chain_graphs)
         for (auto& g : row)
             if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
 }
@@ -410,6 +415,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_generate: null context");
     if (!prompt || n_prompt < 1 || n_new < 0 || (n_new > 0 && !out_tokens)) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate: bad argument");
     const int k1 = c->prm.k1, k2 = c->prm.k2, V = c->V;
+    const int assisted = (c->prm.flags & PSD_FLAG_ASSISTED) ? 1 : 0;
     const int cap = n_prompt + n_new + k2 + 2;
     if (cap > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate: n_prompt + n_new + k2 + 2 = %d exceeds max_seq %d", cap, c->prm.max_seq);
     int rc = check_tokens(c, prompt, n_prompt);
@@ -459,7 +465,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage1"), (double)(2 * m + 1) * V * 4);
             c->timer.begin(c->stream, 3);
             rc = accept_launch(c->QL + (size_t)nbuf * V, c->DL, c->round_tok, 1, m, V, c->prm.T_q, c->prm.temperature, seed,
-                               (uint32_t)L, 1u, bonus, c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
+                               (uint32_t)L, 1u, bonus, c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err,
+                               nullptr, nullptr, assisted);
             if (rc != PSD_OK) return rc;
             c->timer.end(c->stream);
             if (c->prof.on) c->prof.end(c->stream);
@@ -474,7 +481,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
                 if ((rc = copy_rows_to_host(c, tr_p, c->QL + (size_t)nbuf * V, m + 1)) != PSD_OK) return rc;
                 for (int i = 0; i < m; ++i)
                     c->trace(c->trace_user, 0, (uint32_t)(L + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
-                c->trace(c->trace_user, 1, (uint32_t)L, m, bonus, tr_p.data(), tr_q.data(), c->res->tok, n, y, c->res->div);
+                c->trace(c->trace_user, assisted ? 3 : 1, (uint32_t)L, m, bonus, tr_p.data(), tr_q.data(), c->res->tok, n, y,
+                         c->res->div);
             }
             for (int i = 0; i < n; ++i) seq[L + i] = c->res->tok[i];
             if (has_y) seq[L + n] = y;
@@ -520,6 +528,106 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         D.len = std::min(D.len, C + n);
         C += n + 1;
         st.proposed_t += k2;
+        st.accepted_t += n;
+        st.fuzzy_t += c->res->acc.n_fuzzy;
+    }
+    PSD_HIP(hipEventRecord(c->ev[2], c->stream), c->err);
+    PSD_HIP(hipEventSynchronize(c->ev[2]), c->err);
+    float ms = 0.f;
+    PSD_HIP(hipEventElapsedTime(&ms, c->ev[0], c->ev[1]), c->err);
+    st.ms_prefill = ms;
+    PSD_HIP(hipEventElapsedTime(&ms, c->ev[1], c->ev[2]), c->err);
+    st.ms_decode = ms;
+    double stage_ms[4] = {0, 0, 0, 0};
+    c->timer.collect(stage_ms);
+    st.ms_d = stage_ms[0]; st.ms_q = stage_ms[1]; st.ms_t = stage_ms[2]; st.ms_accept = stage_ms[3];
+    if (n_new > 0) memcpy(out_tokens, seq.data() + n_prompt, (size_t)n_new * sizeof(int32_t));
+    if (out_stats) *out_stats = st;
+    return PSD_OK;
+}
+
+extern "C" int psd_set_assisted(psd_ctx* c, int32_t on) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_assisted: null context");
+    c->prm.flags = on ? (c->prm.flags | PSD_FLAG_ASSISTED) : (c->prm.flags & ~PSD_FLAG_ASSISTED);
+    return PSD_OK;
+}
+
+extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float tau, const int32_t* prompt,
+                               int32_t n_prompt, int32_t n_new, uint64_t seed, int32_t* out_tokens,
+                               psd_stats* out_stats) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_generate_sd: null context");
+    if ((proposer != 0 && proposer != 1) || !prompt || n_prompt < 1 || n_new < 0 || (n_new > 0 && !out_tokens))
+        PSD_FAIL(PSD_EINVAL, c->err, "psd_generate_sd: bad argument");
+    if (k < 1 || k > c->k2cap) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate_sd: k=%d outside [1, %d]", k, c->k2cap);
+    if (!(tau >= 0.f)) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate_sd: tau=%g", tau);
+    const int V = c->V;
+    const int cap = n_prompt + n_new + k + 2;
+    if (cap > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate_sd: n_prompt + n_new + k + 2 = %d exceeds max_seq %d", cap, c->prm.max_seq);
+    int rc = check_tokens(c, prompt, n_prompt);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipSetDevice(c->device), c->err);
+    Model &P = c->M[proposer], &T = c->M[2];
+    psd_stats st;
+    memset(&st, 0, sizeof(st));
+    std::vector<int32_t> seq(cap + kMaxW, 0);
+    memcpy(seq.data(), prompt, (size_t)n_prompt * sizeof(int32_t));
+    std::vector<float> tr_p, tr_q;
+    int C = n_prompt;
+    P.len = 0; T.len = 0;
+    PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
+    if ((rc = prefill(c, proposer, seq.data(), C - 1)) != PSD_OK) return rc;
+    if ((rc = prefill(c, 2, seq.data(), C - 1)) != PSD_OK) return rc;
+    PSD_HIP(hipEventRecord(c->ev[1], c->stream), c->err);
+    while (C - n_prompt < n_new) {
+        // the proposer's first step ingests the host-known uncached suffix (two tokens after a fully accepted
+        // pass: its own last proposal and the bonus token), the rest chain on the device
+        const int hp = C - P.len, ht = C - T.len;
+        if (hp < 1 || hp > 2 || ht != 1)
+            PSD_FAIL(PSD_EINVAL, c->err, "internal: cache lengths out of step (C=%d P=%d T=%d)", C, P.len, T.len);
+        if ((rc = model_map_pages(P, P.len, C + k, c->stream, c->err)) != PSD_OK) return rc;
+        if ((rc = model_map_pages(T, T.len, C + k, c->stream, c->err)) != PSD_OK) return rc;
+        PassDesc pd, td;
+        fill_desc(pd, seq.data(), P.len, C, 0, 1, 0);
+        fill_desc(td, seq.data(), T.len, C, k, k + 1, 0);
+        SampleCtl sc{seed, C, 0, ht, 0};
+        if ((rc = upload(c, P.desc, &pd, sizeof(pd))) != PSD_OK) return rc;
+        if ((rc = upload(c, T.desc, &td, sizeof(td))) != PSD_OK) return rc;
+        if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
+        c->timer.begin(c->stream, proposer);
+        for (int i = 0; i < k; ++i)
+            if ((rc = run_pass(c, proposer, 4, c->QL, true, true, 2)) != PSD_OK) return rc;
+        c->timer.end(c->stream);
+        (proposer == 0 ? st.passes_d : st.passes_q) += k;
+        c->timer.begin(c->stream, 2);
+        if ((rc = run_pass(c, 2, wclass(ht + k), c->TL, false, true)) != PSD_OK) return rc;
+        c->timer.end(c->stream);
+        st.passes_t++;
+        if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k + 1) * V * 4);
+        c->timer.begin(c->stream, 3);
+        rc = accept_launch(c->TL, c->QL, c->round_tok, 1, k, V, tau, c->prm.temperature, seed, (uint32_t)C, 2u, 1,
+                           c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
+        if (rc != PSD_OK) return rc;
+        c->timer.end(c->stream);
+        if (c->prof.on) c->prof.end(c->stream);
+        PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
+        PSD_HIP(hipMemcpyAsync(c->res->tok, c->round_tok, k * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
+        if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, k * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
+        if ((rc = stage_sync(c)) != PSD_OK) return rc;
+        const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
+        if (n < 0 || n > k || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
+        if (c->trace) {
+            if ((rc = copy_rows_to_host(c, tr_q, c->QL, k)) != PSD_OK) return rc;
+            if ((rc = copy_rows_to_host(c, tr_p, c->TL, k + 1)) != PSD_OK) return rc;
+            for (int i = 0; i < k; ++i)
+                c->trace(c->trace_user, 0, (uint32_t)(C + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
+            c->trace(c->trace_user, 2, (uint32_t)C, k, 1, tr_p.data(), tr_q.data(), c->res->tok, n, y, c->res->div);
+        }
+        for (int i = 0; i < n; ++i) seq[C + i] = c->res->tok[i];
+        seq[C + n] = y;
+        P.len = std::min(C + k - 1, C + n);  // the proposer never ingested its last proposal
+        T.len = std::min(T.len + ht + k, C + n);
+        C += n + 1;
+        st.proposed_t += k;
         st.accepted_t += n;
         st.fuzzy_t += c->res->acc.n_fuzzy;
     }

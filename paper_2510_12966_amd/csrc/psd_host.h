@@ -45,11 +45,13 @@ size_t accept_workspace_bytes(int n_trials, int k, int vocab);
 // Every launch shape is checked against the workspace size before anything is enqueued.
 // n_accepted_out / next_token_out (optional, both or neither): plain [n_trials] copies of the two results.
 // out[b].n_accepted = -1 when the kernels' bounded wait for each other expired.
+// assisted: strict match against the verifier's top prediction, replacement draw from the verifier's row
+// (Section 3.4); logits_q and T are then unused and div_out receives -1.
 int accept_launch(const float* logits_p, const float* logits_q, const int32_t* tokens, int n_trials, int k,
                   int vocab, float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
                   int take_bonus, AcceptOut* out, float* div_out, void* workspace, size_t workspace_bytes,
                   hipStream_t stream, char* errbuf, int32_t* n_accepted_out = nullptr,
-                  int32_t* next_token_out = nullptr);
+                  int32_t* next_token_out = nullptr, int assisted = 0);
 
 // Where the draft chain is: device-resident so that a captured draft step can be replayed unchanged.
 struct SampleCtl {

@@ -1,0 +1,173 @@
+"""GPU parity of the two-model baseline (Section 3.3) and of the assisted variant (Section 3.4) against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_12966_amd as psd
+from paper_2510_12966_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TIE_DIV, TIE_COIN, TIE_RACE = 1e-6, 1e-6, 1e-5
+DIV_TOL = 1e-5
+
+
+def _desc(shape, blob, dtype, theta):
+    return psd.ModelDesc(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_ffn, shape.vocab,
+                         theta, dtype, blob)
+
+
+def _ctx(cfg, blobs, max_seq, T_q, T_t, k1, k2, flags=0, temperature=1.0):
+    shapes = (cfg.draft, cfg.qualifier, cfg.target)
+    d, q, t = (_desc(s, b, cfg.dtype, cfg.rope_theta) for s, b in zip(shapes, blobs))
+    return psd.Context(d, q, t, T_q, T_t, k1, k2, max_seq, temperature=temperature, flags=flags)
+
+
+class Replay:
+    """Every sampling / ACCEPT step of a GPU run, with the GPU's own logits, decided again by the oracle."""
+
+    def __init__(self, seed, T_t, temperature=1.0):
+        self.seed, self.T_t, self.temp = seed, T_t, temperature
+        self.events = self.ties = self.kinds = 0
+
+    def __call__(self, kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
+        self.events += 1
+        self.kinds |= 1 << kind
+        if kind == 0:
+            want, gap = oracle.sample_row(lp[0], self.temp, self.seed, pos0)
+            if want != nxt:
+                assert gap < TIE_RACE, ("proposal", pos0, want, nxt, gap)
+                self.ties += 1
+            return
+        if kind == 3:   # assisted stage: token comparison is exact, only the replacement draw can tie
+            res = oracle.accept_assisted(lp, tk, self.temp, self.seed, pos0, 1, bool(bonus))
+            assert n_acc == res.n_accepted, ("assisted", pos0, n_acc, res.n_accepted)
+            if nxt != res.next_token:
+                assert res.margin_race < TIE_RACE
+                self.ties += 1
+            return
+        assert kind == 2
+        res, odiv = oracle.accept(lp, lq, tk, self.T_t, self.temp, self.seed, pos0, 2, bool(bonus))
+        assert np.abs(div - odiv).max(initial=0.0) <= DIV_TOL
+        if n_acc != res.n_accepted:
+            assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN, ("accept", pos0, n_acc, res.n_accepted)
+            self.ties += 1
+        elif nxt != res.next_token:
+            assert res.margin_race < TIE_RACE
+            self.ties += 1
+
+
+def _om(shape, blob, cfg, ms):
+    return oracle.Model(shape, blob, cfg.dtype, cfg.rope_theta, ms)
+
+
+@pytest.mark.parametrize("graph", [0, psd.FLAG_GRAPH])
+@pytest.mark.parametrize("proposer,k,tau,temp", [(1, 4, 0.0, 1.0), (1, 8, 0.012, 1.0), (0, 5, 0.02, 1.0), (1, 1, 0.0, 0.7),
+                                                 (0, 7, 0.0, 1.0)])
+def test_two_model_baseline_matches_oracle(tiny_stack, proposer, k, tau, temp, graph):
+    cfg, d, q, t, prompt = tiny_stack
+    n_new, seed = 48, 11
+    ms = len(prompt) + n_new + 8 + 2
+    ctx = _ctx(cfg, (d, q, t), ms, 0.3, 0.2, 4, 8, flags=graph, temperature=temp)
+    rp = Replay(seed, tau, temp)
+    ctx.set_trace(rp)
+    out, st = ctx.generate_sd(proposer, k, tau, prompt, n_new, seed)
+    ctx.set_trace(None)
+    assert rp.events > 0 and rp.kinds == 0b101
+    shape, blob = ((cfg.draft, d), (cfg.qualifier, q))[proposer]
+    ref, ost = oracle.generate_sd(_om(shape, blob, cfg, ms), _om(cfg.target, t, cfg, ms), prompt, n_new, seed, k, tau, temp)
+    if rp.ties == 0 and np.array_equal(out, ref):
+        for key in ("proposed_t", "accepted_t", "fuzzy_t", "passes_t"):
+            assert st[key] == ost[key], key
+        assert (st["passes_d"], st["passes_q"])[proposer] == ost["passes_d"]
+    else:
+        first = int(np.argmax(out != ref)) if not np.array_equal(out, ref) else n_new
+        assert first > 0 or rp.ties > 0
+    assert st["proposed_t"] == k * st["passes_t"] and 0 < st["accepted_t"] <= st["proposed_t"]
+    # the three-model loop afterwards is unaffected (graphs and caches are per pass shape), and a second
+    # two-model call repeats the first
+    full, _ = ctx.generate(prompt, 24, seed)
+    out2, _ = ctx.generate_sd(proposer, k, tau, prompt, n_new, seed)
+    assert np.array_equal(out, out2)
+    D, Q, T = _om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms)
+    fref, _ = oracle.generate(D, Q, T, prompt, 24, seed, 4, 8, 0.3, 0.2, temp)
+    assert np.array_equal(full, fref) or (full[:4] == fref[:4]).all()
+    ctx.close()
+
+
+def test_two_model_baseline_identical_models_equal_plain(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ms = len(prompt) + 40 + 10
+    same = _desc(cfg.target, t, cfg.dtype, cfg.rope_theta)
+    ctx = psd.Context(same, same, same, 0.0, 0.0, 4, 8, ms)
+    # tau slightly above zero: widths 1 and k + 1 may round the same row differently in the last bit
+    out, st = ctx.generate_sd(1, 6, 1e-4, prompt, 40, 2)
+    plain, _ = ctx.generate_plain(2, prompt, 40, 2)
+    assert st["accepted_t"] == st["proposed_t"] and np.array_equal(out, plain)
+    ctx.close()
+
+
+def test_two_model_argument_errors(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx(cfg, (d, q, t), 64, 0.3, 0.2, 4, 8)
+    for bad in ((2, 4, 0.0), (1, 0, 0.0), (1, 9, 0.0), (1, 4, -1.0)):
+        with pytest.raises(psd.PsdError):
+            ctx.generate_sd(bad[0], bad[1], bad[2], prompt, 8, 0)
+    with pytest.raises(psd.PsdError):
+        ctx.generate_sd(1, 4, 0.0, prompt, 64, 0)   # exceeds max_seq
+    ctx.close()
+
+
+@pytest.mark.parametrize("V", [3, 97, 4099, 32000, 128256])
+def test_assisted_accept_matches_oracle(V):
+    rng = np.random.default_rng(V)
+    for k in (0, 1, 6, 32):
+        lp = rng.normal(0, 2.5, (k + 1, V)).astype(np.float32)
+        top = lp.argmax(1)[:k].astype(np.int32)
+        for cut in sorted({0, k // 2, k}):
+            x = top.copy()
+            if cut < k:
+                x[cut] = (x[cut] + 1) % V
+            for temp in (1.0, 0.6):
+                for bonus in (True, False):
+                    n, tok = psd.accept_assisted(lp, x, temp, 5, 70, 1, bonus)
+                    res = oracle.accept_assisted(lp, x, temp, 5, 70, 1, bonus)
+                    assert n == res.n_accepted
+                    assert tok == res.next_token or res.margin_race < TIE_RACE
+    # equal maxima: the lowest index is the top prediction, on both sides
+    lp = np.zeros((2, max(V, 8)), np.float32)
+    lp[0, 5] = lp[0, 2] = 3.0
+    assert psd.accept_assisted(lp, [2], 1.0, 1, 0, 1, True)[0] == 1
+    assert psd.accept_assisted(lp, [5], 1.0, 1, 0, 1, True)[0] == 0
+
+
+@pytest.mark.parametrize("graph", [0, psd.FLAG_GRAPH])
+@pytest.mark.parametrize("T_t,k1,k2,temp", [(0.012, 4, 8, 1.0), (0.0, 3, 7, 0.5), (0.2, 1, 1, 0.3), (0.012, 8, 3, 0.3)])
+def test_assisted_loop_matches_oracle(tiny_stack, T_t, k1, k2, temp, graph):
+    cfg, d, q, t, prompt = tiny_stack
+    n_new, seed = 48, 4
+    ms = len(prompt) + n_new + k2 + 2
+    ctx = _ctx(cfg, (d, q, t), ms, 0.0, T_t, k1, k2, flags=graph | psd.FLAG_ASSISTED, temperature=temp)
+    rp = Replay(seed, T_t, temp)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, seed)
+    ctx.set_trace(None)
+    assert rp.kinds == 0b1101
+    D, Q, T = _om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms)
+    ref, ost = oracle.generate_assisted(D, Q, T, prompt, n_new, seed, k1, k2, T_t, temp)
+    if rp.ties == 0 and np.array_equal(out, ref):
+        for key in ("proposed_q", "accepted_q", "fuzzy_q", "proposed_t", "accepted_t", "fuzzy_t", "passes_d", "passes_q",
+                    "passes_t"):
+            assert st[key] == ost[key], key
+    else:
+        first = int(np.argmax(out != ref)) if not np.array_equal(out, ref) else n_new
+        assert first > 0 or rp.ties > 0
+    assert st["fuzzy_q"] == 0
+    # switching the rule off on the same context gives the fuzzy loop again
+    ctx.set_assisted(False)
+    ctx.set_decoding(0.004, T_t, k1, k2, temp)
+    fz, _ = ctx.generate(prompt, n_new, seed)
+    D, Q, T = _om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms)
+    fref, _ = oracle.generate(D, Q, T, prompt, n_new, seed, k1, k2, 0.004, T_t, temp)
+    assert np.array_equal(fz, fref) or (fz[:3] == fref[:3]).all()
+    ctx.close()
