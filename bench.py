@@ -33,7 +33,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def accept_microbench(psd, synth) -> int:
+def accept_microbench(psd, synth, ks=(4, 8, 16, 32), quick=False, calibrate=False) -> int:
     """Stand-alone ACCEPT stage on batched trials: achieved GB/s (algorithmic bytes: every logit read once) and
     accept-length histogram parity with the oracle on the same trials."""
     import math
@@ -42,8 +42,13 @@ def accept_microbench(psd, synth) -> int:
 
     V, seed, B, reps = 128256, 7, 48, 5
     rows = []
-    for k in (4, 8, 16, 32):
-        for rho in (0.5, 0.8, 0.95):
+    if calibrate:   # a kernel of known traffic, for scaling hardware counters read under rocprofv3 --pmc
+        a, b = psd.DeviceBuffer(256 << 20), psd.DeviceBuffer(256 << 20)
+        psd.lib().psd_dev_copy(b.data_ptr(), a.data_ptr(), 256 << 20, 2)
+        psd.dev_sync()
+        a.free(); b.free()
+    for k in ks:
+        for rho in ((0.8,) if quick else (0.5, 0.8, 0.95)):
             P, Q, X = [], [], []
             for b in range(B):
                 t, q, _ = synth.accept_logits(seed, b, k, V, rho)     # stage "target <- qualifier"
@@ -53,7 +58,7 @@ def accept_microbench(psd, synth) -> int:
             na, nt, dv = psd.DeviceBuffer(4 * B), psd.DeviceBuffer(4 * B), psd.DeviceBuffer(4 * B * k)
             wsb = psd.accept_workspace_bytes(B, k, V)
             ws = psd.DeviceBuffer(wsb)
-            for T in (0.0, 0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, math.log(2)):
+            for T in ((0.2,) if quick else (0.0, 0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, math.log(2))):
                 psd.accept_batch(dp, dq, dx, B, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
                 psd.dev_sync()
                 t0 = time.perf_counter()
@@ -110,9 +115,15 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-baselines", action="store_true",
+                    help="skip the untimed comparison runs on the same context (plain target sampling, two-model SD and "
+                         "fuzzy SD with the qualifier as proposer, assisted variant, strict thresholds)")
     ap.add_argument("--accept-microbench", action="store_true",
                     help="instead of the loop: time the stand-alone batched ACCEPT stage (vocab 128256, k in 4/8/16/32, "
                          "correlated synthetic logits) and check accept-length histograms against the oracle")
+    ap.add_argument("--accept-k", default="4,8,16,32", help="window lengths of --accept-microbench")
+    ap.add_argument("--accept-quick", action="store_true",
+                    help="--accept-microbench on one setting per k (rho 0.8, T 0.2): short enough to run under a profiler")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the timed steps: sweep k1 x k2 x T_q x T_t on the chosen configuration and print a table")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -128,7 +139,8 @@ def main() -> int:
     from paper_2510_12966_amd import synth
 
     if args.accept_microbench:
-        return accept_microbench(psd, synth)
+        return accept_microbench(psd, synth, tuple(int(x) for x in args.accept_k.split(",")), args.accept_quick,
+                                 args.calibrate_copy)
     cfg = synth.CONFIGS[args.config]
     n_new = args.n_new or cfg.n_new
     t0 = time.time()
@@ -167,6 +179,39 @@ def main() -> int:
     value = n_new * args.steps / wall
     log(f"[bench] {args.steps} steps: {ms_per_step:.1f} ms/step, decode-only {n_new * args.steps / decode_ms * 1e3:.1f} tok/s, "
         f"last stats {st}")
+
+    baselines = None
+    if not args.no_baselines:
+        # Untimed comparison runs on the same context, decode-only tokens/s each (Section 3.3: the speed-up is
+        # quoted against two-model speculative decoding with the qualifier-sized model as proposer).
+        def rate(fn, n):
+            _, s_ = fn(n)
+            return round(n / s_["ms_decode"] * 1e3, 1), s_
+        seed = cfg.sample_seed
+        baselines = {"psd_f": round(n_new * args.steps / decode_ms * 1e3, 1)}
+        baselines["plain_target"], _ = rate(lambda n: ctx.generate_plain(2, prompt, n, seed), min(n_new, 128))
+        for name, tau in (("sd", 0.0), ("fsd", cfg.T_t)):
+            best = None
+            for k in sorted({cfg.k1, cfg.k2}):
+                r, s_ = rate(lambda n: ctx.generate_sd(1, k, tau, prompt, n, seed), n_new)
+                row = {"k": k, "tokens_per_s": r, "accept_rate": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
+                if best is None or r > best["tokens_per_s"]:
+                    best = row
+            baselines[name + "_qualifier_to_target"] = best
+        ctx.set_assisted(True)
+        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), n_new)
+        ctx.set_assisted(False)
+        baselines["psd_a"] = {"tokens_per_s": r, "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
+                              "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
+        ctx.set_decoding(0.0, 0.0, cfg.k1, cfg.k2, cfg.temperature)
+        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), n_new)
+        ctx.set_decoding(cfg.T_q, cfg.T_t, cfg.k1, cfg.k2, cfg.temperature)
+        baselines["psd_strict_thresholds"] = {"tokens_per_s": r,
+                                              "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
+                                              "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
+        baselines["psd_f_over_sd"] = round(baselines["psd_f"] / baselines["sd_qualifier_to_target"]["tokens_per_s"], 3)
+        baselines["psd_f_over_fsd"] = round(baselines["psd_f"] / baselines["fsd_qualifier_to_target"]["tokens_per_s"], 3)
+        log(f"[bench] comparison runs (decode tokens/s): {baselines}")
 
     bytes_per_pass = {"draft": None, "qualifier": None, "target": None}
     roofline = None
@@ -236,7 +281,7 @@ def main() -> int:
                         "qualifier": round(st["ms_q"] / max(st["passes_q"], 1), 4),
                         "target": round(st["ms_t"] / max(st["passes_t"], 1), 4),
                         "accept": round(st["ms_accept"] / max(st["passes_q"] + st["passes_t"], 1), 4)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "comparison_runs": baselines,
         "paper_context": "124.13 tok/s PSD_F best, 1.91x over SD, RTX 4090, trained Llama 1B/3B/8B (Tables 2-3)",
     }
     print(json.dumps(line), flush=True)
