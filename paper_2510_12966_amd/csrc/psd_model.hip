@@ -295,13 +295,33 @@ __device__ inline void attn_merge(const float* part, int nsp, int c, int head, i
                 for (int e = 0; e < N; ++e) out[e] = fmaf(o[s][e], f, out[e]);
             }
     } else {
-        for (int s = 0; s < nsp; ++s) M = fmaxf(M, p0[s * stride]);
-        for (int s = 0; s < nsp; ++s) {
-            const float* pr = p0 + s * stride;
-            const float f = expf(pr[0] - M);
-            Lsum = fmaf(pr[1], f, Lsum);
+        // long contexts: the same arithmetic in the same order, with the loads of 16 / 8 partials issued together
+        for (int s0 = 0; s0 < nsp; s0 += 16) {
+            float m[16];
 #pragma unroll
-            for (int e = 0; e < N; ++e) out[e] = fmaf(pr[2 + i + e], f, out[e]);
+            for (int s = 0; s < 16; ++s) m[s] = (s0 + s < nsp) ? p0[(size_t)(s0 + s) * stride] : -INFINITY;
+#pragma unroll
+            for (int s = 0; s < 16; ++s) M = fmaxf(M, m[s]);
+        }
+        for (int s0 = 0; s0 < nsp; s0 += 8) {
+            float m[8], l[8], o[8][N];
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                if (s0 + s < nsp) {
+                    const float* pr = p0 + (size_t)(s0 + s) * stride;
+                    m[s] = pr[0];
+                    l[s] = pr[1];
+#pragma unroll
+                    for (int e = 0; e < N; ++e) o[s][e] = pr[2 + i + e];
+                }
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                if (s0 + s < nsp) {
+                    const float f = expf(m[s] - M);
+                    Lsum = fmaf(l[s], f, Lsum);
+#pragma unroll
+                    for (int e = 0; e < N; ++e) out[e] = fmaf(o[s][e], f, out[e]);
+                }
         }
     }
 #pragma unroll
