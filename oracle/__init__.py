@@ -73,6 +73,7 @@ def lib():
         L.orc_generate.restype = C.c_int
         L.orc_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.c_void_p, C.c_int,
                                    C.c_int, C.c_uint64, C.c_void_p, C.POINTER(Stats)]
+        L.orc_row_stats.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_void_p, C.c_void_p]
         L.orc_accept_assisted.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_uint64, C.c_uint32,
                                           C.c_uint32, C.c_int, C.c_void_p]
         L.orc_generate_assisted.restype = C.c_int
@@ -147,6 +148,14 @@ def accept(logits_p, logits_q, x, T, temperature=1.0, seed=0, position0=0, stage
     lib().orc_accept(lp.ctypes.data, lq.ctypes.data, x.ctypes.data, k, V, T, temperature, seed, position0, stage,
                      int(take_bonus), C.byref(res), div.ctypes.data)
     return res, div[:k]
+
+
+def row_stats(logits, temperature=1.0):
+    """(entropy in nats, largest probability) of softmax(logits / temperature), one row (Section 4)."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    h, m = C.c_double(0), C.c_double(0)
+    lib().orc_row_stats(lg.ctypes.data, lg.size, temperature, C.byref(h), C.byref(m))
+    return h.value, m.value
 
 
 def accept_assisted(logits_p, x, temperature=1.0, seed=0, position0=0, stage=1, take_bonus=True):

@@ -123,6 +123,22 @@ int orc_race(const double* w, int V, uint64_t seed, uint32_t position, uint32_t 
     return best;
 }
 
+/* Entropy (nats) and largest probability of softmax(logits / temperature): the two per-step
+ * statistics of the model-behaviour analysis (Section 4, "Model Behavior Analysis":
+ * entropy of the predictive distribution and the maximum predicted probability). */
+void orc_row_stats(const float* logits, int V, double temperature, double* entropy, double* max_prob) {
+    double* p = (double*)malloc((size_t)V * sizeof(double));
+    orc_softmax(logits, V, temperature, p);
+    double h = 0.0, mx = 0.0;
+    for (int v = 0; v < V; ++v) {
+        if (p[v] > 0.0) h -= p[v] * log(p[v]);
+        if (p[v] > mx) mx = p[v];
+    }
+    *entropy = h;
+    *max_prob = mx;
+    free(p);
+}
+
 /* ------------------------------------------------------------------------- */
 /* ACCEPT: one verify stage over k proposed tokens                           */
 /* ------------------------------------------------------------------------- */

@@ -1,5 +1,6 @@
 """Pins of the oracle's two-model baseline (Section 3.3, first equation) and of the assisted variant (Section 3.4)."""
 import numpy as np
+import scipy.special
 import scipy.stats
 
 import oracle
@@ -168,3 +169,31 @@ def test_assisted_loop_first_token_law_on_vocab8():
         acc_q += st["accepted_q"]
     assert abs(acc_q / N - a) < 4 * np.sqrt(a * (1 - a) / N)
     assert ((counts - N * law) ** 2 / (N * law)).sum() < scipy.stats.chi2.ppf(0.9999, V - 1)
+
+
+# ---- per-step statistics of the behaviour analysis (Section 4) ---------------------------------------------
+
+def test_row_stats_closed_forms_and_library():
+    import math
+    V = 1000
+    h, m = oracle.row_stats(np.full(V, 3.7, np.float32))
+    assert abs(h - math.log(V)) < 1e-12 and abs(m - 1 / V) < 1e-15            # uniform
+    z = np.full(V, -80.0, np.float32); z[17] = 30.0
+    h, m = oracle.row_stats(z)
+    assert h < 1e-40 and abs(m - 1) < 1e-15                                    # one-hot
+    # two-point mass: logits (a, 0) -> p = sigmoid(a); entropy is the binary entropy
+    for a in (0.3, 2.0, -1.5):
+        p = 1 / (1 + math.exp(-a))
+        h, m = oracle.row_stats(np.array([a, 0.0], np.float32))
+        a32 = float(np.float32(a)); p = 1 / (1 + math.exp(-a32))
+        assert abs(h - (-(p * math.log(p) + (1 - p) * math.log(1 - p)))) < 1e-12 and abs(m - max(p, 1 - p)) < 1e-12
+    rng = np.random.default_rng(3)
+    z = rng.normal(0, 2.5, 5000).astype(np.float32)
+    for temp in (1.0, 0.6, 3.0):
+        h, m = oracle.row_stats(z, temp)
+        p = scipy.special.softmax(z.astype(np.float64) / temp)
+        assert abs(h - scipy.stats.entropy(p)) < 1e-10 and abs(m - p.max()) < 1e-12
+    # shift invariance, and the temperature limits
+    assert np.allclose(oracle.row_stats(z), oracle.row_stats(z + np.float32(8.0)), rtol=0, atol=1e-6)
+    assert abs(oracle.row_stats(z, 1e6)[0] - math.log(z.size)) < 1e-6
+    assert oracle.row_stats(z, 1e-3)[1] > 0.999
