@@ -29,6 +29,15 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+def throughput_model(beta_qd, beta_tq, l_d, l_q, v_d, v_q, v_t):
+    """Closed-form tokens/s of Section 3.3 from stage accept rates, speculative lengths and per-model speeds
+    (tokens/s of one forward each).  Returns (V_FSD(Q,D), V_PSD, V_SD with the qualifier as proposer)."""
+    v_fsd_qd = beta_qd * (l_d + 1) / (l_d / v_d + 1.0 / v_q)
+    v_psd = beta_tq * (l_q + 1) / (l_q / v_fsd_qd + 1.0 / v_t)
+    v_sd = beta_tq * (l_q + 1) / (l_q / v_q + 1.0 / v_t)
+    return v_fsd_qd, v_psd, v_sd
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -209,6 +218,18 @@ def main() -> int:
         baselines["psd_strict_thresholds"] = {"tokens_per_s": r,
                                               "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
                                               "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
+        ctx.set_row_stats(True)   # entropy / confidence per model over one more run (Section 4's two statistics)
+        ctx.generate(prompt, min(n_new, 128), seed)
+        baselines["row_stats"] = {m: {"rows": v[0], "mean_entropy_nats": round(v[1], 4), "mean_max_prob": round(v[2], 6)}
+                                  for m, v in ctx.row_stats().items()}
+        ctx.set_row_stats(False)
+        # Section 3.3's closed forms evaluated at this run's own accept rates and per-pass times; they ignore the
+        # catch-up widths, the ACCEPT kernels and the host, so they bound the measured rate from above
+        v_d, v_q, v_t = (1e3 * st[p] / max(st[m], 1e-9) for p, m in (("passes_d", "ms_d"), ("passes_q", "ms_q"), ("passes_t", "ms_t")))
+        f_qd, f_psd, _ = throughput_model(st["accepted_q"] / max(st["proposed_q"], 1), st["accepted_t"] / max(st["proposed_t"], 1),
+                                          cfg.k1, cfg.k2, v_d, v_q, v_t)
+        baselines["section_3_3_model"] = {"V_FSD_QD": round(f_qd, 1), "V_PSD": round(f_psd, 1),
+                                          "measured_over_model": round(baselines["psd_f"] / f_psd, 3)}
         baselines["psd_f_over_sd"] = round(baselines["psd_f"] / baselines["sd_qualifier_to_target"]["tokens_per_s"], 3)
         baselines["psd_f_over_fsd"] = round(baselines["psd_f"] / baselines["fsd_qualifier_to_target"]["tokens_per_s"], 3)
         log(f"[bench] comparison runs (decode tokens/s): {baselines}")

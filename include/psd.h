@@ -91,6 +91,8 @@ enum {
     PSD_FLAG_ASSISTED = 2,          /* qualifier stage of psd_generate as in Section 3.4: a draft token passes iff it is
                                        the qualifier's top prediction, a rejected one is replaced by a sample of the
                                        qualifier's own distribution; T_q is unused */
+    PSD_FLAG_ROW_STATS = 4,         /* collect entropy and largest probability of every logits row the loops produce
+                                       (Section 4, model behaviour analysis); read with psd_get_row_stats */
     PSD_FLAG_SCRAMBLE_PAGES = 0x100 /* test aid: hand out physical KV pages in a shuffled order */
 };
 
@@ -152,6 +154,19 @@ int psd_generate(psd_ctx* ctx, const int32_t* prompt, int32_t n_prompt, int32_t 
  * Errors: PSD_EINVAL, PSD_ESHAPE (n_prompt + n_new + k + 2 > max_seq), PSD_EHIP. */
 int psd_generate_sd(psd_ctx* ctx, int32_t proposer, int32_t k, float tau, const int32_t* prompt, int32_t n_prompt,
                     int32_t n_new, uint64_t seed, int32_t* out_tokens, psd_stats* out_stats);
+
+/* Per-step statistics of the behaviour analysis (Section 4): entropy in nats and largest probability of
+ * softmax(row / temperature) for n_rows logits rows [n_rows][vocab].  where: 0 host pointers, 1 device pointers
+ * (device logits must be 16-byte aligned).  entropy, max_prob: [n_rows] floats. */
+int psd_row_stats(const float* logits, int32_t n_rows, int32_t vocab, float temperature, int32_t where,
+                  float* entropy, float* max_prob);
+
+/* In-loop collection of the same statistics, as PSD_FLAG_ROW_STATS does at creation: while on, psd_generate and
+ * psd_generate_sd evaluate every logits row their passes produce (one extra sweep of those rows per pass).
+ * psd_get_row_stats fills out[9] (host) = per model (draft, qualifier, target): number of rows, mean entropy,
+ * mean largest probability, over the last generation call. */
+int psd_set_row_stats(psd_ctx* ctx, int32_t on);
+int psd_get_row_stats(psd_ctx* ctx, double* out);
 
 /* Switches the qualifier stage of psd_generate between the fuzzy rule (0) and the assisted rule of
  * Section 3.4 (1), as PSD_FLAG_ASSISTED does at creation. */

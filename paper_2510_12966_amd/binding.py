@@ -11,6 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 F32, BF16 = 0, 1
 FLAG_GRAPH = 1
 FLAG_ASSISTED = 2
+FLAG_ROW_STATS = 4
 MAX_WIDTH = 32
 
 
@@ -95,6 +96,9 @@ def lib():
         L.psd_generate_sd.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_uint64, C.c_void_p, C.POINTER(Stats)]
         L.psd_set_assisted.argtypes = [C.c_void_p, C.c_int32]
+        L.psd_set_row_stats.argtypes = [C.c_void_p, C.c_int32]
+        L.psd_get_row_stats.argtypes = [C.c_void_p, C.c_void_p]
+        L.psd_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p]
         L.psd_accept_assisted.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
                                           C.c_uint32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.psd_forward.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
@@ -192,6 +196,17 @@ def accept_assisted(logits_p, tokens, temperature=1.0, seed=0, position0=0, stag
     return n.value, t.value
 
 
+def row_stats(logits, temperature=1.0):
+    """psd_row_stats on a host array [n_rows, vocab].  Returns (entropy[n_rows], max_prob[n_rows])."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    lg = lg.reshape(1, -1) if lg.ndim == 1 else lg
+    n, V = lg.shape
+    h = np.empty(n, dtype=np.float32)
+    m = np.empty(n, dtype=np.float32)
+    _check(lib().psd_row_stats(lg.ctypes.data, n, V, temperature, 0, h.ctypes.data, m.ctypes.data))
+    return h, m
+
+
 def set_accept_path(path):
     _check(lib().psd_set_accept_path(path))
 
@@ -281,6 +296,16 @@ class Context:
         _check(lib().psd_generate_sd(self._h, proposer, k, tau, pr.ctypes.data, pr.size, n_new, seed, out.ctypes.data,
                                      C.byref(st)), self._h)
         return out, st.as_dict()
+
+    def set_row_stats(self, on: bool):
+        _check(lib().psd_set_row_stats(self._h, int(on)), self._h)
+
+    def row_stats(self):
+        """{model: (rows, mean entropy, mean largest probability)} of the last generation call."""
+        out = np.zeros(9, dtype=np.float64)
+        _check(lib().psd_get_row_stats(self._h, out.ctypes.data), self._h)
+        return {name: (int(out[3 * i]), float(out[3 * i + 1]), float(out[3 * i + 2]))
+                for i, name in enumerate(("draft", "qualifier", "target"))}
 
     def set_assisted(self, on: bool):
         _check(lib().psd_set_assisted(self._h, int(on)), self._h)

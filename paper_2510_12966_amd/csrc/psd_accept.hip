@@ -599,6 +599,99 @@ int sample_launch(const float* logits, int n_rows, int vocab, float temperature,
     return PSD_OK;
 }
 
+// ---- per-step statistics of the behaviour analysis (Section 4): entropy and largest probability ----------
+// H = ln Z - sum_v p_v z_v with z = logit / temperature, Z = sum_v e^(z_v); per chunk: maximum, S = sum 2^(y - m)
+// and U = sum 2^(y - m) (y - m) in base 2 (y = z log2 e); the second kernel folds the chunks in order.
+struct StatPart { float m, s, u, pad; };
+
+__global__ __launch_bounds__(kAccThreads) void row_stats_partial(const float* logits, int V, int nch, float inv_temp,
+                                                                 StatPart* parts) {
+    __shared__ float4 lds[4];
+    const int ch = blockIdx.x, r = blockIdx.y;
+    const float* row = logits + (size_t)r * V;
+    const bool vec = (V & 3) == 0;
+    const float c2 = inv_temp * kLog2e;
+    float a[kQuadsPerThread][4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kQuadsPerThread; ++j) {
+        load4(row, ch * kAcceptChunk + 4 * (threadIdx.x + kAccThreads * j), V, vec, a[j]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, a[j][e]);
+    }
+    const float mw = fmaxf(wave_max_dpp(mx) * c2, -kBig);
+    float sw = 0.f, uw = 0.f;
+#pragma unroll
+    for (int j = 0; j < kQuadsPerThread; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float d = fmaxf(fmaf(a[j][e], c2, -mw), -kBig);  // masked entries: 2^d = 0 and 0 * finite = 0
+            const float x = fast_exp2(d);
+            sw = sw + x;
+            uw = fmaf(x, d, uw);
+        }
+    sw = wave_sum_dpp(sw);
+    uw = wave_sum_dpp(uw);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = make_float4(mw, sw, uw, 0.f);
+    __syncthreads();
+    if (threadIdx.x == 0) {  // the four waves in order, relative to the chunk maximum
+        float M = fmaxf(fmaxf(lds[0].x, lds[1].x), fmaxf(lds[2].x, lds[3].x)), S = 0.f, U = 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const float f = fast_exp2(lds[i].x - M);
+            S = fmaf(lds[i].y, f, S);
+            U = fmaf(fmaf(lds[i].y, lds[i].x - M, lds[i].z), f, U);  // sum x (d + (m_w - M))
+        }
+        parts[(size_t)r * nch + ch] = StatPart{M, S, U, 0.f};
+    }
+}
+
+// one wave per row; acc (optional, device): {rows, sum of entropies, sum of largest probabilities} as doubles,
+// updated by a single lane in row order
+__global__ __launch_bounds__(64) void row_stats_final(const StatPart* parts, int nch, int n_rows, float* entropy,
+                                                      float* max_prob, double* acc) {
+    const int lane = threadIdx.x;
+    double h_sum = 0.0, p_sum = 0.0;
+    for (int r = 0; r < n_rows; ++r) {
+        const StatPart* pr = parts + (size_t)r * nch;
+        float m = -INFINITY;
+        for (int c = lane; c < nch; c += 64) m = fmaxf(m, pr[c].m);
+        const float M = wave_max_dpp(m);
+        float s = 0.f, u = 0.f;
+        for (int c = lane; c < nch; c += 64) {
+            const StatPart t = pr[c];
+            const float f = fast_exp2(t.m - M);
+            s = fmaf(t.s, f, s);
+            u = fmaf(fmaf(t.s, t.m - M, t.u), f, u);
+        }
+        const float S = wave_sum_dpp(s), U = wave_sum_dpp(u);
+        // base 2: log2 Z = M + log2 S, sum_v p_v (y_v - M) = U / S  ->  H = ln 2 (log2 S - U / S);  p_max = 1 / S
+        const float H = kLn2 * (log2f(S) - U / S), P = 1.f / S;
+        if (lane == 0) {
+            if (entropy) entropy[r] = H;
+            if (max_prob) max_prob[r] = P;
+        }
+        h_sum += H;
+        p_sum += P;
+    }
+    if (acc && lane == 0) { acc[0] += n_rows; acc[1] += h_sum; acc[2] += p_sum; }
+}
+
+size_t row_stats_workspace_bytes(int n_rows, int vocab) { return (size_t)n_rows * accept_chunks(vocab) * sizeof(StatPart); }
+
+int row_stats_launch(const float* logits, int n_rows, int vocab, float temperature, float* entropy, float* max_prob,
+                     double* acc, void* workspace, hipStream_t stream, char* errbuf) {
+    if (!logits || !workspace) PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: null pointer");
+    if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
+        PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
+    if ((uintptr_t)logits & 15) PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: logits must be 16-byte aligned");
+    const int nch = accept_chunks(vocab);
+    row_stats_partial<<<dim3(nch, n_rows), kAccThreads, 0, stream>>>(logits, vocab, nch, 1.0f / temperature,
+                                                                    (StatPart*)workspace);
+    row_stats_final<<<1, 64, 0, stream>>>((const StatPart*)workspace, nch, n_rows, entropy, max_prob, acc);
+    PSD_HIP(hipGetLastError(), errbuf);
+    return PSD_OK;
+}
+
 }  // namespace psd
 
 // ---- C ABI --------------------------------------------------------------------------------------

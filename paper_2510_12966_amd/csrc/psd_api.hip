@@ -115,6 +115,36 @@ extern "C" int psd_accept_assisted(const float* logits_p, const int32_t* tokens,
                        stage, take_bonus, where, n_accepted, next_token, nullptr, 1);
 }
 
+extern "C" int psd_row_stats(const float* logits, int32_t n_rows, int32_t vocab, float temperature, int32_t where,
+                             float* entropy, float* max_prob) {
+    char* err = tls_error();
+    if (!logits || !entropy || !max_prob) PSD_FAIL(PSD_EINVAL, err, "psd_row_stats: null pointer");
+    if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
+        PSD_FAIL(PSD_EINVAL, err, "psd_row_stats: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
+    if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "psd_row_stats: where must be 0 or 1");
+    DevBuf dl, ws, dout;
+    const size_t nb = (size_t)n_rows * vocab * sizeof(float);
+    const float* l = logits;
+    float *e = entropy, *m = max_prob;
+    PSD_HIP(hipMalloc(&ws.p, row_stats_workspace_bytes(n_rows, vocab)), err);
+    if (where == 0) {
+        PSD_HIP(hipMalloc(&dl.p, nb), err);
+        PSD_HIP(hipMemcpy(dl.p, logits, nb, hipMemcpyHostToDevice), err);
+        PSD_HIP(hipMalloc(&dout.p, 2 * (size_t)n_rows * sizeof(float)), err);
+        l = (const float*)dl.p;
+        e = (float*)dout.p;
+        m = e + n_rows;
+    }
+    int rc = row_stats_launch(l, n_rows, vocab, temperature, e, m, nullptr, ws.p, nullptr, err);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipDeviceSynchronize(), err);
+    if (where == 0) {
+        PSD_HIP(hipMemcpy(entropy, e, (size_t)n_rows * sizeof(float), hipMemcpyDeviceToHost), err);
+        PSD_HIP(hipMemcpy(max_prob, m, (size_t)n_rows * sizeof(float), hipMemcpyDeviceToHost), err);
+    }
+    return PSD_OK;
+}
+
 extern "C" int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float temperature, uint64_t seed,
                           uint32_t position0, int32_t where, int32_t* tokens_out) {
     char* err = tls_error();

@@ -86,6 +86,8 @@ struct psd_ctx {
     SampleCtl* chain = nullptr;
     int32_t* round_tok = nullptr;  // [32] draft tokens of the round
     int32_t* win_tok = nullptr;    // [32] window tokens for the target stage
+    void* rs_ws = nullptr;         // workspace of the per-row statistics kernels
+    double* rs_acc = nullptr;      // [3 models][rows, sum of entropies, sum of largest probabilities]
     // pinned staging
     char* stage = nullptr;  // kStageSlots * kStageSlotBytes
     int stage_next = 0, stage_since_sync = 0;
@@ -211,6 +213,12 @@ static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
     return PSD_OK;
 }
 
+// behaviour statistics (Section 4) of `rows` logits rows model `mi` has just produced; only when asked for
+static int note_rows(psd_ctx* c, int mi, const float* rows, int n) {
+    if (!(c->prm.flags & PSD_FLAG_ROW_STATS) || n < 1) return PSD_OK;
+    return row_stats_launch(rows, n, c->V, c->prm.temperature, nullptr, nullptr, c->rs_acc + 3 * mi, c->rs_ws, c->stream, c->err);
+}
+
 static int check_tokens(psd_ctx* c, const int32_t* t, int n) {
     for (int i = 0; i < n; ++i)
         if (t[i] < 0 || t[i] >= c->V) PSD_FAIL(PSD_EINVAL, c->err, "token %d at index %d is outside [0, %d)", t[i], i, c->V);
@@ -251,6 +259,8 @@ static size_t ctx_extra_bytes(int V, int k1, int k2) {
     add(sizeof(SampleCtl));
     add(kMaxW * 4);
     add(kMaxW * 4);
+    add(row_stats_workspace_bytes(kMaxW, V));
+    add(9 * sizeof(double));
     return b + 4096;
 }
 
@@ -319,6 +329,8 @@ extern "C" int psd_create(const psd_model_desc* draft, const psd_model_desc* qua
     c->chain = (SampleCtl*)take(sizeof(SampleCtl));
     c->round_tok = (int32_t*)take(kMaxW * 4);
     c->win_tok = (int32_t*)take(kMaxW * 4);
+    c->rs_ws = take(row_stats_workspace_bytes(kMaxW, V));
+    c->rs_acc = (double*)take(9 * sizeof(double));
     if (!ok) { set_error(c->err, "psd_create: device pool too small"); return fail(PSD_ENOMEM); }
     CK(hipHostMalloc((void**)&c->stage, (size_t)kStageSlots * kStageSlotBytes, hipHostMallocDefault));
     CK(hipHostMalloc((void**)&c->res, sizeof(RoundResult), hipHostMallocDefault));
@@ -429,6 +441,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     std::vector<float> tr_p, tr_q;  // trace copies
     int C = n_prompt;
     for (int i = 0; i < 3; ++i) c->M[i].len = 0;
+    PSD_HIP(hipMemsetAsync(c->rs_acc, 0, 9 * sizeof(double), c->stream), c->err);
 
     PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
     for (int i = 0; i < 3; ++i)
@@ -461,6 +474,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             if ((rc = run_pass(c, 1, wclass(hq + m), c->QL, false, true)) != PSD_OK) return rc;
             c->timer.end(c->stream);
             st.passes_q++;
+            if ((rc = note_rows(c, 0, c->DL, m)) != PSD_OK) return rc;
+            if ((rc = note_rows(c, 1, c->QL + (size_t)nbuf * V, m + 1)) != PSD_OK) return rc;
             const int bonus = nbuf + m < k2;
             if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage1"), (double)(2 * m + 1) * V * 4);
             c->timer.begin(c->stream, 3);
@@ -505,6 +520,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         if ((rc = run_pass(c, 2, wclass(wT), c->TL, false, true)) != PSD_OK) return rc;
         c->timer.end(c->stream);
         st.passes_t++;
+        if ((rc = note_rows(c, 2, c->TL, k2 + 1)) != PSD_OK) return rc;
         if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k2 + 1) * V * 4);
         c->timer.begin(c->stream, 3);
         rc = accept_launch(c->TL, c->QL, c->win_tok, 1, k2, V, c->prm.T_t, c->prm.temperature, seed, (uint32_t)C, 2u, 1,
@@ -546,6 +562,26 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     return PSD_OK;
 }
 
+extern "C" int psd_set_row_stats(psd_ctx* c, int32_t on) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_row_stats: null context");
+    c->prm.flags = on ? (c->prm.flags | PSD_FLAG_ROW_STATS) : (c->prm.flags & ~PSD_FLAG_ROW_STATS);
+    return PSD_OK;
+}
+
+extern "C" int psd_get_row_stats(psd_ctx* c, double* out) {
+    if (!c || !out) PSD_FAIL(PSD_EINVAL, c ? c->err : tls_error(), "psd_get_row_stats: null pointer");
+    PSD_HIP(hipSetDevice(c->device), c->err);
+    PSD_HIP(hipStreamSynchronize(c->stream), c->err);
+    double h[9];
+    PSD_HIP(hipMemcpy(h, c->rs_acc, sizeof(h), hipMemcpyDeviceToHost), c->err);
+    for (int m = 0; m < 3; ++m) {
+        out[3 * m] = h[3 * m];
+        out[3 * m + 1] = h[3 * m] > 0 ? h[3 * m + 1] / h[3 * m] : 0.0;
+        out[3 * m + 2] = h[3 * m] > 0 ? h[3 * m + 2] / h[3 * m] : 0.0;
+    }
+    return PSD_OK;
+}
+
 extern "C" int psd_set_assisted(psd_ctx* c, int32_t on) {
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_assisted: null context");
     c->prm.flags = on ? (c->prm.flags | PSD_FLAG_ASSISTED) : (c->prm.flags & ~PSD_FLAG_ASSISTED);
@@ -574,6 +610,7 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
     std::vector<float> tr_p, tr_q;
     int C = n_prompt;
     P.len = 0; T.len = 0;
+    PSD_HIP(hipMemsetAsync(c->rs_acc, 0, 9 * sizeof(double), c->stream), c->err);
     PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
     if ((rc = prefill(c, proposer, seq.data(), C - 1)) != PSD_OK) return rc;
     if ((rc = prefill(c, 2, seq.data(), C - 1)) != PSD_OK) return rc;
@@ -602,6 +639,8 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
         if ((rc = run_pass(c, 2, wclass(ht + k), c->TL, false, true)) != PSD_OK) return rc;
         c->timer.end(c->stream);
         st.passes_t++;
+        if ((rc = note_rows(c, proposer, c->QL, k)) != PSD_OK) return rc;
+        if ((rc = note_rows(c, 2, c->TL, k + 1)) != PSD_OK) return rc;
         if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k + 1) * V * 4);
         c->timer.begin(c->stream, 3);
         rc = accept_launch(c->TL, c->QL, c->round_tok, 1, k, V, tau, c->prm.temperature, seed, (uint32_t)C, 2u, 1,

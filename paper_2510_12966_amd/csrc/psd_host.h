@@ -67,4 +67,11 @@ struct SampleCtl {
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
                   const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf);
 
+// Entropy (nats) and largest probability of softmax(row / temperature) for n_rows logits rows (device memory).
+// entropy / max_prob: optional [n_rows] outputs; acc: optional device double[3] {rows, sum H, sum p_max} that is
+// added to.  workspace: row_stats_workspace_bytes(n_rows, vocab) bytes.
+size_t row_stats_workspace_bytes(int n_rows, int vocab);
+int row_stats_launch(const float* logits, int n_rows, int vocab, float temperature, float* entropy, float* max_prob,
+                     double* acc, void* workspace, hipStream_t stream, char* errbuf);
+
 }  // namespace psd

@@ -58,3 +58,15 @@ def test_binding_has_no_fallback_and_does_not_import_the_oracle():
     src = open(b.__file__).read() + open(os.path.join(os.path.dirname(b.__file__), "__init__.py")).read()
     assert "oracle" not in src
     assert "is missing" in src   # a missing library is an error, never a silent CPU path
+
+
+def test_throughput_model_of_section_3_3():
+    import bench
+    # one stage: beta (l + 1) / (l / V_D + 1 / V_Q); hand-computed: 0.8 * 5 / (4 / 1000 + 1 / 400) = 615.38...
+    f_qd, v_psd, v_sd = bench.throughput_model(0.8, 0.9, 4, 8, 1000.0, 400.0, 250.0)
+    assert abs(f_qd - 0.8 * 5 / (4 / 1000 + 1 / 400)) < 1e-9 and abs(f_qd - 615.3846153846) < 1e-6
+    assert abs(v_psd - 0.9 * 9 / (8 / f_qd + 1 / 250)) < 1e-9
+    assert abs(v_sd - 0.9 * 9 / (8 / 400 + 1 / 250)) < 1e-9 and abs(v_sd - 337.5) < 1e-9
+    # a faster first stage can only help, and beta = 1, l -> large approaches the proposer's speed
+    assert bench.throughput_model(1.0, 1.0, 4, 8, 2000.0, 400.0, 250.0)[1] > v_psd
+    assert abs(bench.throughput_model(1.0, 1.0, 10 ** 6, 8, 1000.0, 400.0, 250.0)[0] - 1000.0) < 1.0

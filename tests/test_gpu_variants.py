@@ -171,3 +171,52 @@ def test_assisted_loop_matches_oracle(tiny_stack, T_t, k1, k2, temp, graph):
     fref, _ = oracle.generate(D, Q, T, prompt, n_new, seed, k1, k2, 0.004, T_t, temp)
     assert np.array_equal(fz, fref) or (fz[:3] == fref[:3]).all()
     ctx.close()
+
+
+# ---- per-step statistics of the behaviour analysis (Section 4) ---------------------------------------------
+
+@pytest.mark.parametrize("V", [2, 97, 2048, 4099, 32000, 128256])
+def test_row_stats_match_oracle(V):
+    rng = np.random.default_rng(V)
+    rows = rng.normal(0, 3, (5, V)).astype(np.float32)
+    rows[1] *= 0.01                                  # nearly uniform
+    rows[2, V // 2] += 60.0                          # nearly one-hot
+    if V > 8:
+        rows[3, 3:V - 2:3] = -np.inf                 # masked entries
+    for temp in (1.0, 0.5):
+        h, m = psd.row_stats(rows, temp)
+        for r in range(rows.shape[0]):
+            oh, om = oracle.row_stats(rows[r], temp)
+            assert abs(h[r] - oh) <= 1e-5 * max(1.0, oh), (V, r, temp, h[r], oh)
+            assert abs(m[r] - om) <= 1e-5, (V, r, temp, m[r], om)
+
+
+def test_row_stats_collected_in_the_loop_match_the_oracle_on_the_same_rows(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    n_new, seed, k1, k2 = 40, 6, 4, 8
+    ms = len(prompt) + n_new + k2 + 2
+    ctx = _ctx(cfg, (d, q, t), ms, 0.004, 0.012, k1, k2, flags=psd.FLAG_ROW_STATS)
+    acc = {0: [], 1: [], 2: []}          # oracle statistics of every row the trace hands over, per producing model
+
+    def tap(kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
+        rows = lp if kind != 0 else lp[:1]
+        acc[kind].extend(oracle.row_stats(r, 1.0) for r in rows)
+
+    ctx.set_trace(tap)
+    ctx.generate(prompt, n_new, seed)
+    ctx.set_trace(None)
+    got = ctx.row_stats()
+    for kind, name in ((0, "draft"), (1, "qualifier"), (2, "target")):
+        want = np.array(acc[kind])
+        assert got[name][0] == len(want) > 0
+        assert abs(got[name][1] - want[:, 0].mean()) < 1e-5 and abs(got[name][2] - want[:, 1].mean()) < 1e-6
+    # a flat synthetic stack: every model is close to the uniform law over 512 tokens
+    assert got["target"][1] > 0.9 * np.log(512)
+    # the two-model loop counts the proposer's rows under the proposer
+    ctx.generate_sd(1, 5, 0.0, prompt, 20, seed)
+    g2 = ctx.row_stats()
+    assert g2["draft"][0] == 0 and g2["qualifier"][0] > 0 and g2["target"][0] > 0
+    ctx.set_row_stats(False)
+    ctx.generate(prompt, 8, seed)
+    assert ctx.row_stats()["target"][0] == 0
+    ctx.close()
