@@ -202,53 +202,75 @@ __global__ void accept_clear(AcceptWs w, size_t n_parts) {
 
 enum { SWEEP_ONE_LAUNCH = 0, SWEEP_PARTIALS = 1, SWEEP_DIVERGENCE = 2 };
 
-// kSweepQuads quads of 4 logits per thread and row stay in registers between the two halves (40 registers);
-// the exponentials of the first half are evaluated again in the second, which keeps the kernel at 8 waves
-// per SIMD.  Every wave keeps its own maximum, sum and divergence partial: the only barrier is the one
-// inside row_stats.
-template <int MODE>
-__global__ __launch_bounds__(kAccThreads, 8) void accept_sweep(AcceptShape s, AcceptWs w) {
-    constexpr int T = kAccThreads, QUADS = kSweepQuads, kChunk = kSweepChunk;
-    __shared__ float4 lds[T / 64];
-    // workgroup id = (trial * k + position) * chunks + chunk: the chunks of a row are neighbours in launch
-    // order, and consecutive ids go round the 8 accelerator dies (keeping a row on one die was slower)
-    constexpr int NW = T / 64;
-    const int nsw = s.nsl / NW;
-    const int ch = blockIdx.x % nsw;
-    const int pair = blockIdx.x / nsw;  // trial * k + position
-    const int b = pair / s.k, i = pair - b * s.k;
-    const float* prow = s.lp + ((size_t)b * (s.k + 1) + i) * s.V;
-    const float* qrow = s.lq + (size_t)pair * s.V;
+// ---- the sweep, in pieces -----------------------------------------------------------------------------------
+// A work item is one chunk of kSweepChunk entries of one judged position: item = (trial * k + position) * chunks
+// + chunk, so the chunks of a row are neighbours in item order.  kSweepQuads quads of 4 logits per thread and row
+// stay in registers between the two halves (40 registers); the exponentials of the first half are evaluated
+// again in the second.  Every wave keeps its own maximum, sum and divergence partial: the only barrier is the
+// one inside row_stats.
+struct SweepItem {
+    const float *prow, *qrow;
+    int pair, ch;
+};
+__device__ inline SweepItem sweep_item(const AcceptShape& s, int item) {
+    const int nsw = s.nsl / kSweepWaves;
+    SweepItem it;
+    it.ch = item % nsw;
+    it.pair = item / nsw;  // trial * k + position
+    const int b = it.pair / s.k, i = it.pair - b * s.k;
+    it.prow = s.lp + ((size_t)b * (s.k + 1) + i) * s.V;
+    it.qrow = s.lq + (size_t)it.pair * s.V;
+    return it;
+}
+
+// Issues the loads of an item and nothing else: no branch, so that the compiler can keep them in flight across
+// the arithmetic of another item.  Needs V % 4 == 0 and V >= 4; quads beyond the row are read from the row's last
+// quad instead and masked when they are first used.
+__device__ inline void sweep_load(const AcceptShape& s, const SweepItem& it, float a[kSweepQuads][4], float c[kSweepQuads][4]) {
+#pragma unroll
+    for (int j = 0; j < kSweepQuads; ++j) {
+        const int v = min(it.ch * kSweepChunk + 4 * ((int)threadIdx.x + kAccThreads * j), s.V - 4);
+        const f32x4 ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(it.prow + v));
+        const f32x4 tc = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(it.qrow + v));
+        a[j][0] = ta.x; a[j][1] = ta.y; a[j][2] = ta.z; a[j][3] = ta.w;
+        c[j][0] = tc.x; c[j][1] = tc.y; c[j][2] = tc.z; c[j][3] = tc.w;
+    }
+}
+
+// the same for any vocabulary size and alignment (checked, element-wise where a quad is not whole)
+__device__ inline void sweep_load_any(const AcceptShape& s, const SweepItem& it, float a[kSweepQuads][4], float c[kSweepQuads][4]) {
     const bool vec = (s.V & 3) == 0;
+#pragma unroll
+    for (int j = 0; j < kSweepQuads; ++j) {
+        const int v = it.ch * kSweepChunk + 4 * (threadIdx.x + kAccThreads * j);
+        load4_stream(it.prow, v, s.V, vec, a[j]);
+        load4_stream(it.qrow, v, s.V, vec, c[j]);
+    }
+}
+
+// first half: per-wave base-2 maximum and sum of both rows; PUBLISH: written where the row's other chunks poll
+template <bool PUBLISH>
+__device__ inline void sweep_first(const AcceptShape& s, const AcceptWs& w, const SweepItem& it,
+                                   float a[kSweepQuads][4], float c[kSweepQuads][4]) {
     const float c2 = s.inv_temp * kLog2e;  // logit -> base-2 exponent
-    float a[QUADS][4], c[QUADS][4];
-    if (vec && (ch + 1) * kChunk <= s.V) {  // the whole chunk lies inside the row: no per-quad checks
+    if ((it.ch + 1) * kSweepChunk > s.V) {  // the row ends inside this chunk: entries beyond it carry no probability
 #pragma unroll
-        for (int j = 0; j < QUADS; ++j) {
-            const int v = ch * kChunk + 4 * (threadIdx.x + T * j);
-            const f32x4 ta = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(prow + v));
-            const f32x4 tc = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(qrow + v));
-            a[j][0] = ta.x; a[j][1] = ta.y; a[j][2] = ta.z; a[j][3] = ta.w;
-            c[j][0] = tc.x; c[j][1] = tc.y; c[j][2] = tc.z; c[j][3] = tc.w;
-        }
-    } else {
+        for (int j = 0; j < kSweepQuads; ++j)
+            if (it.ch * kSweepChunk + 4 * ((int)threadIdx.x + kAccThreads * j) >= s.V) {
 #pragma unroll
-        for (int j = 0; j < QUADS; ++j) {
-            const int v = ch * kChunk + 4 * (threadIdx.x + T * j);
-            load4_stream(prow, v, s.V, vec, a[j]);
-            load4_stream(qrow, v, s.V, vec, c[j]);
-        }
+                for (int e = 0; e < 4; ++e) { a[j][e] = -INFINITY; c[j][e] = -INFINITY; }
+            }
     }
     float ma = -INFINITY, mc = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < QUADS; ++j)
+    for (int j = 0; j < kSweepQuads; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) { ma = fmaxf(ma, a[j][e]); mc = fmaxf(mc, c[j][e]); }
     // masked entries only: a finite floor, so that -inf logits give 2^(-inf) = 0 and not NaN
     const float mp = fmaxf(wave_max_dpp(ma) * c2, -kBig), mq = fmaxf(wave_max_dpp(mc) * c2, -kBig);
     float sp = 0.f, sq = 0.f;
 #pragma unroll
-    for (int j = 0; j < QUADS; ++j)
+    for (int j = 0; j < kSweepQuads; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             sp = sp + fast_exp2(fmaf(a[j][e], c2, -mp));
@@ -256,18 +278,24 @@ __global__ __launch_bounds__(kAccThreads, 8) void accept_sweep(AcceptShape s, Ac
         }
     sp = wave_sum_dpp(sp);
     sq = wave_sum_dpp(sq);
-    const int slot = ch * NW + (threadIdx.x >> 6);
-    RowPart* parts = w.part + (size_t)pair * s.nsl;
-    if (MODE != SWEEP_DIVERGENCE && (threadIdx.x & 63) == 0) {
-        st_agent64(&parts[slot].mp, mp, sp);
-        st_agent64(&parts[slot].mq, mq, sq);
+    if (PUBLISH && (threadIdx.x & 63) == 0) {
+        RowPart* slot = w.part + (size_t)it.pair * s.nsl + it.ch * kSweepWaves + (threadIdx.x >> 6);
+        st_agent64(&slot->mp, mp, sp);
+        st_agent64(&slot->mq, mq, sq);
     }
-    if (MODE == SWEEP_PARTIALS) return;
+}
+
+// second half: row statistics from everybody's partials (WAIT: polled), then the divergence partial of the chunk.
+// Returns false in every thread when the bounded wait expired.
+template <bool WAIT>
+__device__ inline bool sweep_second(const AcceptShape& s, const AcceptWs& w, const SweepItem& it,
+                                    const float a[kSweepQuads][4], const float c[kSweepQuads][4], float4* lds) {
+    const float c2 = s.inv_temp * kLog2e;
     RowStats R;
-    if (!row_stats<MODE == SWEEP_ONE_LAUNCH, T>(parts, s.nsl, lds, R)) {
+    if (!row_stats<WAIT, kAccThreads>(w.part + (size_t)it.pair * s.nsl, s.nsl, lds, R)) {
         // the decision kernel reports the expiry; nothing below is waited for by anyone
         if (threadIdx.x == 0) __hip_atomic_store(w.expired, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return;
+        return false;
     }
     // p_v = 2^(a_v c2 - lp), q_v = 2^(c_v c2 - lq);  t = log2 q_v - log2 p_v = (c_v - a_v) c2 + dl
     const float lSp = log2f(R.Sp), lSq = log2f(R.Sq);
@@ -275,7 +303,7 @@ __global__ __launch_bounds__(kAccThreads, 8) void accept_sweep(AcceptShape s, Ac
     const float dl = (R.Mp - R.Mq) + (lSp - lSq);
     float acc = 0.f;
 #pragma unroll
-    for (int j = 0; j < QUADS; ++j)
+    for (int j = 0; j < kSweepQuads; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float p = fast_exp2(fmaf(a[j][e], c2, -lp));
@@ -289,8 +317,26 @@ __global__ __launch_bounds__(kAccThreads, 8) void accept_sweep(AcceptShape s, Ac
             acc = fmaf(q, u - fmaxf(-t, 0.f), acc);
         }
     acc = wave_sum_dpp(acc);
-    if ((threadIdx.x & 63) == 0) w.jsd[(size_t)pair * s.nsl + slot] = (0.5f * kLn2) * acc;
-    if (ch == 0 && threadIdx.x == 0) w.stats[pair] = R;
+    if ((threadIdx.x & 63) == 0)
+        w.jsd[(size_t)it.pair * s.nsl + it.ch * kSweepWaves + (threadIdx.x >> 6)] = (0.5f * kLn2) * acc;
+    if (it.ch == 0 && threadIdx.x == 0) w.stats[it.pair] = R;
+    return true;
+}
+
+// One workgroup per item.  SWEEP_ONE_LAUNCH: publish, wait for the row, finish.  Two launches: SWEEP_PARTIALS stops
+// after the first half, SWEEP_DIVERGENCE repeats the first half without publishing and reads the finished partials.
+// The workgroups of a row are neighbours in launch order and consecutive ids go round the 8 accelerator dies, so
+// the chunks a workgroup waits for are resident with it.
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(kAccThreads, (MODE == SWEEP_ONE_LAUNCH && VEC) ? 8 : 6) void accept_sweep(AcceptShape s, AcceptWs w) {
+    __shared__ float4 lds[kSweepWaves];
+    const SweepItem it = sweep_item(s, blockIdx.x);
+    float a[kSweepQuads][4], c[kSweepQuads][4];
+    if (VEC) sweep_load(s, it, a, c);
+    else sweep_load_any(s, it, a, c);
+    sweep_first<MODE != SWEEP_DIVERGENCE>(s, w, it, a, c);
+    if (MODE == SWEEP_PARTIALS) return;
+    sweep_second<MODE == SWEEP_ONE_LAUNCH>(s, w, it, a, c, lds);
 }
 
 // One workgroup of 16 waves per trial: wave r sums the divergence partials of positions r, r + 16 (lane c
@@ -531,12 +577,18 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     }
     accept_clear<<<(unsigned)((n_parts + 256) / 256), 256, 0, stream>>>(w, n_parts);
     if (pairs > 0) {
-        const int grid = pairs * nsw;
-        if (g_accept_path != 1 && kSweepWaves * nsw <= kSweepMaxSlots) {
-            accept_sweep<SWEEP_ONE_LAUNCH><<<grid, kAccThreads, 0, stream>>>(s, w);
+        const int n_items = pairs * nsw;
+        const bool vec = (vocab & 3) == 0;  // rows are then 16-byte aligned and hold whole quads
+        const bool one_launch = g_accept_path != 1 && kSweepWaves * nsw <= kSweepMaxSlots;
+        if (one_launch) {
+            if (vec) accept_sweep<SWEEP_ONE_LAUNCH, true><<<n_items, kAccThreads, 0, stream>>>(s, w);
+            else accept_sweep<SWEEP_ONE_LAUNCH, false><<<n_items, kAccThreads, 0, stream>>>(s, w);
+        } else if (vec) {
+            accept_sweep<SWEEP_PARTIALS, true><<<n_items, kAccThreads, 0, stream>>>(s, w);
+            accept_sweep<SWEEP_DIVERGENCE, true><<<n_items, kAccThreads, 0, stream>>>(s, w);
         } else {
-            accept_sweep<SWEEP_PARTIALS><<<grid, kAccThreads, 0, stream>>>(s, w);
-            accept_sweep<SWEEP_DIVERGENCE><<<grid, kAccThreads, 0, stream>>>(s, w);
+            accept_sweep<SWEEP_PARTIALS, false><<<n_items, kAccThreads, 0, stream>>>(s, w);
+            accept_sweep<SWEEP_DIVERGENCE, false><<<n_items, kAccThreads, 0, stream>>>(s, w);
         }
     }
     accept_decide<<<n_trials, 1024, 0, stream>>>(s, w, T, seed, position0, stage, out, div_out, n_accepted_out,
