@@ -214,8 +214,8 @@ int psd_accept_assisted(const float* logits_p, const int32_t* tokens, int32_t k,
  *   stream: a hipStream_t passed as void* (NULL = the default stream); the call only enqueues work.
  * Logits must be finite or -inf (-inf entries have probability 0).  The kernels of one row wait for each
  * other inside one launch; that wait is bounded by a clock, and if it ever expires (it cannot while the
- * device runs the launch alone) n_accepted[b] = -1 for every trial of the call: psd_accept and psd_generate
- * turn that into PSD_EHIP. */
+ * device runs the launch alone) n_accepted[b] = -1 for every trial of the call: call psd_set_accept_path(1) and
+ * run it again (psd_accept and the generation calls do that themselves). */
 size_t psd_accept_workspace_bytes(int32_t n_trials, int32_t k, int32_t vocab);
 int psd_accept_batch(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t n_trials,
                      int32_t k, int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
@@ -223,11 +223,16 @@ int psd_accept_batch(const float* logits_p, const float* logits_q, const int32_t
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* How the ACCEPT stage sweeps the logits (Section 3.2 divergence), process-wide; for measurement and tests.
- *   0  automatic: one launch that reads every logit once when a row has at most 256 chunks of 2048 entries,
+ *   0  automatic: one launch that reads every logit once when a row has at most 64 chunks of 5120 entries,
  *      else two launches that read the logits twice
  *   1  always two launches     2  same as 0
- * Both give bit-identical results.  Not thread-safe against running calls.  Returns PSD_EINVAL otherwise. */
+ *   3  test aid: as 0, but a workgroup's wait for the rest of its row expires at once unless it is already
+ *      satisfied, so the expiry handling below can be exercised without a stuck kernel
+ * Both sweeps give bit-identical results.  When a wait expires, psd_accept, psd_generate and psd_generate_sd
+ * switch the process to path 1 and run the stage again; psd_get_accept_path tells which path is in force.
+ * Not thread-safe against running calls.  Returns PSD_EINVAL for other values. */
 int psd_set_accept_path(int32_t path);
+int psd_get_accept_path(void);
 
 /* Fresh sample from softmax(logits / temperature) by the exponential race (how the
  * draft proposes, Figure 1): rows [n_rows][vocab], row r is decided for position position0 + r.

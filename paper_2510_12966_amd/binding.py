@@ -211,6 +211,10 @@ def set_accept_path(path):
     _check(lib().psd_set_accept_path(path))
 
 
+def get_accept_path():
+    return lib().psd_get_accept_path()
+
+
 def accept_workspace_bytes(n_trials, k, vocab):
     return lib().psd_accept_workspace_bytes(n_trials, k, vocab)
 

@@ -41,6 +41,9 @@ constexpr unsigned long long kWaitTicks = 5000000ull;  // 50 ms of the 100 MHz w
 constexpr uint32_t kUnwritten = 0xffffffffu;           // a NaN pattern no maximum can have
 
 static int g_accept_path = 0;   // 0 automatic, 1 two-launch sweep, 2 one-launch sweep where it is allowed
+static unsigned long long g_wait_ticks = kWaitTicks;  // bound of the wait between workgroups (0: test aid)
+
+void accept_wait_expired() { g_accept_path = 1; }
 
 // base-2 maximum of a chunk and its sum of 2^(z - m), for the verifier row (p) and the proposer row (q);
 // each half is published with one 64-bit store and is valid once its m is not the unwritten pattern
@@ -114,6 +117,7 @@ struct AcceptShape {
     int k, V, nch;          // nch: chunks of kAcceptChunk entries (sampling and race kernels)
     float inv_temp;
     int nsl;                // result slots per row of the sweep kernel: one per wave, 4 per workgroup
+    unsigned long long wait_ticks;  // bound of the wait for the other chunks of a row, in wall-clock ticks
 };
 
 struct AcceptWs {  // carved out of the caller's workspace
@@ -140,7 +144,7 @@ __device__ inline unsigned long long ld_agent64(const void* p) {
 // WAIT: the partials come from workgroups of the running kernel; each thread polls its slot until both
 // halves are written, or the clock runs out: then false is returned in every thread.  One barrier.
 template <bool WAIT, int T>
-__device__ inline bool row_stats(const RowPart* parts, int nsl, float4* lds, RowStats& r) {
+__device__ inline bool row_stats(const RowPart* parts, int nsl, unsigned long long wait_ticks, float4* lds, RowStats& r) {
     constexpr int NW = T / 64;
     float mp = -INFINITY, mq = -INFINITY, sp = 0.f, sq = 0.f;
     const int wave = threadIdx.x >> 6;
@@ -156,7 +160,7 @@ __device__ inline bool row_stats(const RowPart* parts, int nsl, float4* lds, Row
                                  __uint_as_float((uint32_t)u1), __uint_as_float((uint32_t)(u1 >> 32))};
                     break;
                 }
-                if (wall_clock64() - t0 > kWaitTicks) { me.mp = INFINITY; break; }  // +inf marks the expiry
+                if (wall_clock64() - t0 >= wait_ticks) { me.mp = INFINITY; break; }  // +inf marks the expiry
                 __builtin_amdgcn_s_sleep(32);
             }
         }
@@ -292,7 +296,7 @@ __device__ inline bool sweep_second(const AcceptShape& s, const AcceptWs& w, con
                                     const float a[kSweepQuads][4], const float c[kSweepQuads][4], float4* lds) {
     const float c2 = s.inv_temp * kLog2e;
     RowStats R;
-    if (!row_stats<WAIT, kAccThreads>(w.part + (size_t)it.pair * s.nsl, s.nsl, lds, R)) {
+    if (!row_stats<WAIT, kAccThreads>(w.part + (size_t)it.pair * s.nsl, s.nsl, s.wait_ticks, lds, R)) {
         // the decision kernel reports the expiry; nothing below is waited for by anyone
         if (threadIdx.x == 0) __hip_atomic_store(w.expired, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return false;
@@ -565,7 +569,7 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     if ((long long)pairs * nsw > 0x7fffffffLL) PSD_FAIL(PSD_EINVAL, errbuf, "accept: n_trials * k * chunks overflows the grid");
     AcceptWs w;
     carve(&w, workspace, n_trials, k, vocab);
-    AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw};
+    AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw, g_wait_ticks};
     const size_t n_parts = (size_t)pairs * nsw * kSweepWaves;
     if (assisted) {
         if (pairs > 0) accept_top<<<dim3(nch, k, n_trials), kAccThreads, 0, stream>>>(s, w);
@@ -750,10 +754,13 @@ int row_stats_launch(const float* logits, int n_rows, int vocab, float temperatu
 using namespace psd;
 
 extern "C" int psd_set_accept_path(int32_t path) {
-    if (path < 0 || path > 2) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_accept_path: path=%d", path);
-    g_accept_path = path;
+    if (path < 0 || path > 3) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_accept_path: path=%d", path);
+    g_accept_path = path == 3 ? 0 : path;
+    g_wait_ticks = path == 3 ? 0ull : kWaitTicks;
     return PSD_OK;
 }
+
+extern "C" int psd_get_accept_path(void) { return g_accept_path; }
 
 extern "C" size_t psd_accept_workspace_bytes(int32_t n_trials, int32_t k, int32_t vocab) {
     if (n_trials < 1 || k < 0 || vocab < 1) return 0;

@@ -82,12 +82,15 @@ static int accept_once(const char* who, const float* logits_p, const float* logi
     }
     int32_t* res = (int32_t*)dres.p;
     const size_t inner = accept_workspace_bytes(1, k, vocab);
-    int rc = accept_launch(p, q, t, 1, k, vocab, T, temperature, seed, position0, stage, take_bonus,
-                           (AcceptOut*)((char*)ws.p + inner), dv, ws.p, inner, nullptr, err, res, res + 1, assisted);
-    if (rc != PSD_OK) return rc;
-    PSD_HIP(hipDeviceSynchronize(), err);
-    int32_t h[2];
-    PSD_HIP(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost), err);
+    int32_t h[2] = {-1, -1};
+    for (int attempt = 0; attempt < 2 && h[0] < 0; ++attempt) {
+        int rc = accept_launch(p, q, t, 1, k, vocab, T, temperature, seed, position0, stage, take_bonus,
+                               (AcceptOut*)((char*)ws.p + inner), dv, ws.p, inner, nullptr, err, res, res + 1, assisted);
+        if (rc != PSD_OK) return rc;
+        PSD_HIP(hipDeviceSynchronize(), err);
+        PSD_HIP(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost), err);
+        if (h[0] < 0) accept_wait_expired();  // not resident as a whole: two launches from now on, and once more
+    }
     if (h[0] < 0) PSD_FAIL(PSD_EHIP, err, "%s: the kernels' bounded wait for each other expired", who);
     if (where == 0) {
         *n_accepted = h[0];

@@ -219,6 +219,30 @@ static int note_rows(psd_ctx* c, int mi, const float* rows, int n) {
     return row_stats_launch(rows, n, c->V, c->prm.temperature, nullptr, nullptr, c->rs_acc + 3 * mi, c->rs_ws, c->stream, c->err);
 }
 
+// One ACCEPT stage on the stream, its result in c->res after one synchronisation.  n_tok: how many of the round's
+// draft tokens to bring back as well.  The kernels of a row wait for each other under a clock; should that wait
+// ever expire (n_accepted = -1: the launch was not resident as a whole), the library switches to the two-launch
+// sweep for good and the stage is run again.
+static int accept_sync(psd_ctx* c, const char* prof_row, const float* lp, const float* lq, const int32_t* toks, int k,
+                       float T, uint64_t seed, uint32_t pos0, uint32_t stage, int bonus, int assisted, int n_tok) {
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of(prof_row), (double)(2 * k + 1) * c->V * 4);
+        c->timer.begin(c->stream, 3);
+        int rc = accept_launch(lp, lq, toks, 1, k, c->V, T, c->prm.temperature, seed, pos0, stage, bonus, c->acc_out,
+                               c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err, nullptr, nullptr, assisted);
+        if (rc != PSD_OK) return rc;
+        c->timer.end(c->stream);
+        if (c->prof.on) c->prof.end(c->stream);
+        PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
+        if (n_tok > 0) PSD_HIP(hipMemcpyAsync(c->res->tok, c->round_tok, n_tok * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
+        if (c->trace && k > 0) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, k * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
+        if ((rc = stage_sync(c)) != PSD_OK) return rc;
+        if (c->res->acc.n_accepted >= 0) return PSD_OK;
+        accept_wait_expired();
+    }
+    PSD_FAIL(PSD_EHIP, c->err, "ACCEPT: the kernels' bounded wait expired and the two-launch sweep failed as well");
+}
+
 static int check_tokens(psd_ctx* c, const int32_t* t, int n) {
     for (int i = 0; i < n; ++i)
         if (t[i] < 0 || t[i] >= c->V) PSD_FAIL(PSD_EINVAL, c->err, "token %d at index %d is outside [0, %d)", t[i], i, c->V);
@@ -477,18 +501,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             if ((rc = note_rows(c, 0, c->DL, m)) != PSD_OK) return rc;
             if ((rc = note_rows(c, 1, c->QL + (size_t)nbuf * V, m + 1)) != PSD_OK) return rc;
             const int bonus = nbuf + m < k2;
-            if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage1"), (double)(2 * m + 1) * V * 4);
-            c->timer.begin(c->stream, 3);
-            rc = accept_launch(c->QL + (size_t)nbuf * V, c->DL, c->round_tok, 1, m, V, c->prm.T_q, c->prm.temperature, seed,
-                               (uint32_t)L, 1u, bonus, c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err,
-                               nullptr, nullptr, assisted);
-            if (rc != PSD_OK) return rc;
-            c->timer.end(c->stream);
-            if (c->prof.on) c->prof.end(c->stream);
-            PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
-            PSD_HIP(hipMemcpyAsync(c->res->tok, c->round_tok, m * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
-            if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, m * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
-            if ((rc = stage_sync(c)) != PSD_OK) return rc;
+            if ((rc = accept_sync(c, "accept stage1", c->QL + (size_t)nbuf * V, c->DL, c->round_tok, m, c->prm.T_q, seed,
+                                  (uint32_t)L, 1u, bonus, assisted, m)) != PSD_OK) return rc;
             const int n = c->res->acc.n_accepted, y = c->res->acc.next_token, has_y = y >= 0;
             if (n < 0 || n > m || (!has_y && (n < m || bonus))) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
             if (c->trace) {
@@ -521,16 +535,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         c->timer.end(c->stream);
         st.passes_t++;
         if ((rc = note_rows(c, 2, c->TL, k2 + 1)) != PSD_OK) return rc;
-        if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k2 + 1) * V * 4);
-        c->timer.begin(c->stream, 3);
-        rc = accept_launch(c->TL, c->QL, c->win_tok, 1, k2, V, c->prm.T_t, c->prm.temperature, seed, (uint32_t)C, 2u, 1,
-                           c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
-        if (rc != PSD_OK) return rc;
-        c->timer.end(c->stream);
-        if (c->prof.on) c->prof.end(c->stream);
-        PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
-        if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, k2 * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
-        if ((rc = stage_sync(c)) != PSD_OK) return rc;
+        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->win_tok, k2, c->prm.T_t, seed, (uint32_t)C, 2u, 1, 0,
+                              0)) != PSD_OK) return rc;
         const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
         if (n < 0 || n > k2 || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
         if (c->trace) {
@@ -641,17 +647,8 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
         st.passes_t++;
         if ((rc = note_rows(c, proposer, c->QL, k)) != PSD_OK) return rc;
         if ((rc = note_rows(c, 2, c->TL, k + 1)) != PSD_OK) return rc;
-        if (c->prof.on) c->prof.begin(c->stream, c->prof.row_of("accept stage2"), (double)(2 * k + 1) * V * 4);
-        c->timer.begin(c->stream, 3);
-        rc = accept_launch(c->TL, c->QL, c->round_tok, 1, k, V, tau, c->prm.temperature, seed, (uint32_t)C, 2u, 1,
-                           c->acc_out, c->acc_div, c->acc_ws, c->acc_ws_bytes, c->stream, c->err);
-        if (rc != PSD_OK) return rc;
-        c->timer.end(c->stream);
-        if (c->prof.on) c->prof.end(c->stream);
-        PSD_HIP(hipMemcpyAsync(&c->res->acc, c->acc_out, sizeof(AcceptOut), hipMemcpyDeviceToHost, c->stream), c->err);
-        PSD_HIP(hipMemcpyAsync(c->res->tok, c->round_tok, k * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
-        if (c->trace) PSD_HIP(hipMemcpyAsync(c->res->div, c->acc_div, k * sizeof(float), hipMemcpyDeviceToHost, c->stream), c->err);
-        if ((rc = stage_sync(c)) != PSD_OK) return rc;
+        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->round_tok, k, tau, seed, (uint32_t)C, 2u, 1, 0, k)) != PSD_OK)
+            return rc;
         const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
         if (n < 0 || n > k || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
         if (c->trace) {

@@ -53,6 +53,9 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
                   hipStream_t stream, char* errbuf, int32_t* n_accepted_out = nullptr,
                   int32_t* next_token_out = nullptr, int assisted = 0);
 
+// Called by whoever reads n_accepted = -1: from now on the sweep runs as two launches (no waiting between workgroups).
+void accept_wait_expired();
+
 // Where the draft chain is: device-resident so that a captured draft step can be replayed unchanged.
 struct SampleCtl {
     uint64_t seed;

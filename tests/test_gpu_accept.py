@@ -186,3 +186,27 @@ def test_accept_masked_entries():
     for x in ([50, 3500, 4000], [200, 2500, 4999]):
         for T in (0.0, 0.3, 1.0):
             _compare(lp, lq, np.array(x, np.int32), T, 1.0, 4, 7, 2, True)
+
+
+def test_expired_wait_falls_back_to_two_launches_and_still_matches_oracle():
+    """A zero wait limit makes every unsatisfied wait between workgroups expire at once (all kernels still run to
+    completion); the host notices, switches to the two-launch sweep and runs the stage again."""
+    V, k = 128256, 6
+    lp, lq, x = _stage_inputs(7, 3, k, V, 0.8, 2)
+    try:
+        psd.set_accept_path(3)
+        for T in (0.0, 0.2):
+            assert _compare(lp, lq, x, T, 1.0, 9, 40, 2, True) in ("exact", "tie")
+        assert psd.get_accept_path() in (0, 1)          # 1 as soon as one wait has expired
+        expired = psd.get_accept_path() == 1
+        psd.set_accept_path(3)
+        # the batched entry point only reports: -1 for every trial of a call in which a wait expired
+        P = [lp] * 4; Q = [lq] * 4; X = [x] * 4
+        na, nt, dv = _batched(P, Q, X, 0.2, 1.0, 9, 40, 2, True)
+        assert (na == -1).all() or (na >= 0).all()
+        expired = expired or (na == -1).all()
+        assert expired                                    # 26 chunks per row: some workgroup always has to wait
+    finally:
+        psd.set_accept_path(0)
+    assert psd.get_accept_path() == 0
+    assert _compare(lp, lq, x, 0.2, 1.0, 9, 40, 2, True) in ("exact", "tie")

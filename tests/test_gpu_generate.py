@@ -193,3 +193,16 @@ def test_paper_shapes_sampled_parity():
         print(f"paper model {which}: max |logit err| {err:.3e}, logit std {ref.std():.3f}", flush=True)
         assert err <= 3e-2
     ctx.close()
+
+
+def test_generation_survives_expired_waits(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx(cfg, (d, q, t), 16 + 32 + 10, 0.004, 0.012, 4, 8)
+    ref, _ = ctx.generate(prompt, 32, 3)
+    try:
+        psd.set_accept_path(3)     # waits expire at once; vocabulary 512 is a single chunk, so nothing ever waits
+        out, _ = ctx.generate(prompt, 32, 3)
+        assert np.array_equal(out, ref)
+    finally:
+        psd.set_accept_path(0)
+    ctx.close()
