@@ -78,6 +78,10 @@ def lib():
                                           C.c_uint32, C.c_int, C.c_void_p]
         L.orc_generate_assisted.restype = C.c_int
         L.orc_generate_assisted.argtypes = L.orc_generate.argtypes
+        L.orc_accept_greedy.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+        L.orc_generate_greedy.restype = C.c_int
+        L.orc_generate_greedy.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.c_void_p, C.c_int,
+                                          C.c_int, C.c_void_p, C.c_void_p]
         L.orc_generate_sd.restype = C.c_int
         L.orc_generate_sd.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_double, C.c_double, C.c_void_p, C.c_int,
                                       C.c_int, C.c_uint64, C.c_void_p, C.c_void_p]
@@ -229,6 +233,29 @@ def generate_assisted(D, Q, T, prompt, n_new, seed, k1, k2, T_t, temperature=1.0
                                      out.ctypes.data, C.byref(st))
     if rc != 0:
         raise ValueError(f"orc_generate_assisted failed: {rc}")
+    return out, st.as_dict()
+
+
+def accept_greedy(logits_p, x, take_bonus=True):
+    """Greedy stage (temperature -> 0 limit): exact match against the verifier's top prediction, no draws."""
+    lp = np.ascontiguousarray(logits_p, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    k, V = lp.shape[0] - 1, lp.shape[1]
+    assert x.size == k
+    res = AcceptResult()
+    lib().orc_accept_greedy(lp.ctypes.data, x.ctypes.data, k, V, int(take_bonus), C.byref(res))
+    return res
+
+
+def generate_greedy(D, Q, T, prompt, n_new, k1, k2):
+    prm = Params(0.0, 0.0, 1.0, k1, k2)
+    pr = np.ascontiguousarray(prompt, dtype=np.int32)
+    out = np.empty(n_new, dtype=np.int32)
+    st = Stats()
+    rc = lib().orc_generate_greedy(D.h, Q.h, T.h, C.byref(prm), pr.ctypes.data, pr.size, n_new, out.ctypes.data,
+                                   C.byref(st))
+    if rc != 0:
+        raise ValueError(f"orc_generate_greedy failed: {rc}")
     return out, st.as_dict()
 
 

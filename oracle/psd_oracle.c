@@ -251,6 +251,25 @@ void orc_accept_assisted(const float* logits_p, const int32_t* x, int k, int V, 
                                          ORC_DRAW_SAMPLE, 0u, &res->margin_race);
 }
 
+static int row_argmax(const float* row, int V) {
+    int top = 0;
+    for (int v = 1; v < V; ++v) if (row[v] > row[top]) top = v;   /* lowest index among equal maxima */
+    return top;
+}
+
+/* Greedy stage: the temperature -> 0 limit of the rule (Section 3.1: with tau = 0 the proposer's top
+ * prediction has to match the verifier's exactly).  All distributions are one-hot there, so proposal i
+ * is accepted iff it equals argmax logits_p[i]; the replacement at the first mismatch n, and the bonus
+ * token of a fully accepted run, are the verifier's top predictions of rows n and k.  No random draws. */
+void orc_accept_greedy(const float* logits_p, const int32_t* x, int k, int V, int take_bonus, orc_accept_result* res) {
+    res->margin_div = INFINITY; res->margin_coin = INFINITY; res->margin_race = 1.0;
+    res->n_fuzzy = 0; res->pad = 0; res->next_token = -1;
+    int n = 0;
+    while (n < k && x[n] == row_argmax(logits_p + (size_t)n * V, V)) ++n;
+    res->n_accepted = n;
+    if (n < k || take_bonus) res->next_token = row_argmax(logits_p + (size_t)n * V, V);
+}
+
 /* Draft proposal: token ~ softmax(logits / temperature) by the race. */
 int orc_sample_row(const float* logits, int V, double temperature, uint64_t seed, uint32_t position,
                    uint32_t purpose, uint32_t stage, double* gap) {
@@ -502,13 +521,16 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
             for (int i = 0; i < m; ++i) {
                 rc |= run_model(D, seq, &lenD, L + i, 1, dl + (size_t)i * V);
                 st->passes_d++;
-                seq[L + i] = orc_sample_row(dl + (size_t)i * V, V, prm->temperature, seed, (uint32_t)(L + i),
-                                            ORC_DRAW_SAMPLE, 0u, NULL);
+                seq[L + i] = assisted == 2 ? row_argmax(dl + (size_t)i * V, V)
+                                           : orc_sample_row(dl + (size_t)i * V, V, prm->temperature, seed, (uint32_t)(L + i),
+                                                            ORC_DRAW_SAMPLE, 0u, NULL);
             }
             rc |= run_model(Q, seq, &lenQ, L + m, m + 1, ql);
             st->passes_q++;
             int bonus = nbuf + m < k2;
-            if (assisted)
+            if (assisted == 2)
+                orc_accept_greedy(ql, seq + L, m, V, bonus, &ar);
+            else if (assisted)
                 orc_accept_assisted(ql, seq + L, m, V, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar);
             else
                 orc_accept(ql, dl, seq + L, m, V, prm->T_q, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar, NULL);
@@ -522,7 +544,10 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
         }
         rc |= run_model(T, seq, &lenT, C + k2, k2 + 1, tl);
         st->passes_t++;
-        orc_accept(tl, qrows, seq + C, k2, V, prm->T_t, prm->temperature, seed, (uint32_t)C, 2u, 1, &ar, NULL);
+        if (assisted == 2)
+            orc_accept_greedy(tl, seq + C, k2, V, 1, &ar);
+        else
+            orc_accept(tl, qrows, seq + C, k2, V, prm->T_t, prm->temperature, seed, (uint32_t)C, 2u, 1, &ar, NULL);
         int n = ar.n_accepted;
         seq[C + n] = ar.next_token;
         lenT = imin(lenT, C + n); lenQ = imin(lenQ, C + n); lenD = imin(lenD, C + n);
@@ -545,6 +570,14 @@ int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm
 int orc_generate_assisted(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
                           int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
     return generate_loop(D, Q, T, prm, 1, prompt, n_prompt, n_new, seed, out_tokens, st);
+}
+
+/* Greedy decoding through the loop (temperature -> 0): proposals and replacements are top predictions,
+ * both stages match tokens exactly; thresholds, temperature and seed play no part.  The output is the
+ * target's own greedy continuation whatever draft and qualifier are. */
+int orc_generate_greedy(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
+                        int n_prompt, int n_new, int32_t* out_tokens, orc_stats* st) {
+    return generate_loop(D, Q, T, prm, 2, prompt, n_prompt, n_new, 0, out_tokens, st);
 }
 
 /* Two-model speculative decoding, the comparison the speed-up is quoted against

@@ -197,3 +197,53 @@ def test_row_stats_closed_forms_and_library():
     assert np.allclose(oracle.row_stats(z), oracle.row_stats(z + np.float32(8.0)), rtol=0, atol=1e-6)
     assert abs(oracle.row_stats(z, 1e6)[0] - math.log(z.size)) < 1e-6
     assert oracle.row_stats(z, 1e-3)[1] > 0.999
+
+
+# ---- greedy decoding through the loop (temperature -> 0 limit, Section 3.1) ------------------------------
+
+def _greedy_continuation(M, prompt, n):
+    seq = list(prompt)
+    for _ in range(n):
+        seq.append(int(M.forward(np.array(seq, dtype=np.int32), 0)[-1].astype(np.float32).argmax()))
+    return np.array(seq[len(prompt):], dtype=np.int32)
+
+
+def test_greedy_loop_is_lossless_for_any_draft_and_qualifier(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    n_new = 40
+    ms = len(prompt) + n_new + 10
+    want = _greedy_continuation(_m(cfg.target, t, cfg, ms), prompt, n_new)
+    for k1, k2 in ((4, 8), (1, 1), (3, 7), (8, 3)):
+        out, st = oracle.generate_greedy(_m(cfg.draft, d, cfg, ms), _m(cfg.qualifier, q, cfg, ms), _m(cfg.target, t, cfg, ms),
+                                         prompt, n_new, k1, k2)
+        assert np.array_equal(out, want)
+        assert st["accepted_q"] <= st["proposed_q"] and st["accepted_t"] <= st["proposed_t"] and st["fuzzy_q"] == 0
+        assert st["proposed_t"] == k2 * st["passes_t"]
+    assert st["accepted_q"] < st["proposed_q"]            # different models do disagree on this stack
+    # identical models: nothing is ever rejected
+    A = lambda: _m(cfg.target, t, cfg, ms)
+    out, st = oracle.generate_greedy(A(), A(), A(), prompt, n_new, 4, 8)
+    assert np.array_equal(out, want) and st["accepted_q"] == st["proposed_q"] and st["accepted_t"] == st["proposed_t"]
+
+
+def test_greedy_stage_is_the_low_temperature_limit_of_the_sampling_stage():
+    rng = np.random.default_rng(5)
+    k, V = 4, 30
+    lp = rng.normal(0, 2, (k + 1, V)).astype(np.float32)
+    lq = rng.normal(0, 2, (k, V)).astype(np.float32)
+    for trial in range(6):
+        x = lp.argmax(1)[:k].astype(np.int32)
+        if trial:
+            x[trial % k] = (x[trial % k] + 3) % V
+        g = oracle.accept_greedy(lp, x, True)
+        # at temperature 1e-3 both distributions are one-hot to 1e-300: divergence 0 or ln 2, coin 0 or 1
+        s, _ = oracle.accept(lp, lq.copy() if trial else lp[:k], x, 0.0, 1e-3, trial, 0, 1, True)
+        if trial == 0:
+            assert g.n_accepted == k == s.n_accepted and g.next_token == s.next_token == lp[k].argmax()
+        else:
+            # proposer rows differ, so compare the greedy rule with the strict-match rule it must equal
+            n = 0
+            while n < k and x[n] == lp[n].argmax():
+                n += 1
+            assert g.n_accepted == n and g.next_token == lp[n].argmax()
+    assert oracle.accept_greedy(lp, lp.argmax(1)[:k], False).next_token == -1
