@@ -218,6 +218,11 @@ def main() -> int:
         baselines["psd_strict_thresholds"] = {"tokens_per_s": r,
                                               "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
                                               "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
+        ctx.set_greedy(True)      # temperature -> 0 limit: top predictions everywhere, exact token match in both stages
+        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), n_new)
+        ctx.set_greedy(False)
+        baselines["psd_greedy"] = {"tokens_per_s": r, "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
+                                   "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
         ctx.set_row_stats(True)   # entropy / confidence per model over one more run (Section 4's two statistics)
         ctx.generate(prompt, min(n_new, 128), seed)
         baselines["row_stats"] = {m: {"rows": v[0], "mean_entropy_nats": round(v[1], 4), "mean_max_prob": round(v[2], 6)}

@@ -91,6 +91,9 @@ enum {
     PSD_FLAG_ASSISTED = 2,          /* qualifier stage of psd_generate as in Section 3.4: a draft token passes iff it is
                                        the qualifier's top prediction, a rejected one is replaced by a sample of the
                                        qualifier's own distribution; T_q is unused */
+    PSD_FLAG_GREEDY = 8,            /* greedy decoding, the temperature -> 0 limit (Section 3.1): proposals, replacements and
+                                       bonus tokens are top predictions, both stages match tokens exactly; thresholds,
+                                       temperature and seed play no part; the output is the target's greedy continuation */
     PSD_FLAG_ROW_STATS = 4,         /* collect entropy and largest probability of every logits row the loops produce
                                        (Section 4, model behaviour analysis); read with psd_get_row_stats */
     PSD_FLAG_SCRAMBLE_PAGES = 0x100 /* test aid: hand out physical KV pages in a shuffled order */
@@ -168,6 +171,10 @@ int psd_row_stats(const float* logits, int32_t n_rows, int32_t vocab, float temp
 int psd_set_row_stats(psd_ctx* ctx, int32_t on);
 int psd_get_row_stats(psd_ctx* ctx, double* out);
 
+/* Switches greedy decoding on or off, as PSD_FLAG_GREEDY does at creation (applies to psd_generate,
+ * psd_generate_sd and psd_generate_plain; captured graphs of the sampling steps are dropped). */
+int psd_set_greedy(psd_ctx* ctx, int32_t on);
+
 /* Switches the qualifier stage of psd_generate between the fuzzy rule (0) and the assisted rule of
  * Section 3.4 (1), as PSD_FLAG_ASSISTED does at creation. */
 int psd_set_assisted(psd_ctx* ctx, int32_t on);
@@ -242,7 +249,8 @@ int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float tempera
 
 /* Trace hook for tests: when set, psd_generate copies the inputs of every draft
  * sample (kind 0, k = 0, logits_p = the draft row) and every ACCEPT (kind 1 / 2 =
- * stage; kind 3 = stage 1 under the assisted rule) back to the host and calls fn after the step has been decided.  All
+ * stage; kind 3 = stage 1 under the assisted rule; greedy decoding: kind 6 = proposal, 4 / 5 = stage 1 / 2)
+ * back to the host and calls fn after the step has been decided.  All
  * pointers are host memory valid during the callback only.  Slow; tests only. */
 typedef void (*psd_trace_fn)(void* user, int32_t kind, uint32_t position0, int32_t k, int32_t take_bonus,
                              const float* logits_p, const float* logits_q, const int32_t* tokens,

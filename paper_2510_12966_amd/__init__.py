@@ -4,7 +4,7 @@ Everything on the decoding path runs inside the HIP library; this package only m
 arguments (ctypes) and offers the seeded synthetic-input generator under ``synth``.
 """
 from .binding import (PsdError, Context, ModelDesc, accept, accept_assisted, row_stats, accept_batch, accept_workspace_bytes, set_accept_path, get_accept_path, sample, lib, DeviceBuffer, dev_sync,
-                      lib_path, F32, BF16, FLAG_GRAPH, FLAG_ASSISTED, FLAG_ROW_STATS, MAX_WIDTH)
+                      lib_path, F32, BF16, FLAG_GRAPH, FLAG_ASSISTED, FLAG_ROW_STATS, FLAG_GREEDY, MAX_WIDTH)
 
 __all__ = ["PsdError", "Context", "ModelDesc", "accept", "accept_assisted", "row_stats", "accept_batch", "accept_workspace_bytes", "set_accept_path", "get_accept_path", "sample", "lib", "DeviceBuffer", "dev_sync",
-           "lib_path", "F32", "BF16", "FLAG_GRAPH", "FLAG_ASSISTED", "FLAG_ROW_STATS", "MAX_WIDTH"]
+           "lib_path", "F32", "BF16", "FLAG_GRAPH", "FLAG_ASSISTED", "FLAG_ROW_STATS", "FLAG_GREEDY", "MAX_WIDTH"]

@@ -12,6 +12,7 @@ F32, BF16 = 0, 1
 FLAG_GRAPH = 1
 FLAG_ASSISTED = 2
 FLAG_ROW_STATS = 4
+FLAG_GREEDY = 8
 MAX_WIDTH = 32
 
 
@@ -97,6 +98,7 @@ def lib():
                                       C.c_uint64, C.c_void_p, C.POINTER(Stats)]
         L.psd_set_assisted.argtypes = [C.c_void_p, C.c_int32]
         L.psd_set_row_stats.argtypes = [C.c_void_p, C.c_int32]
+        L.psd_set_greedy.argtypes = [C.c_void_p, C.c_int32]
         L.psd_get_row_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.psd_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p]
         L.psd_accept_assisted.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
@@ -310,6 +312,9 @@ class Context:
         _check(lib().psd_get_row_stats(self._h, out.ctypes.data), self._h)
         return {name: (int(out[3 * i]), float(out[3 * i + 1]), float(out[3 * i + 2]))
                 for i, name in enumerate(("draft", "qualifier", "target"))}
+
+    def set_greedy(self, on: bool):
+        _check(lib().psd_set_greedy(self._h, int(on)), self._h)
 
     def set_assisted(self, on: bool):
         _check(lib().psd_set_assisted(self._h, int(on)), self._h)

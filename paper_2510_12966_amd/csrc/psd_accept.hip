@@ -125,7 +125,7 @@ struct AcceptWs {  // carved out of the caller's workspace
     float* jsd;          // [B*k][nsl]
     RowStats* stats;     // [B*k] row maxima and sums, written by the row's first chunk
     RacePart* race;      // [B][nch]
-    KeyIdx* top;         // [B*k][nch] per-chunk maximum logit of the verifier rows (assisted stage)
+    KeyIdx* top;         // [B*(k+1)][nch] per-chunk maximum logit of the verifier rows (assisted and greedy stages)
     uint32_t* expired;   // [1] set when a bounded wait ran out
 };
 
@@ -414,30 +414,35 @@ __global__ __launch_bounds__(kAccThreads) void accept_top(AcceptShape s, AcceptW
             if (v + e < s.V) best = better(best, KeyIdx{a[e], v + e});  // equal maxima: lowest index
     }
     best = block_best<4>(best, smk);
-    if (threadIdx.x == 0) w.top[((size_t)b * s.k + i) * s.nch + ch] = best;
+    if (threadIdx.x == 0) w.top[((size_t)b * (s.k + 1) + i) * s.nch + ch] = best;
 }
 
-// one workgroup of 16 waves per trial: wave r reduces the chunk maxima of positions r, r + 16
-__global__ __launch_bounds__(1024) void accept_decide_assisted(AcceptShape s, AcceptWs w, AcceptOut* out, float* div_out,
-                                                               int32_t* n_out, int32_t* tok_out) {
-    __shared__ int s_pass[PSD_MAX_WIDTH];
+// one workgroup of 16 waves per trial: wave r reduces the chunk maxima of rows r, r + 16, ...
+// greedy: rows 0 .. k are reduced and the replacement / bonus token is the top prediction of row n itself
+// (temperature -> 0 limit, Section 3.1); otherwise rows 0 .. k - 1 and the token is drawn by the race kernels.
+__global__ __launch_bounds__(1024) void accept_decide_assisted(AcceptShape s, AcceptWs w, int greedy, int take_bonus,
+                                                               AcceptOut* out, float* div_out, int32_t* n_out,
+                                                               int32_t* tok_out) {
+    __shared__ int s_top[PSD_MAX_WIDTH + 1];
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = wave; i < s.k; i += 16) {
-        const KeyIdx* pr = w.top + ((size_t)b * s.k + i) * s.nch;
+    const int rows = greedy ? s.k + 1 : s.k;
+    for (int i = wave; i < rows; i += 16) {
+        const KeyIdx* pr = w.top + ((size_t)b * (s.k + 1) + i) * s.nch;
         KeyIdx best{-INFINITY, 0x7fffffff};
         for (int c = lane; c < s.nch; c += 64) best = better(best, pr[c]);
         best = wave_best(best);
         if (lane == 0) {
-            s_pass[i] = s.tokens[(size_t)b * s.k + i] == best.idx;
-            if (div_out) div_out[(size_t)b * s.k + i] = -1.f;  // no divergence is evaluated in this stage
+            s_top[i] = best.idx;
+            if (div_out && i < s.k) div_out[(size_t)b * s.k + i] = -1.f;  // no divergence is evaluated in this stage
         }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         int n = 0;
-        while (n < s.k && s_pass[n]) ++n;
-        out[b] = AcceptOut{n, -1, 0, 0};
-        if (n_out) { n_out[b] = n; tok_out[b] = -1; }
+        while (n < s.k && s.tokens[(size_t)b * s.k + n] == s_top[n]) ++n;
+        const int tok = (greedy && (n < s.k || take_bonus)) ? s_top[n] : -1;
+        out[b] = AcceptOut{n, tok, 0, 0};
+        if (n_out) { n_out[b] = n; tok_out[b] = tok; }
     }
 }
 
@@ -542,7 +547,7 @@ static size_t carve(AcceptWs* w, void* base, int n_trials, int k, int vocab) {
     float* jsd = (float*)take(pairs * nsw_max * sizeof(float));
     RowStats* st = (RowStats*)take(pairs * sizeof(RowStats));
     RacePart* race = (RacePart*)take((size_t)n_trials * nch * sizeof(RacePart));
-    KeyIdx* top = (KeyIdx*)take(pairs * nch * sizeof(KeyIdx));
+    KeyIdx* top = (KeyIdx*)take((pairs + n_trials) * nch * sizeof(KeyIdx));
     uint32_t* expired = (uint32_t*)take(sizeof(uint32_t));
     if (w) *w = AcceptWs{part, jsd, st, race, top, expired};
     return off;
@@ -571,11 +576,15 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     carve(&w, workspace, n_trials, k, vocab);
     AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw, g_wait_ticks};
     const size_t n_parts = (size_t)pairs * nsw * kSweepWaves;
-    if (assisted) {
-        if (pairs > 0) accept_top<<<dim3(nch, k, n_trials), kAccThreads, 0, stream>>>(s, w);
-        accept_decide_assisted<<<n_trials, 1024, 0, stream>>>(s, w, out, div_out, n_accepted_out, next_token_out);
-        accept_race<<<dim3(nch, n_trials), kAccThreads, 0, stream>>>(s, w, out, seed, position0, stage, take_bonus, 1);
-        accept_pick<<<n_trials, kAccThreads, 0, stream>>>(s, w, take_bonus, 1, out, next_token_out);
+    if (assisted) {   // 1: assisted stage, 2: greedy stage
+        const int greedy = assisted == 2, rows = greedy ? k + 1 : k;
+        if (rows > 0) accept_top<<<dim3(nch, rows, n_trials), kAccThreads, 0, stream>>>(s, w);
+        accept_decide_assisted<<<n_trials, 1024, 0, stream>>>(s, w, greedy, take_bonus, out, div_out, n_accepted_out,
+                                                               next_token_out);
+        if (!greedy) {
+            accept_race<<<dim3(nch, n_trials), kAccThreads, 0, stream>>>(s, w, out, seed, position0, stage, take_bonus, 1);
+            accept_pick<<<n_trials, kAccThreads, 0, stream>>>(s, w, take_bonus, 1, out, next_token_out);
+        }
         PSD_HIP(hipGetLastError(), errbuf);
         return PSD_OK;
     }
@@ -606,9 +615,10 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
 // ---- fresh samples (draft proposals) ---------------------------------------------------------
 // score_v = z_v / temperature - ln(-ln u_v); token = argmax (the exponential race in log form, so no
 // normalisation pass is needed)
+// greedy: the key is the logit itself (the top prediction; no random numbers)
 __global__ __launch_bounds__(kAccThreads) void sample_partial(const float* logits, int V, int nch, float inv_temp,
                                                               uint64_t seed, uint32_t position0,
-                                                              const SampleCtl* ctl, KeyIdx* parts) {
+                                                              const SampleCtl* ctl, KeyIdx* parts, int greedy) {
     __shared__ KeyIdx smk[4];
     const int ch = blockIdx.x, r = blockIdx.y;
     int row0 = 0;
@@ -623,6 +633,12 @@ __global__ __launch_bounds__(kAccThreads) void sample_partial(const float* logit
         if (v >= V) continue;
         float a[4], u[4];
         load4(row, v, V, vec, a);
+        if (greedy) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (v + e < V) best = better(best, KeyIdx{a[e], v + e});
+            continue;
+        }
         draw4(seed, (uint32_t)(v >> 2), pos, DRAW_SAMPLE, 0u, u);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -642,14 +658,14 @@ __global__ void sample_final(const KeyIdx* parts, int nch, int32_t* tokens_out) 
 }
 
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
-                  const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf) {
+                  const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf, int greedy) {
     if (!logits || !tokens_out || !partial) PSD_FAIL(PSD_EINVAL, errbuf, "sample: null pointer");
     if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
         PSD_FAIL(PSD_EINVAL, errbuf, "sample: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
     if ((uintptr_t)logits & 15) PSD_FAIL(PSD_EINVAL, errbuf, "sample: logits must be 16-byte aligned");
     const int nch = accept_chunks(vocab);
     sample_partial<<<dim3(nch, n_rows), kAccThreads, 0, stream>>>(logits, vocab, nch, 1.0f / temperature, seed,
-                                                                   position0, ctl, (KeyIdx*)partial);
+                                                                   position0, ctl, (KeyIdx*)partial, greedy);
     sample_final<<<n_rows, 64, 0, stream>>>((const KeyIdx*)partial, nch, tokens_out);
     PSD_HIP(hipGetLastError(), errbuf);
     return PSD_OK;

@@ -155,7 +155,7 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
         if (with_sample) {
             if (prof && prof->on) prof->begin(c->stream, prof->row_of("sample draft"), (double)c->V * 4);
             rc = sample_launch(logits, 1, c->V, c->prm.temperature, 0, 0, c->chain, c->samp_tok, c->samp_part,
-                               c->stream, c->err);
+                               c->stream, c->err, (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0);
             if (rc != PSD_OK) return rc;
             draft_advance<<<1, 64, 0, c->stream>>>(c->samp_tok, c->chain, M.desc, c->M[verifier].desc, c->round_tok);
             if (prof && prof->on) prof->end(c->stream);
@@ -451,7 +451,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_generate: null context");
     if (!prompt || n_prompt < 1 || n_new < 0 || (n_new > 0 && !out_tokens)) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate: bad argument");
     const int k1 = c->prm.k1, k2 = c->prm.k2, V = c->V;
-    const int assisted = (c->prm.flags & PSD_FLAG_ASSISTED) ? 1 : 0;
+    const int greedy = (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0;
+    const int assisted = greedy ? 2 : (c->prm.flags & PSD_FLAG_ASSISTED) ? 1 : 0;  // rule of the qualifier stage
     const int cap = n_prompt + n_new + k2 + 2;
     if (cap > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate: n_prompt + n_new + k2 + 2 = %d exceeds max_seq %d", cap, c->prm.max_seq);
     int rc = check_tokens(c, prompt, n_prompt);
@@ -509,8 +510,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
                 if ((rc = copy_rows_to_host(c, tr_q, c->DL, m)) != PSD_OK) return rc;
                 if ((rc = copy_rows_to_host(c, tr_p, c->QL + (size_t)nbuf * V, m + 1)) != PSD_OK) return rc;
                 for (int i = 0; i < m; ++i)
-                    c->trace(c->trace_user, 0, (uint32_t)(L + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
-                c->trace(c->trace_user, assisted ? 3 : 1, (uint32_t)L, m, bonus, tr_p.data(), tr_q.data(), c->res->tok, n, y,
+                    c->trace(c->trace_user, greedy ? 6 : 0, (uint32_t)(L + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
+                c->trace(c->trace_user, greedy ? 4 : assisted ? 3 : 1, (uint32_t)L, m, bonus, tr_p.data(), tr_q.data(), c->res->tok, n, y,
                          c->res->div);
             }
             for (int i = 0; i < n; ++i) seq[L + i] = c->res->tok[i];
@@ -535,14 +536,14 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         c->timer.end(c->stream);
         st.passes_t++;
         if ((rc = note_rows(c, 2, c->TL, k2 + 1)) != PSD_OK) return rc;
-        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->win_tok, k2, c->prm.T_t, seed, (uint32_t)C, 2u, 1, 0,
-                              0)) != PSD_OK) return rc;
+        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->win_tok, k2, c->prm.T_t, seed, (uint32_t)C, 2u, 1,
+                              greedy ? 2 : 0, 0)) != PSD_OK) return rc;
         const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
         if (n < 0 || n > k2 || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
         if (c->trace) {
             if ((rc = copy_rows_to_host(c, tr_p, c->TL, k2 + 1)) != PSD_OK) return rc;
             if ((rc = copy_rows_to_host(c, tr_q, c->QL, k2)) != PSD_OK) return rc;
-            c->trace(c->trace_user, 2, (uint32_t)C, k2, 1, tr_p.data(), tr_q.data(), seq.data() + C, n, y, c->res->div);
+            c->trace(c->trace_user, greedy ? 5 : 2, (uint32_t)C, k2, 1, tr_p.data(), tr_q.data(), seq.data() + C, n, y, c->res->div);
         }
         seq[C + n] = y;
         T.len = std::min(T.len + wT, C + n);
@@ -588,6 +589,18 @@ extern "C" int psd_get_row_stats(psd_ctx* c, double* out) {
     return PSD_OK;
 }
 
+extern "C" int psd_set_greedy(psd_ctx* c, int32_t on) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_greedy: null context");
+    const int32_t before = c->prm.flags;
+    c->prm.flags = on ? (c->prm.flags | PSD_FLAG_GREEDY) : (c->prm.flags & ~PSD_FLAG_GREEDY);
+    if (before != c->prm.flags) {   // captured sampling steps hold the other rule
+        PSD_HIP(hipSetDevice(c->device), c->err);
+        PSD_HIP(hipStreamSynchronize(c->stream), c->err);
+        drop_graphs(c);
+    }
+    return PSD_OK;
+}
+
 extern "C" int psd_set_assisted(psd_ctx* c, int32_t on) {
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_assisted: null context");
     c->prm.flags = on ? (c->prm.flags | PSD_FLAG_ASSISTED) : (c->prm.flags & ~PSD_FLAG_ASSISTED);
@@ -603,6 +616,7 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
     if (k < 1 || k > c->k2cap) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate_sd: k=%d outside [1, %d]", k, c->k2cap);
     if (!(tau >= 0.f)) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate_sd: tau=%g", tau);
     const int V = c->V;
+    const int greedy = (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0;
     const int cap = n_prompt + n_new + k + 2;
     if (cap > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate_sd: n_prompt + n_new + k + 2 = %d exceeds max_seq %d", cap, c->prm.max_seq);
     int rc = check_tokens(c, prompt, n_prompt);
@@ -647,7 +661,8 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
         st.passes_t++;
         if ((rc = note_rows(c, proposer, c->QL, k)) != PSD_OK) return rc;
         if ((rc = note_rows(c, 2, c->TL, k + 1)) != PSD_OK) return rc;
-        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->round_tok, k, tau, seed, (uint32_t)C, 2u, 1, 0, k)) != PSD_OK)
+        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->round_tok, k, tau, seed, (uint32_t)C, 2u, 1,
+                              greedy ? 2 : 0, k)) != PSD_OK)
             return rc;
         const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
         if (n < 0 || n > k || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
@@ -655,8 +670,8 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
             if ((rc = copy_rows_to_host(c, tr_q, c->QL, k)) != PSD_OK) return rc;
             if ((rc = copy_rows_to_host(c, tr_p, c->TL, k + 1)) != PSD_OK) return rc;
             for (int i = 0; i < k; ++i)
-                c->trace(c->trace_user, 0, (uint32_t)(C + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
-            c->trace(c->trace_user, 2, (uint32_t)C, k, 1, tr_p.data(), tr_q.data(), c->res->tok, n, y, c->res->div);
+                c->trace(c->trace_user, greedy ? 6 : 0, (uint32_t)(C + i), 0, 0, tr_q.data() + (size_t)i * V, nullptr, nullptr, 0, c->res->tok[i], nullptr);
+            c->trace(c->trace_user, greedy ? 5 : 2, (uint32_t)C, k, 1, tr_p.data(), tr_q.data(), c->res->tok, n, y, c->res->div);
         }
         for (int i = 0; i < n; ++i) seq[C + i] = c->res->tok[i];
         seq[C + n] = y;
@@ -707,7 +722,8 @@ extern "C" int psd_generate_plain(psd_ctx* c, int32_t which, const int32_t* prom
         fill_desc(d, seq.data(), M.len, L, 0, 1, 0);
         if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
         if ((rc = run_pass(c, which, 4, c->HL, false)) != PSD_OK) return rc;
-        if ((rc = sample_launch(c->HL, 1, c->V, c->prm.temperature, seed, (uint32_t)L, nullptr, c->samp_tok, c->samp_part, c->stream, c->err)) != PSD_OK) return rc;
+        if ((rc = sample_launch(c->HL, 1, c->V, c->prm.temperature, seed, (uint32_t)L, nullptr, c->samp_tok, c->samp_part, c->stream, c->err,
+                                (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0)) != PSD_OK) return rc;
         PSD_HIP(hipMemcpyAsync(c->res->tok, c->samp_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);
         if ((rc = stage_sync(c)) != PSD_OK) return rc;
         seq[L] = c->res->tok[0];

@@ -46,7 +46,8 @@ size_t accept_workspace_bytes(int n_trials, int k, int vocab);
 // n_accepted_out / next_token_out (optional, both or neither): plain [n_trials] copies of the two results.
 // out[b].n_accepted = -1 when the kernels' bounded wait for each other expired.
 // assisted: strict match against the verifier's top prediction, replacement draw from the verifier's row
-// (Section 3.4); logits_q and T are then unused and div_out receives -1.
+// (Section 3.4); logits_q and T are then unused and div_out receives -1.  assisted = 2: greedy stage, the
+// temperature -> 0 limit (Section 3.1): the same match, replacement and bonus are the verifier's top predictions.
 int accept_launch(const float* logits_p, const float* logits_q, const int32_t* tokens, int n_trials, int k,
                   int vocab, float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage,
                   int take_bonus, AcceptOut* out, float* div_out, void* workspace, size_t workspace_bytes,
@@ -67,8 +68,10 @@ struct SampleCtl {
 
 // Fresh samples: row r -> token for position position0 + r.  partial: n_rows * accept_chunks(vocab) * 8 bytes.
 // ctl (optional, device): when non-null, seed / position0 / first logits row come from *ctl instead.
+// greedy: the top prediction of every row instead of a sample.
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
-                  const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf);
+                  const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf,
+                  int greedy = 0);
 
 // Entropy (nats) and largest probability of softmax(row / temperature) for n_rows logits rows (device memory).
 // entropy / max_prob: optional [n_rows] outputs; acc: optional device double[3] {rows, sum H, sum p_max} that is

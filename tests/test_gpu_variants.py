@@ -220,3 +220,67 @@ def test_row_stats_collected_in_the_loop_match_the_oracle_on_the_same_rows(tiny_
     ctx.generate(prompt, 8, seed)
     assert ctx.row_stats()["target"][0] == 0
     ctx.close()
+
+
+# ---- greedy decoding (temperature -> 0 limit, Section 3.1) --------------------------------------------------
+
+class GreedyReplay:
+    """Every proposal and every stage of a greedy run decided again by the oracle on the GPU's own logits: exact."""
+
+    def __init__(self):
+        self.kinds = 0
+
+    def __call__(self, kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
+        self.kinds |= 1 << kind
+        if kind == 6:
+            assert nxt == int(lp[0].argmax())
+            return
+        assert kind in (4, 5)
+        res = oracle.accept_greedy(lp, tk, bool(bonus))
+        assert (n_acc, nxt) == (res.n_accepted, res.next_token), (kind, pos0, n_acc, nxt, res.n_accepted, res.next_token)
+
+
+@pytest.mark.parametrize("graph", [0, psd.FLAG_GRAPH])
+@pytest.mark.parametrize("k1,k2", [(4, 8), (1, 1), (3, 7), (8, 3)])
+def test_greedy_loop_matches_oracle_stage_by_stage(tiny_stack, k1, k2, graph):
+    cfg, d, q, t, prompt = tiny_stack
+    n_new = 40
+    ms = len(prompt) + n_new + k2 + 2
+    ctx = _ctx(cfg, (d, q, t), ms, 0.3, 0.2, k1, k2, flags=graph | psd.FLAG_GREEDY)
+    rp = GreedyReplay()
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, 0)
+    ctx.set_trace(None)
+    assert rp.kinds == (1 << 4) | (1 << 5) | (1 << 6)
+    assert st["fuzzy_q"] == 0 and st["fuzzy_t"] == 0 and st["proposed_t"] == k2 * st["passes_t"]
+    ref, ost = oracle.generate_greedy(_om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms),
+                                      prompt, n_new, k1, k2)
+    if np.array_equal(out, ref):
+        for key in ("proposed_q", "accepted_q", "proposed_t", "accepted_t", "passes_d", "passes_q", "passes_t"):
+            assert st[key] == ost[key], key
+    else:   # fp32 logits against fp64 logits: two top logits within rounding of each other may swap
+        assert (out[:4] == ref[:4]).all()
+    # the seed plays no part; sampling comes back when the rule is switched off
+    out2, _ = ctx.generate(prompt, n_new, 12345)
+    assert np.array_equal(out, out2)
+    ctx.set_greedy(False)
+    smp, _ = ctx.generate(prompt, n_new, 1)
+    assert not np.array_equal(smp, out)
+    ctx.close()
+
+
+def test_greedy_loop_is_lossless_on_a_bf16_stack():
+    """bf16 models give a position the same logits bits at every pass width, so the loop's output must equal the
+    target's own greedy continuation on the GPU exactly, for the three-model loop and the two-model baseline."""
+    cfg = synth.CONFIGS["small"]
+    d, q, t, prompt = synth.build_stack(cfg)
+    n_new = 40
+    ctx = _ctx(cfg, (d, q, t), cfg.n_prompt + n_new + cfg.k2 + 2, cfg.T_q, cfg.T_t, cfg.k1, cfg.k2,
+               flags=psd.FLAG_GRAPH | psd.FLAG_GREEDY)
+    want, _ = ctx.generate_plain(2, prompt, n_new, 0)
+    out, st = ctx.generate(prompt, n_new, 0)
+    assert np.array_equal(out, want)
+    sd, st2 = ctx.generate_sd(1, cfg.k1, 0.0, prompt, n_new, 0)
+    assert np.array_equal(sd, want)
+    print("greedy small stack:", st, st2, flush=True)
+    ctx.close()
