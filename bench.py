@@ -213,13 +213,13 @@ def main() -> int:
         baselines["psd_a"] = {"tokens_per_s": r, "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
                               "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
         ctx.set_decoding(0.0, 0.0, cfg.k1, cfg.k2, cfg.temperature)
-        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), n_new)
+        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), min(n_new, 128))
         ctx.set_decoding(cfg.T_q, cfg.T_t, cfg.k1, cfg.k2, cfg.temperature)
         baselines["psd_strict_thresholds"] = {"tokens_per_s": r,
                                               "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
                                               "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
         ctx.set_greedy(True)      # temperature -> 0 limit: top predictions everywhere, exact token match in both stages
-        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), n_new)
+        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), min(n_new, 64))
         ctx.set_greedy(False)
         baselines["psd_greedy"] = {"tokens_per_s": r, "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
                                    "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
