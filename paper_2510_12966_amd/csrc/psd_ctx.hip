@@ -17,7 +17,7 @@
 namespace psd {
 
 constexpr int kStageSlots = 64;
-constexpr int kStageSlotBytes = 256;
+constexpr int kStageSlotBytes = 1024;  // a pass descriptor with 128 token ids fits
 
 struct RoundResult {  // pinned host mirror of what a round leaves on the device
     AcceptOut acc;
@@ -125,7 +125,7 @@ static int stage_sync(psd_ctx* c) {
     return PSD_OK;
 }
 
-// copies `bytes` (<= 256) of host data to device memory in stream order through a pinned ring slot
+// copies `bytes` (<= 1024) of host data to device memory in stream order through a pinned ring slot
 static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
     if (bytes > kStageSlotBytes) PSD_FAIL(PSD_EINVAL, c->err, "internal: staging slot overflow");
     if (c->stage_since_sync >= kStageSlots - 1) {
@@ -197,17 +197,17 @@ static void fill_desc(PassDesc& d, const int32_t* seq, int from, int to, int ext
     for (int i = from; i < to; ++i) d.tok[i - from] = seq[i];
 }
 
-// ingests seq[M.len, upto) with no logits, in chunks of up to 32 tokens
+// ingests seq[M.len, upto) with no logits, in chunks of up to 128 (bf16 models) or 32 tokens
 static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
     Model& M = c->M[mi];
     while (M.len < upto) {
-        const int w = std::min(kMaxW, upto - M.len);
+        const int w = std::min(M.dtype == PSD_BF16 ? kCols : kMaxW, upto - M.len);
         int rc = model_map_pages(M, M.len, M.len + w, c->stream, c->err);
         if (rc != PSD_OK) return rc;
         PassDesc d;
         fill_desc(d, seq, M.len, M.len + w, 0, 0, 0);
         if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
-        if ((rc = run_pass(c, mi, wclass(w), nullptr, false)) != PSD_OK) return rc;
+        if ((rc = run_pass(c, mi, w > kMaxW ? kCols : wclass(w), nullptr, false)) != PSD_OK) return rc;
         M.len += w;
     }
     return PSD_OK;
@@ -427,8 +427,9 @@ extern "C" int psd_kernel_stats(psd_ctx* c, psd_kernel_stat* out, int32_t cap) {
 extern "C" int psd_forward(psd_ctx* c, int32_t which, const int32_t* tokens, int32_t w, int32_t pos0, float* logits_out) {
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_forward: null context");
     if (which < 0 || which > 2 || !tokens) PSD_FAIL(PSD_EINVAL, c->err, "psd_forward: bad argument");
-    if (w < 1 || w > kMaxW) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: width %d outside [1, %d]", w, kMaxW);
     Model& M = c->M[which];
+    const int wcap = (!logits_out && M.dtype == PSD_BF16) ? kCols : kMaxW;   // wider passes only ingest
+    if (w < 1 || w > wcap) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: width %d outside [1, %d]", w, wcap);
     if (pos0 < 0 || pos0 + w > M.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: positions [%d, %d) exceed max_seq %d", pos0, pos0 + w, M.max_seq);
     if (pos0 > M.len) PSD_FAIL(PSD_EINVAL, c->err, "psd_forward: pos0 %d but only %d KV rows are valid", pos0, M.len);
     int rc = check_tokens(c, tokens, w);
@@ -439,7 +440,7 @@ extern "C" int psd_forward(psd_ctx* c, int32_t which, const int32_t* tokens, int
     fill_desc(d, tokens, 0, w, 0, logits_out ? w : 0, 0);
     d.pos0 = pos0;
     if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
-    if ((rc = run_pass(c, which, wclass(w), logits_out ? c->HL : nullptr, false)) != PSD_OK) return rc;
+    if ((rc = run_pass(c, which, w > kMaxW ? kCols : wclass(w), logits_out ? c->HL : nullptr, false)) != PSD_OK) return rc;
     M.len = pos0 + w;
     if ((rc = stage_sync(c)) != PSD_OK) return rc;
     if (logits_out) PSD_HIP(hipMemcpy(logits_out, c->HL, (size_t)w * c->V * sizeof(float), hipMemcpyDeviceToHost), c->err);

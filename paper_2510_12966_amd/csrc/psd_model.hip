@@ -23,15 +23,16 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_LOGITS = 2 };
 
 // ---- operand packing ----------------------------------------------------------------------------
-// GEMM input X[c][f] (c < 32 tokens, f < K features), bf16 path: [K/32][2 col tiles][hi, lo][64 lanes][8],
+// GEMM input X[c][f] (c < 16 CT tokens, f < K features), bf16 path: [K/32][CT col tiles][hi, lo][64 lanes][8]
+// (CT = 2 for passes of up to 32 tokens, 8 for the 128-token passes that ingest a prompt),
 // lane = ((f % 32) / 8) * 16 + c % 16: exactly the B operand of v_mfma_f32_16x16x32_bf16.
 // fp32 path: plain rows [c][K].
-template <bool BF16>
+template <bool BF16, int CT = 2>
 __device__ inline void pack_store(void* xb, int K, int c, int f, float v) {
     if constexpr (BF16) {
         const int ks = f >> 5, g = (f & 31) >> 3, e = f & 7, t = c >> 4, cc = c & 15;
         uint16_t* p = (uint16_t*)xb;
-        const size_t base = ((((size_t)ks * 2 + t) * 2) * 64 + g * 16 + cc) * 8 + e;
+        const size_t base = ((((size_t)ks * CT + t) * 2) * 64 + g * 16 + cc) * 8 + e;
         const uint16_t hi = f32_to_bf16(v);
         p[base] = hi;
         p[base + 64 * 8] = f32_to_bf16(v - bf16_to_f32(hi));
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(256) void attn_partial(const float* qkv, const Pass
     float* p = ps + wave * kAttnSplit;
     for (int c = wave; c < w; c += 4) {
         const int visible = min(nkeys, pos0 + c + 1 - key0);
-        float* out = part + (((size_t)split * kMaxW + c) * H + h) * (hd + 2);
+        float* out = part + (((size_t)split * kCols + c) * H + h) * (hd + 2);
         if (visible <= 0) {
             if (lane == 0) { out[0] = -INFINITY; out[1] = 0.f; }
             continue;
@@ -250,10 +251,10 @@ __global__ void attn_combine_pack(const float* part, const PassDesc* desc, void*
     if (c >= desc->w) return;
     const int nsp = (desc->pos0 + c + kAttnSplit) / kAttnSplit;  // splits holding keys <= pos0 + c
     float M = -INFINITY;
-    for (int s = 0; s < nsp; ++s) M = fmaxf(M, part[(((size_t)s * kMaxW + c) * H + h) * (hd + 2)]);
+    for (int s = 0; s < nsp; ++s) M = fmaxf(M, part[(((size_t)s * kCols + c) * H + h) * (hd + 2)]);
     float Lsum = 0.f, o = 0.f;
     for (int s = 0; s < nsp; ++s) {
-        const float* pr = part + (((size_t)s * kMaxW + c) * H + h) * (hd + 2);
+        const float* pr = part + (((size_t)s * kCols + c) * H + h) * (hd + 2);
         const float f = expf(pr[0] - M);
         Lsum += pr[1] * f;
         o += pr[2 + i] * f;
@@ -266,7 +267,7 @@ __global__ void attn_combine_pack(const float* part, const PassDesc* desc, void*
 // i .. i + N - 1.
 template <int N>
 __device__ inline void attn_merge(const float* part, int nsp, int c, int head, int H, int hd, int i, float out[N]) {
-    const size_t stride = (size_t)kMaxW * H * (hd + 2);
+    const size_t stride = (size_t)kCols * H * (hd + 2);
     const float* p0 = part + ((size_t)c * H + head) * (hd + 2);
     float M = -INFINITY, Lsum = 0.f;
 #pragma unroll
@@ -340,11 +341,11 @@ enum { EPI_QKV = 10, EPI_SWIGLU = 11 };
 
 struct GemmArgs {
     const u32x4* Wt;       // tiled weights [Npad/16][KS][64] x 16 B
-    const u32x4* XB;       // packed activations [KS][2][2][64] x 16 B
+    const u32x4* XB;       // packed activations [KS][CT][2][64] x 16 B
     int N, KS;
     int wcap;              // widest pass this launch is meant for (4, 16 or 32): operand columns >= wcap are not loaded
     const PassDesc* desc;
-    // rms scale of the input (EPI_QKV, EPI_SWIGLU, EPI_LOGITS): partial sums of squares [d/16][32]
+    // rms scale of the input (EPI_QKV, EPI_SWIGLU, EPI_LOGITS): partial sums of squares [d/16][16 CT]
     const float* ss_in;
     int ss_tiles;
     float inv_d, eps;
@@ -353,7 +354,7 @@ struct GemmArgs {
     int ldy;
     void* xb_out;          // RESID / SWIGLU: operand of the next GEMM
     const float* gain_out; // RESID: gain of the RMSNorm that follows
-    float* ss_out;         // RESID: [N/16][32]
+    float* ss_out;         // RESID: [N/16][16 CT]
     // QKV only
     const float2* rope;
     uint16_t* kv;
@@ -362,18 +363,20 @@ struct GemmArgs {
 };
 
 // stores 4 (or 2) consecutive features of column c into a packed operand
+template <int CT>
 __device__ inline void pack4(void* xb, int c, int f0, const float v[4]) {
     const int ks = f0 >> 5, gq = (f0 & 31) >> 3, e = f0 & 7, t = c >> 4, cc = c & 15;
-    uint16_t* p = (uint16_t*)xb + ((((size_t)ks * 2 + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
+    uint16_t* p = (uint16_t*)xb + ((((size_t)ks * CT + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
     uint16_t hi[4], lo[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) { hi[r] = f32_to_bf16(v[r]); lo[r] = f32_to_bf16(v[r] - bf16_to_f32(hi[r])); }
     *reinterpret_cast<uint2*>(p) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
     *reinterpret_cast<uint2*>(p + 512) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
 }
+template <int CT>
 __device__ inline void pack2(void* xb, int c, int f0, float v0, float v1) {
     const int ks = f0 >> 5, gq = (f0 & 31) >> 3, e = f0 & 7, t = c >> 4, cc = c & 15;
-    uint16_t* p = (uint16_t*)xb + ((((size_t)ks * 2 + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
+    uint16_t* p = (uint16_t*)xb + ((((size_t)ks * CT + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
     const uint16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
     const uint16_t l0 = f32_to_bf16(v0 - bf16_to_f32(h0)), l1 = f32_to_bf16(v1 - bf16_to_f32(h1));
     *reinterpret_cast<uint32_t*>(p) = h0 | ((uint32_t)h1 << 16);
@@ -381,7 +384,7 @@ __device__ inline void pack2(void* xb, int c, int f0, float v0, float v1) {
 }
 
 // value tile of one lane: rows n0 + 4 g + r (r = 0..3) of column c
-template <int EPI>
+template <int EPI, int CT>
 __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w, f32x4 v, float rs) {
     const int n = tile * 16 + g * 4;
     if constexpr (EPI == EPI_LOGITS) {
@@ -402,15 +405,15 @@ __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w
         *reinterpret_cast<float4*>(dst) = o;
         const float4 gn = *reinterpret_cast<const float4*>(a.gain_out + n);
         const float pk[4] = {o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w};
-        pack4(a.xb_out, c, n, pk);
+        pack4<CT>(a.xb_out, c, n, pk);
         float ss = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
         ss += __shfl_xor(ss, 16, kWave);
         ss += __shfl_xor(ss, 32, kWave);
-        if (g == 0) a.ss_out[tile * 32 + c] = ss;
+        if (g == 0) a.ss_out[tile * (16 * CT) + c] = ss;
     } else if constexpr (EPI == EPI_SWIGLU) {
         // weight rows are interleaved: tile row 2e = gate of feature 8 tile + e, tile row 2e + 1 = its up row
         const float g0 = v[0] * rs, u0 = v[1] * rs, g1 = v[2] * rs, u1 = v[3] * rs;
-        pack2(a.xb_out, c, tile * 8 + g * 2, g0 / (1.f + expf(-g0)) * u0, g1 / (1.f + expf(-g1)) * u1);
+        pack2<CT>(a.xb_out, c, tile * 8 + g * 2, g0 / (1.f + expf(-g0)) * u0, g1 / (1.f + expf(-g1)) * u1);
     } else if constexpr (EPI == EPI_QKV) {
         // weight rows are permuted inside every head: tile row 2e, 2e + 1 = rotary pair (j, j + hd/2), j = 8 t + e
         const int hd = a.hd, half = hd >> 1;
@@ -457,14 +460,15 @@ __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w
 // Small projections get more waves and fewer tiles per workgroup so that enough loads are in flight.
 // The rms scale of the input is gathered on the side: every thread loads a few sum-of-squares partials before
 // the K loop and they are folded through LDS, in a fixed order, when the loop is done.
-template <int NT, int NW, int RT, int EPI>
+template <int NT, int NW, int RT, int EPI, int CT>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
-    __shared__ f32x4 red[NW - 1][RT][NT][64];
-    __shared__ float ssp[4 * NW][16 * NT];
+    constexpr int TG = NT > 2 ? 2 : NT;   // column tiles whose partials cross LDS together
+    __shared__ f32x4 red[NW - 1][RT][TG][64];
+    constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
+    __shared__ float ssp[kScaled ? 4 * NW : 1][16 * NT];
     const int tile0 = blockIdx.x * RT, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int k0 = (int)(((long)a.KS * wave) / NW), k1 = (int)(((long)a.KS * (wave + 1)) / NW);
     const int g = lane >> 4, cc = lane & 15;
-    constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
     float ss_mine[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) ss_mine[t] = 0.f;
@@ -473,12 +477,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
 #pragma unroll 8
-            for (int st = gi; st < a.ss_tiles; st += 4 * NW) ss_mine[t] += a.ss_in[st * 32 + t * 16 + cc];
+            for (int st = gi; st < a.ss_tiles; st += 4 * NW) ss_mine[t] += a.ss_in[st * (16 * CT) + t * 16 + cc];
         }
     }
     const u32x4* a_ptr = a.Wt + ((size_t)tile0 * a.KS + k0) * 64 + lane;
     const size_t tile_stride = (size_t)a.KS * 64;
-    const u32x4* b_ptr = a.XB + (size_t)k0 * 256 + lane;
+    constexpr int kBStep = CT * 128;   // 16-byte words of the operand per K step
+    const u32x4* b_ptr = a.XB + (size_t)k0 * kBStep + lane;
     bool col_live[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) col_live[t] = t * 16 + cc < a.wcap;   // known at launch: nothing waits for the descriptor
@@ -487,7 +492,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = 16 / RT;   // 16 weight loads of 16 bytes in flight per lane
+    constexpr int U = (NT > 2 ? (NW > 8 ? 4 : 8) : 16) / RT;   // weight loads of 16 bytes in flight per lane and row tile
+    static_assert(U >= 1, "too many row tiles per wave");
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
     auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp) {
 #pragma unroll
@@ -511,9 +517,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
 #pragma unroll
-        for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * 256);
+        for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep);
         a_ptr += (size_t)U * 64;
-        b_ptr += (size_t)U * 256;
+        b_ptr += (size_t)U * kBStep;
     }
     for (; ks < k1; ++ks) {
         u32x4 wv[RT];
@@ -521,37 +527,44 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
         for (int r = 0; r < RT; ++r) wv[r] = __builtin_nontemporal_load(a_ptr + r * tile_stride);
         step(wv, b_ptr);
         a_ptr += 64;
-        b_ptr += 256;
-    }
-    if (wave > 0) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) red[wave - 1][r][t][lane] = acc[r][t];
+        b_ptr += kBStep;
     }
     if constexpr (kScaled) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) ssp[wave * 4 + g][t * 16 + cc] = ss_mine[t];
     }
-    __syncthreads();
-    if (wave != 0) return;
-    const int w = a.desc->w;
+    // the waves' partial sums meet in LDS TG column tiles at a time and are added in wave order
+    int w = 0;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        float rs = 1.f;
-        if constexpr (kScaled) {
-            float ssum = 0.f;
+    for (int t0 = 0; t0 < NT; t0 += TG) {
+        if (t0 > 0) __syncthreads();   // wave 0 has read the previous group
+        if (wave > 0) {
 #pragma unroll
-            for (int v = 0; v < 4 * NW; ++v) ssum += ssp[v][t * 16 + cc];
-            rs = rsqrtf(ssum * a.inv_d + a.eps);
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int tt = 0; tt < TG; ++tt) red[wave - 1][r][tt][lane] = acc[r][t0 + tt];
         }
-        const int c = t * 16 + cc;
+        __syncthreads();
+        if (wave != 0) continue;
+        if (t0 == 0) w = a.desc->w;
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
+        for (int tt = 0; tt < TG; ++tt) {
+            const int t = t0 + tt;
+            float rs = 1.f;
+            if constexpr (kScaled) {
+                float ssum = 0.f;
 #pragma unroll
-            for (int v = 0; v < NW - 1; ++v) acc[r][t] += red[v][r][t][lane];
-            // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
-            if (c < w) epilogue<EPI>(a, tile0 + r, g, c, w, acc[r][t], rs);
+                for (int v = 0; v < 4 * NW; ++v) ssum += ssp[v][t * 16 + cc];
+                rs = rsqrtf(ssum * a.inv_d + a.eps);
+            }
+            const int c = t * 16 + cc;
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+#pragma unroll
+                for (int v = 0; v < NW - 1; ++v) acc[r][t] += red[v][r][tt][lane];
+                // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
+                if (c < w) epilogue<EPI, CT>(a, tile0 + r, g, c, w, acc[r][t], rs);
+            }
         }
     }
 }
@@ -603,11 +616,11 @@ __global__ __launch_bounds__(1024) void gemm_o_narrow(const GemmArgs a, const fl
     if (wave != 0) return;
 #pragma unroll
     for (int v = 0; v < NW - 1; ++v) acc += red[v][lane];
-    if (cc < w) epilogue<EPI_RESID>(a, tile, g, cc, w, acc, 1.f);
+    if (cc < w) epilogue<EPI_RESID, 2>(a, tile, g, cc, w, acc, 1.f);
 }
 
 // token embedding: x = E[token]; also the first RMSNorm's operand and sum-of-squares partials.  grid d/16, 64 threads
-template <int NT>
+template <int NT, int CT>
 __global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const PassDesc* desc, float* x, void* xb,
                                                  const float* gain, float* ss_out, int d, int V) {
     const int tile = blockIdx.x, lane = threadIdx.x, g = lane >> 4, cc = lane & 15;
@@ -625,11 +638,11 @@ __global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const Pa
         *reinterpret_cast<float4*>(x + (size_t)c * d + n) = make_float4(v[0], v[1], v[2], v[3]);
         const float4 gn = *reinterpret_cast<const float4*>(gain + n);
         const float pk[4] = {v[0] * gn.x, v[1] * gn.y, v[2] * gn.z, v[3] * gn.w};
-        pack4(xb, c, n, pk);
+        pack4<CT>(xb, c, n, pk);
         float ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
         ss += __shfl_xor(ss, 16, kWave);
         ss += __shfl_xor(ss, 32, kWave);
-        if (g == 0) ss_out[tile * 32 + c] = ss;
+        if (g == 0) ss_out[tile * (16 * CT) + c] = ss;
     }
 }
 
@@ -782,7 +795,7 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
                 Ls = fmaf(mrg[v][qr][1], f, Ls);
                 o = fmaf(mrg[v][qr][2 + i], f, o);
             }
-            float* out = part + (((size_t)split * kMaxW + rr / G) * H + gkv * G + rr % G) * (HD + 2);
+            float* out = part + (((size_t)split * kCols + rr / G) * H + gkv * G + rr % G) * (HD + 2);
             out[2 + i] = o;
             if (i == 0) { out[0] = M; out[1] = Ls; }
         }
@@ -790,13 +803,14 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
 }
 
 // grid (wmax, H), block hd: merges the split partials and writes the O-projection's input operand (wide passes)
+template <int CT>
 __global__ void attn_combine_bf16(const float* part, const PassDesc* desc, void* xb, int H, int hd) {
     const int c = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
     if (c >= desc->w) return;
     const int nsp = (desc->pos0 + c + kAttnSplit) / kAttnSplit;  // splits holding keys <= pos0 + c
     float o[1];
     attn_merge<1>(part, nsp, c, h, H, hd, i, o);
-    pack_store<true>(xb, H * hd, c, h * hd + i, o[0]);
+    pack_store<true, CT>(xb, H * hd, c, h * hd + i, o[0]);
 }
 
 // fp32 weights, row-major [N][K]; X fp32 rows [c][K].  One wave per output row.
@@ -904,15 +918,18 @@ static int model_carve(Model& M, Pool& pool) {
     M.kv = take((size_t)M.n_pages * M.L * M.KV * 2 * kPage * M.hd * 4);   // fp32, or bf16 hi + lo
     M.page_table = (int32_t*)take((size_t)M.n_pages * sizeof(int32_t));
     const size_t kmax = std::max((size_t)M.d, (size_t)M.F);
-    M.x = (float*)take((size_t)kMaxW * M.d * sizeof(float));
+    M.x = (float*)take((size_t)kCols * M.d * sizeof(float));
     M.xb = take(kmax * 128);
     if (M.dtype == PSD_BF16) {
         M.xb2 = take(kmax * 128);
         M.ss = (float*)take((size_t)(M.d / 16) * 32 * sizeof(float));
+        M.xbw = take(kmax * 4 * kCols);
+        M.xbw2 = take(kmax * 4 * kCols);
+        M.ssw = (float*)take((size_t)(M.d / 16) * kCols * sizeof(float));
     }
-    M.qkv = (float*)take((size_t)kMaxW * M.nqkv * sizeof(float));
+    M.qkv = (float*)take((size_t)kCols * M.nqkv * sizeof(float));
     M.gu = (float*)take((size_t)kMaxW * 2 * M.F * sizeof(float));
-    M.attn_part = (float*)take((size_t)M.nsplit_max * kMaxW * M.H * (M.hd + 2) * sizeof(float));
+    M.attn_part = (float*)take((size_t)M.nsplit_max * kCols * M.H * (M.hd + 2) * sizeof(float));
     M.desc = (PassDesc*)take(sizeof(PassDesc));
     return ok ? PSD_OK : PSD_ENOMEM;
 }
@@ -1014,8 +1031,8 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     // scratch starts zeroed so that never-written operand columns hold finite values
     const size_t kmax = std::max(d, F);
     PSD_HIP(hipMemsetAsync(M.xb, 0, kmax * 128, stream), err);
-    PSD_HIP(hipMemsetAsync(M.x, 0, (size_t)kMaxW * d * sizeof(float), stream), err);
-    PSD_HIP(hipMemsetAsync(M.qkv, 0, (size_t)kMaxW * M.nqkv * sizeof(float), stream), err);
+    PSD_HIP(hipMemsetAsync(M.x, 0, (size_t)kCols * d * sizeof(float), stream), err);
+    PSD_HIP(hipMemsetAsync(M.qkv, 0, (size_t)kCols * M.nqkv * sizeof(float), stream), err);
     PSD_HIP(hipMemsetAsync(M.gu, 0, (size_t)kMaxW * 2 * F * sizeof(float), stream), err);
     PSD_HIP(hipMemsetAsync(M.desc, 0, sizeof(PassDesc), stream), err);
     // KV pages start as zeros: attention may read (and mask) slots of a page that were never written
@@ -1023,6 +1040,9 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     if (bf) {
         PSD_HIP(hipMemsetAsync(M.xb2, 0, kmax * 128, stream), err);
         PSD_HIP(hipMemsetAsync(M.ss, 0, (size_t)(M.d / 16) * 32 * sizeof(float), stream), err);
+        PSD_HIP(hipMemsetAsync(M.xbw, 0, kmax * 4 * kCols, stream), err);
+        PSD_HIP(hipMemsetAsync(M.xbw2, 0, kmax * 4 * kCols, stream), err);
+        PSD_HIP(hipMemsetAsync(M.ssw, 0, (size_t)(M.d / 16) * kCols * sizeof(float), stream), err);
     }
     // page bookkeeping: every logical block unmapped, free list in (optionally scrambled) order
     M.h_page_table.assign(M.n_pages, -1);
@@ -1140,7 +1160,7 @@ static int forward_f32(Model& M, int wmax, float* logits, Launch& L) {
     return PSD_OK;
 }
 
-// bf16 models: six launches per layer (q/k/v projection, attention, merge, o, gate/up, down)
+// bf16 models: five or six launches per layer (q/k/v projection, attention, merge, o, gate/up, down)
 template <int EPI>
 static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     Model& M = L.M;
@@ -1151,14 +1171,27 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     // Waves per workgroup (the K split, hence the summation order) follow from the number of row tiles only, never
     // from the pass width: a token's result must not depend on the width of the pass that computes it.  Row tiles
     // per wave do not change the arithmetic and are picked per width class.
-    const bool wide = L.wcls > 16;
-#define PSD_GEMM(NT_, NW_, RT_) gemm_bf16<NT_, NW_, RT_, EPI><<<tiles / RT_, 64 * NW_, 0, L.s>>>(a)
-    if (tiles <= 256) {
-        if (wide) PSD_GEMM(2, 16, 1); else PSD_GEMM(1, 16, 1);
-    } else if (tiles % 2 == 0) {
-        if (wide) PSD_GEMM(2, 8, 2); else PSD_GEMM(1, 8, 2);
+#define PSD_GEMM(NT_, NW_, RT_, CT_) gemm_bf16<NT_, NW_, RT_, EPI, CT_><<<tiles / RT_, 64 * NW_, 0, L.s>>>(a)
+    if (L.wcls > 32) {   // 128 columns: every weight block is used 8 times as often, so more row tiles share an operand load
+        if (tiles <= 256) {
+            // two row tiles per wave only where the workgroup's LDS stays under 64 KB (no sum-of-squares table)
+            if (EPI == EPI_RESID && tiles % 2 == 0) PSD_GEMM(8, 16, 2, 8); else PSD_GEMM(8, 16, 1, 8);
+        } else if (tiles % 4 == 0) {
+            PSD_GEMM(8, 8, 4, 8);
+        } else if (tiles % 2 == 0) {
+            PSD_GEMM(8, 8, 2, 8);
+        } else {
+            PSD_GEMM(8, 8, 1, 8);
+        }
     } else {
-        if (wide) PSD_GEMM(2, 8, 1); else PSD_GEMM(1, 8, 1);
+        const bool wide = L.wcls > 16;
+        if (tiles <= 256) {
+            if (wide) PSD_GEMM(2, 16, 1, 2); else PSD_GEMM(1, 16, 1, 2);
+        } else if (tiles % 2 == 0) {
+            if (wide) PSD_GEMM(2, 8, 2, 2); else PSD_GEMM(1, 8, 2, 2);
+        } else {
+            if (wide) PSD_GEMM(2, 8, 1, 2); else PSD_GEMM(1, 8, 1, 2);
+        }
     }
 #undef PSD_GEMM
     L.end();
@@ -1169,22 +1202,27 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     const int d = M.d, F = M.F, H = M.H, KV = M.KV, hd = M.hd, G = H / KV;
     const double act = (double)wmax * d * 4;
     const float inv_d = 1.0f / (float)d;
+    const bool c128 = wmax > 32;   // prompt ingestion: operands with 8 column tiles in their own buffers
+    void* xb = c128 ? M.xbw : M.xb;
+    void* xb2 = c128 ? M.xbw2 : M.xb2;
+    float* ss = c128 ? M.ssw : M.ss;
     L.begin("embed", act);
-    if (wmax <= 16) embed_pack<1><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, M.xb, M.layers[0].attn_norm, M.ss, d, M.V);
-    else embed_pack<2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, M.xb, M.layers[0].attn_norm, M.ss, d, M.V);
+    if (c128) embed_pack<8, 8><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
+    else if (wmax <= 16) embed_pack<1, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
+    else embed_pack<2, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     L.end();
     const int qt_max = (wmax * G + 15) / 16;
     // narrow passes of small models: the o projection merges the attention split partials itself (one launch less)
     const bool fold_merge = wmax <= 4 && d <= 2048 && d / 16 <= 256 && H * hd == d;
     GemmArgs base{};
-    base.ss_in = M.ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
+    base.ss_in = ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
     base.rope = M.rope; base.kv = (uint16_t*)M.kv; base.page_table = M.page_table;
     base.L = M.L; base.H = H; base.KV = KV; base.hd = hd;
     for (int l = 0; l < M.L; ++l) {
         const LayerW& w = M.layers[l];
         const float* next_gain = l + 1 < M.L ? M.layers[l + 1].attn_norm : M.final_norm;
         GemmArgs a = base;
-        a.Wt = (const u32x4*)w.wqkv; a.XB = (const u32x4*)M.xb; a.N = M.nqkv; a.KS = d / 32;
+        a.Wt = (const u32x4*)w.wqkv; a.XB = (const u32x4*)xb; a.N = M.nqkv; a.KS = d / 32;
         a.Y = M.qkv; a.ldy = M.nqkv; a.layer = l;
         launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
         L.begin("attn", 0);
@@ -1194,8 +1232,8 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
         L.end();
         a = base;
-        a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)M.xb2; a.N = d; a.KS = (H * hd) / 32;
-        a.Y = M.x; a.ldy = d; a.xb_out = M.xb; a.gain_out = w.ffn_norm; a.ss_out = M.ss;
+        a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)xb2; a.N = d; a.KS = (H * hd) / 32;
+        a.Y = M.x; a.ldy = d; a.xb_out = xb; a.gain_out = w.ffn_norm; a.ss_out = ss;
         if (fold_merge) {
             a.desc = M.desc; a.wcap = 4;
             L.begin("gemm_o", (double)d * d * 2);
@@ -1203,28 +1241,30 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
             L.end();
         } else {
             L.begin("attn_combine", act);
-            attn_combine_bf16<<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, M.xb2, H, hd);
+            if (c128) attn_combine_bf16<8><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
+            else attn_combine_bf16<2><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
             L.end();
             launch_gemm_bf16<EPI_RESID>(L, "gemm_o", a);
         }
         a = base;
-        a.Wt = (const u32x4*)w.wgu; a.XB = (const u32x4*)M.xb; a.N = 2 * F; a.KS = d / 32; a.xb_out = M.xb2;
+        a.Wt = (const u32x4*)w.wgu; a.XB = (const u32x4*)xb; a.N = 2 * F; a.KS = d / 32; a.xb_out = xb2;
         launch_gemm_bf16<EPI_SWIGLU>(L, "gemm_gate_up", a);
         a = base;
-        a.Wt = (const u32x4*)w.wd; a.XB = (const u32x4*)M.xb2; a.N = d; a.KS = F / 32;
-        a.Y = M.x; a.ldy = d; a.xb_out = M.xb; a.gain_out = next_gain; a.ss_out = M.ss;
+        a.Wt = (const u32x4*)w.wd; a.XB = (const u32x4*)xb2; a.N = d; a.KS = F / 32;
+        a.Y = M.x; a.ldy = d; a.xb_out = xb; a.gain_out = next_gain; a.ss_out = ss;
         launch_gemm_bf16<EPI_RESID>(L, "gemm_down", a);
     }
     if (logits) {
         GemmArgs a = base;
-        a.Wt = (const u32x4*)M.embed; a.XB = (const u32x4*)M.xb; a.N = M.V; a.KS = d / 32; a.Y = logits; a.ldy = M.V;
+        a.Wt = (const u32x4*)M.embed; a.XB = (const u32x4*)xb; a.N = M.V; a.KS = d / 32; a.Y = logits; a.ldy = M.V;
         launch_gemm_bf16<EPI_LOGITS>(L, "gemm_lm_head", a);
     }
     return PSD_OK;
 }
 
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err) {
-    if (wmax != 4 && wmax != 16 && wmax != 32) PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
+    if (wmax != 4 && wmax != 16 && wmax != 32 && wmax != kCols) PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
+    if (wmax == kCols && (M.dtype != PSD_BF16 || logits)) PSD_FAIL(PSD_EINVAL, err, "forward: 128-token passes are for bf16 prompt ingestion only");
     Launch L{M, stream, prof, wmax, {0}};
     int rc = M.dtype == PSD_BF16 ? forward_bf16(M, wmax, logits, L) : forward_f32(M, wmax, logits, L);
     if (rc != PSD_OK) return rc;

@@ -92,6 +92,36 @@ def test_bf16_width_invariance_is_bit_exact():
     ctx.close()
 
 
+@pytest.mark.parametrize("scramble", [0, 0x100])
+def test_bf16_prompt_ingestion_in_128_token_passes_is_bit_exact(scramble):
+    # a prompt ingested in 128-token passes leaves the same KV cache, bit for bit, as 32-token and ragged passes:
+    # the logits of what follows are identical; and they match the oracle
+    shapes = MINI[0]
+    blobs = [synth.target_weights(s, 20 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    n = 300
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 384, flags=scramble)
+    toks = synth.tokens(9, 0, n + 7, 1000)
+    for which in range(3):
+        out = []
+        for widths in ([128, 128, 44], [32] * 9 + [12], [128, 100, 7, 65], [1, 128, 43, 128]):
+            assert sum(widths) == n
+            pos = 0
+            for w in widths:
+                ctx.forward(which, toks[pos:pos + w], pos, want_logits=False)
+                pos += w
+            out.append(ctx.forward(which, toks[n:n + 7], n))
+        for o in out[1:]:
+            assert np.array_equal(out[0], o)
+        om = oracle.Model(shapes[which], blobs[which], synth.DTYPE_BF16, 10000.0, 384)
+        ref = om.forward(toks, 0)[n:]
+        assert np.abs(out[0] - ref).max() <= TOL_BF16
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, toks[:64], 0)                      # logits only up to 32 tokens per pass
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, toks[:129], 0, want_logits=False)
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
