@@ -184,7 +184,7 @@ int psd_set_assisted(psd_ctx* ctx, int32_t on);
 int psd_generate_plain(psd_ctx* ctx, int32_t which, const int32_t* prompt, int32_t n_prompt, int32_t n_new,
                        uint64_t seed, int32_t* out_tokens, psd_stats* out_stats);
 
-/* One forward pass of model `which` over `w` tokens (1 <= w <= PSD_MAX_WIDTH; up to 128 for a bf16 model
+/* One forward pass of model `which` over `w` tokens (1 <= w <= PSD_MAX_WIDTH; up to 512 for a bf16 model
  * when logits_out is NULL: the wide passes that ingest a prompt) at positions pos0 .. pos0+w-1; KV rows below pos0 must have been written by
  * earlier calls (pos0 may also re-write older rows: that is a rollback).
  *   tokens      host, w ids

@@ -6,6 +6,7 @@
 // The draft's chain of single-token steps stays on the device: the sampling kernels write the new token
 // into the next draft pass descriptor and into the qualifier's, so the host synchronises once per
 // qualifier round and once per target pass, when it reads the ACCEPT result.
+#include <stddef.h>
 #include <string.h>
 
 #include <algorithm>
@@ -17,7 +18,7 @@
 namespace psd {
 
 constexpr int kStageSlots = 64;
-constexpr int kStageSlotBytes = 1024;  // a pass descriptor with 128 token ids fits
+constexpr int kStageSlotBytes = 2304;  // a pass descriptor with 512 token ids fits
 
 struct RoundResult {  // pinned host mirror of what a round leaves on the device
     AcceptOut acc;
@@ -125,7 +126,7 @@ static int stage_sync(psd_ctx* c) {
     return PSD_OK;
 }
 
-// copies `bytes` (<= 1024) of host data to device memory in stream order through a pinned ring slot
+// copies `bytes` (<= kStageSlotBytes) of host data to device memory in stream order through a pinned ring slot
 static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
     if (bytes > kStageSlotBytes) PSD_FAIL(PSD_EINVAL, c->err, "internal: staging slot overflow");
     if (c->stage_since_sync >= kStageSlots - 1) {
@@ -140,7 +141,13 @@ static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
     return PSD_OK;
 }
 
-static int wclass(int w) { return w <= 4 ? 4 : (w <= 16 ? 16 : 32); }
+// launch class of a pass of w tokens: 4, 16, 32, or (prompt ingestion only) the next multiple of 128
+static int wclass(int w) { return w <= 4 ? 4 : (w <= 16 ? 16 : (w <= kMaxW ? 32 : (w + 127) / 128 * 128)); }
+
+// bytes of a pass descriptor that have to travel: the header and the token slots the pass can read
+static size_t desc_bytes(const PassDesc& d) {
+    return offsetof(PassDesc, tok) + sizeof(int32_t) * (size_t)std::min(kCols, std::max((int)d.w, kMaxW));
+}
 
 // enqueues one pass of model `mi`; the descriptor is already on the device.  with_sample: the draft step
 // also samples its token and advances the chain.
@@ -197,17 +204,17 @@ static void fill_desc(PassDesc& d, const int32_t* seq, int from, int to, int ext
     for (int i = from; i < to; ++i) d.tok[i - from] = seq[i];
 }
 
-// ingests seq[M.len, upto) with no logits, in chunks of up to 128 (bf16 models) or 32 tokens
+// ingests seq[M.len, upto) with no logits, in chunks of up to 512 (bf16 models) or 32 tokens
 static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
     Model& M = c->M[mi];
     while (M.len < upto) {
-        const int w = std::min(M.dtype == PSD_BF16 ? kCols : kMaxW, upto - M.len);
+        const int w = std::min(M.ingest_max, upto - M.len);
         int rc = model_map_pages(M, M.len, M.len + w, c->stream, c->err);
         if (rc != PSD_OK) return rc;
         PassDesc d;
         fill_desc(d, seq, M.len, M.len + w, 0, 0, 0);
-        if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
-        if ((rc = run_pass(c, mi, w > kMaxW ? kCols : wclass(w), nullptr, false)) != PSD_OK) return rc;
+        if ((rc = upload(c, M.desc, &d, desc_bytes(d))) != PSD_OK) return rc;
+        if ((rc = run_pass(c, mi, wclass(w), nullptr, false)) != PSD_OK) return rc;
         M.len += w;
     }
     return PSD_OK;
@@ -428,7 +435,7 @@ extern "C" int psd_forward(psd_ctx* c, int32_t which, const int32_t* tokens, int
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_forward: null context");
     if (which < 0 || which > 2 || !tokens) PSD_FAIL(PSD_EINVAL, c->err, "psd_forward: bad argument");
     Model& M = c->M[which];
-    const int wcap = (!logits_out && M.dtype == PSD_BF16) ? kCols : kMaxW;   // wider passes only ingest
+    const int wcap = logits_out ? kMaxW : M.ingest_max;   // wider passes only ingest
     if (w < 1 || w > wcap) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: width %d outside [1, %d]", w, wcap);
     if (pos0 < 0 || pos0 + w > M.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_forward: positions [%d, %d) exceed max_seq %d", pos0, pos0 + w, M.max_seq);
     if (pos0 > M.len) PSD_FAIL(PSD_EINVAL, c->err, "psd_forward: pos0 %d but only %d KV rows are valid", pos0, M.len);
@@ -439,8 +446,8 @@ extern "C" int psd_forward(psd_ctx* c, int32_t which, const int32_t* tokens, int
     PassDesc d;
     fill_desc(d, tokens, 0, w, 0, logits_out ? w : 0, 0);
     d.pos0 = pos0;
-    if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
-    if ((rc = run_pass(c, which, w > kMaxW ? kCols : wclass(w), logits_out ? c->HL : nullptr, false)) != PSD_OK) return rc;
+    if ((rc = upload(c, M.desc, &d, desc_bytes(d))) != PSD_OK) return rc;
+    if ((rc = run_pass(c, which, wclass(w), logits_out ? c->HL : nullptr, false)) != PSD_OK) return rc;
     M.len = pos0 + w;
     if ((rc = stage_sync(c)) != PSD_OK) return rc;
     if (logits_out) PSD_HIP(hipMemcpy(logits_out, c->HL, (size_t)w * c->V * sizeof(float), hipMemcpyDeviceToHost), c->err);
@@ -488,8 +495,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             fill_desc(dd, seq.data(), D.len, L, 0, 1, 0);
             fill_desc(qd, seq.data(), Q.len, L, m, m + 1, nbuf);
             SampleCtl sc{seed, L, 0, hq, 0};
-            if ((rc = upload(c, D.desc, &dd, sizeof(dd))) != PSD_OK) return rc;
-            if ((rc = upload(c, Q.desc, &qd, sizeof(qd))) != PSD_OK) return rc;
+            if ((rc = upload(c, D.desc, &dd, desc_bytes(dd))) != PSD_OK) return rc;
+            if ((rc = upload(c, Q.desc, &qd, desc_bytes(qd))) != PSD_OK) return rc;
             if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
             c->timer.begin(c->stream, 0);
             for (int i = 0; i < m; ++i)
@@ -530,7 +537,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         if ((rc = model_map_pages(T, T.len, C + k2, c->stream, c->err)) != PSD_OK) return rc;
         PassDesc td;
         fill_desc(td, seq.data(), T.len, C + k2, 0, k2 + 1, 0);
-        if ((rc = upload(c, T.desc, &td, sizeof(td))) != PSD_OK) return rc;
+        if ((rc = upload(c, T.desc, &td, desc_bytes(td))) != PSD_OK) return rc;
         if ((rc = upload(c, c->win_tok, seq.data() + C, k2 * sizeof(int32_t))) != PSD_OK) return rc;
         c->timer.begin(c->stream, 2);
         if ((rc = run_pass(c, 2, wclass(wT), c->TL, false, true)) != PSD_OK) return rc;
@@ -648,8 +655,8 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
         fill_desc(pd, seq.data(), P.len, C, 0, 1, 0);
         fill_desc(td, seq.data(), T.len, C, k, k + 1, 0);
         SampleCtl sc{seed, C, 0, ht, 0};
-        if ((rc = upload(c, P.desc, &pd, sizeof(pd))) != PSD_OK) return rc;
-        if ((rc = upload(c, T.desc, &td, sizeof(td))) != PSD_OK) return rc;
+        if ((rc = upload(c, P.desc, &pd, desc_bytes(pd))) != PSD_OK) return rc;
+        if ((rc = upload(c, T.desc, &td, desc_bytes(td))) != PSD_OK) return rc;
         if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
         c->timer.begin(c->stream, proposer);
         for (int i = 0; i < k; ++i)
@@ -721,7 +728,7 @@ extern "C" int psd_generate_plain(psd_ctx* c, int32_t which, const int32_t* prom
         if ((rc = model_map_pages(M, M.len, L, c->stream, c->err)) != PSD_OK) return rc;
         PassDesc d;
         fill_desc(d, seq.data(), M.len, L, 0, 1, 0);
-        if ((rc = upload(c, M.desc, &d, sizeof(d))) != PSD_OK) return rc;
+        if ((rc = upload(c, M.desc, &d, desc_bytes(d))) != PSD_OK) return rc;
         if ((rc = run_pass(c, which, 4, c->HL, false)) != PSD_OK) return rc;
         if ((rc = sample_launch(c->HL, 1, c->V, c->prm.temperature, seed, (uint32_t)L, nullptr, c->samp_tok, c->samp_part, c->stream, c->err,
                                 (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0)) != PSD_OK) return rc;

@@ -12,12 +12,13 @@ namespace psd {
 constexpr int kPage = 64;        // tokens per KV page
 constexpr int kAttnSplit = 128;  // keys per attention workgroup (two pages); boundaries are absolute positions
 constexpr int kMaxW = PSD_MAX_WIDTH;   // widest pass that can produce logits (and the widest the ABI takes)
-constexpr int kCols = 128;             // widest pass at all: prompt ingestion of bf16 models, no logits
+constexpr int kCols = 512;             // widest pass at all: prompt ingestion of bf16 models, no logits
+constexpr int kWideCT = kCols / 16;    // column tiles of the operand buffers those passes use
 
 // What one forward pass has to do; lives in DEVICE memory so that a captured graph can be replayed
 // with new contents.  Written by the host before a pass, or by the sampling kernel for the draft chain.
 struct PassDesc {
-    int32_t w;           // tokens in this pass (1..32; up to 128 while ingesting a prompt)
+    int32_t w;           // tokens in this pass (1..32; up to 512 while ingesting a prompt)
     int32_t pos0;        // position of the first token == number of valid KV rows before the pass
     int32_t n_logit;     // the last n_logit tokens get logit rows (0 = none)
     int32_t logit_row0;  // first destination row in the logits buffer
@@ -88,19 +89,20 @@ struct Model {
     std::vector<int32_t> free_pages;
     int pages_mapped = 0;
     // scratch (device)
-    float* x = nullptr;       // residual stream [128][d]
+    float* x = nullptr;       // residual stream [512][d]
     void* xb = nullptr;       // GEMM input operand (bf16 hi/lo tiles, or plain fp32 rows): normalised residual
     void* xb2 = nullptr;      // second operand buffer: attention output / SwiGLU output (bf16 path)
     float* ss = nullptr;      // [d/16][32] partial sums of squares of the residual stream (bf16 path)
-    void* xbw = nullptr;      // the same three for 128-column passes: operands with 8 column tiles, [d/16][128] partials
+    void* xbw = nullptr;      // the same three for prompt-ingestion passes: operands with 32 column tiles, [d/16][512] partials
     void* xbw2 = nullptr;
     float* ssw = nullptr;
-    float* qkv = nullptr;     // [128][nqkv]
+    float* qkv = nullptr;     // [512][nqkv]
     float* gu = nullptr;      // [32][2F]
-    float* attn_part = nullptr;  // [nsplit_max][128][H][hd + 2]
+    float* attn_part = nullptr;  // [nsplit_max][512][H][hd + 2]
     PassDesc* desc = nullptr;
     // host mirror
     int len = 0;  // valid KV rows
+    int ingest_max = 0;  // widest pass that may ingest a prompt (32 for fp32 models; 128 or 512 for bf16 ones)
     size_t weight_bytes = 0;  // bytes one pass streams (all matrices once)
 };
 
@@ -114,7 +116,7 @@ int model_init(Model& M, const psd_model_desc& desc, const char* tag, int max_se
 int model_map_pages(Model& M, int keep, int upto, hipStream_t stream, char* err);
 
 // Enqueues one pass described by *M.desc (already on the device).  wmax: 4, 16 or 32 = widest pass the launch must cover;
-// 128 (bf16 models, logits == nullptr): prompt ingestion.
+// 128, 256, 384 or 512 (bf16 models, logits == nullptr): prompt ingestion.
 // logits: device [rows][V] destination (may be null when the pass produces none).
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err);
 

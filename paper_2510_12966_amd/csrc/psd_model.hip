@@ -569,6 +569,133 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     }
 }
 
+// Projections of a prompt-ingestion pass wider than 128 tokens.  A workgroup of eight waves owns 16 row tiles x
+// 128 columns (blockIdx.y picks the column group) and walks the whole of K: every K step's 16 weight blocks and
+// the column group's operand (hi and lo halves) go through LDS once, double-buffered, and each wave multiplies a
+// 4 x 4 block of tiles out of it, so a weight block fetched from memory is used for 128 columns and an operand
+// block for 256 rows.  The arithmetic is that of gemm_bf16 with NW waves: K is cut at the same NW boundaries, each
+// range is accumulated from zero by the same MFMA sequence, and the ranges are added in order, so the result has
+// the same bits as the narrow kernels'.
+template <int NW, int EPI>
+__global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int tiles) {
+    constexpr int CT = kWideCT;
+    constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+    __shared__ u32x4 smem[2 * 2 * 16 * 64];                   // 64 KB: weight blocks, then operand blocks, two buffers each
+    u32x4 (*sA)[16][64] = reinterpret_cast<u32x4 (*)[16][64]>(smem);
+    u32x4 (*sB)[16][64] = reinterpret_cast<u32x4 (*)[16][64]>(smem + 2 * 16 * 64);   // [column tile][hi, lo][lane] flattened
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, cc = lane & 15;
+    const int wr = wave >> 1, wc = wave & 1;     // rows 4 wr .. + 4 of the 16 tiles, column tiles 4 wc .. + 4 of the 8
+    const int tile0 = blockIdx.x * 16, cg = blockIdx.y, KS = a.KS;
+    constexpr int kBStep = CT * 128;
+    // what this thread stages per K step: two weight words and two operand words
+    const int ta = tile0 + (tid >> 6);
+    const u32x4* pa0 = a.Wt + (size_t)(ta < tiles ? ta : tiles - 1) * KS * 64 + lane;
+    const u32x4* pa1 = a.Wt + (size_t)(ta + 8 < tiles ? ta + 8 : tiles - 1) * KS * 64 + lane;
+    const u32x4* pb = a.XB + (size_t)cg * 1024 + tid;
+    struct Stage { u32x4 a0, a1, b0, b1; };
+    auto fetch = [&](Stage& s, int ks) {
+        s.a0 = __builtin_nontemporal_load(pa0 + (size_t)ks * 64);
+        s.a1 = __builtin_nontemporal_load(pa1 + (size_t)ks * 64);
+        s.b0 = pb[(size_t)ks * kBStep];
+        s.b1 = pb[(size_t)ks * kBStep + 512];
+    };
+    Stage s0, s1;
+    fetch(s0, 0);
+    if (KS > 1) fetch(s1, 1);
+    float rs[4] = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (kScaled) {
+        // the narrow kernels' 4 NW strided partial sums of the input's sums of squares, per column, added in slot order
+        float (*ssp)[128] = reinterpret_cast<float (*)[128]>(smem);
+        const int col = tid & 127;
+        for (int slot = tid >> 7; slot < 4 * NW; slot += 4) {
+            float sum = 0.f;
+            for (int st = slot; st < a.ss_tiles; st += 4 * NW) sum += a.ss_in[st * (16 * CT) + cg * 128 + col];
+            ssp[slot][col] = sum;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float ssum = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4 * NW; ++u) ssum += ssp[u][(wc * 4 + t) * 16 + cc];
+            rs[t] = rsqrtf(ssum * a.inv_d + a.eps);
+        }
+        __syncthreads();
+    }
+    f32x4 cur[4][4], tot[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { cur[r][t] = f32x4{0.f, 0.f, 0.f, 0.f}; tot[r][t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    // K ranges end at KS (v + 1) / NW; the launcher guarantees KS >= NW, so none is empty.  A range's sum starts from
+    // +0 and can therefore never be -0: adding it to a zero total leaves its bits as they are.
+    int v = 0, nb = KS / NW;
+    auto fold = [&]() {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                tot[r][t] += cur[r][t];
+                cur[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        ++v;
+        nb = (int)(((long)KS * (v + 1)) / NW);
+    };
+    auto put = [&](const Stage& s, int buf) {
+        sA[buf][tid >> 6][lane] = s.a0;
+        sA[buf][8 + (tid >> 6)][lane] = s.a1;
+        (&sB[buf][0][0])[tid] = s.b0;
+        (&sB[buf][0][0])[tid + 512] = s.b1;
+    };
+    auto multiply = [&](int buf) {
+        u32x4 wv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) wv[r] = sA[buf][wr * 4 + r][lane];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const u32x4 bh = sB[buf][(wc * 4 + t) * 2][lane], bl = sB[buf][(wc * 4 + t) * 2 + 1][lane];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                cur[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
+                                                                    __builtin_bit_cast(bf16x8, bh), cur[r][t], 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                cur[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
+                                                                    __builtin_bit_cast(bf16x8, bl), cur[r][t], 0, 0, 0);
+        }
+    };
+    // K step ks is multiplied out of LDS buffer ks & 1 while step ks + 1 is written to the other buffer and
+    // steps ks + 2, ks + 3 are in flight in registers
+    put(s0, 0);
+    if (KS > 2) fetch(s0, 2);
+    __syncthreads();
+    for (int ks = 0; ks < KS; ks += 2) {
+        if (ks == nb) fold();
+        if (ks + 1 < KS) put(s1, 1);
+        if (ks + 3 < KS) fetch(s1, ks + 3);
+        multiply(0);
+        __syncthreads();
+        if (ks + 1 >= KS) break;
+        if (ks + 1 == nb) fold();
+        if (ks + 2 < KS) put(s0, 0);
+        if (ks + 4 < KS) fetch(s0, ks + 4);
+        multiply(1);
+        __syncthreads();
+    }
+    fold();
+    const int w = a.desc->w;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int c = cg * 128 + (wc * 4 + t) * 16 + cc;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int tile = tile0 + wr * 4 + r;
+            // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
+            if (tile < tiles && c < w) epilogue<EPI, CT>(a, tile, g, c, w, tot[r][t], rs[t]);
+        }
+    }
+}
+
 // o projection of a narrow pass (<= 4 tokens, K <= 2048, one row tile per workgroup): the merge of the attention
 // split partials, otherwise a kernel of its own, is done here while the weight blocks are in flight; the merged
 // rows go to LDS in B-operand order.  Same K split, MFMA order and reduction as gemm_bf16<1, 16, 1, EPI_RESID>, and
@@ -669,6 +796,8 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
     const int key0 = split * kAttnSplit, kv_max = pos0 + w;
     const int G = H / KV, R = w * G;
     if (key0 >= kv_max || qt * 16 >= R) return;
+    // every key of this split lies after the tile's last query: nothing to attend to, and the merge never reads it
+    if (key0 > pos0 + ((qt * 16 + 15 < R ? qt * 16 + 15 : R - 1) / G)) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, cq = lane & 15;
     const int wkey0 = key0 + wave * 32;
     const bool wave_live = wkey0 < kv_max;
@@ -942,6 +1071,10 @@ static void model_shape(Model& M, const psd_model_desc& m, int max_seq) {
     M.max_seq = max_seq;
     M.n_pages = (max_seq + kPage - 1) / kPage;
     M.nsplit_max = (max_seq + kAttnSplit - 1) / kAttnSplit;
+    // the panel kernel of the widest passes wants every K range of every projection non-empty
+    auto panel_ok = [](int n, int k) { return k / 32 >= (round16(n) / 16 <= 256 ? 16 : 8); };
+    M.ingest_max = m.dtype != PSD_BF16 ? kMaxW
+                   : (panel_ok(M.nqkv, M.d) && panel_ok(M.d, M.H * M.hd) && panel_ok(2 * M.F, M.d) && panel_ok(M.d, M.F)) ? kCols : 128;
 }
 
 size_t model_pool_bytes(const psd_model_desc& m, int max_seq) {
@@ -1172,16 +1305,22 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     // from the pass width: a token's result must not depend on the width of the pass that computes it.  Row tiles
     // per wave do not change the arithmetic and are picked per width class.
 #define PSD_GEMM(NT_, NW_, RT_, CT_) gemm_bf16<NT_, NW_, RT_, EPI, CT_><<<tiles / RT_, 64 * NW_, 0, L.s>>>(a)
-    if (L.wcls > 32) {   // 128 columns: every weight block is used 8 times as often, so more row tiles share an operand load
+    if (L.wcls > 128) {   // several column groups of 128: weights and operand shared through LDS
+        if constexpr (EPI != EPI_LOGITS) {
+            const dim3 pgrid((tiles + 15) / 16, L.wcls / 128);
+            if (tiles <= 256) gemm_panel<16, EPI><<<pgrid, 512, 0, L.s>>>(a, tiles);   // same K split as the narrow kernels
+            else gemm_panel<8, EPI><<<pgrid, 512, 0, L.s>>>(a, tiles);
+        }
+    } else if (L.wcls > 32) {   // 128 columns: every weight block is used 8 times as often, so more row tiles share an operand load
         if (tiles <= 256) {
             // two row tiles per wave only where the workgroup's LDS stays under 64 KB (no sum-of-squares table)
-            if (EPI == EPI_RESID && tiles % 2 == 0) PSD_GEMM(8, 16, 2, 8); else PSD_GEMM(8, 16, 1, 8);
+            if (EPI == EPI_RESID && tiles % 2 == 0) PSD_GEMM(8, 16, 2, kWideCT); else PSD_GEMM(8, 16, 1, kWideCT);
         } else if (tiles % 4 == 0) {
-            PSD_GEMM(8, 8, 4, 8);
+            PSD_GEMM(8, 8, 4, kWideCT);
         } else if (tiles % 2 == 0) {
-            PSD_GEMM(8, 8, 2, 8);
+            PSD_GEMM(8, 8, 2, kWideCT);
         } else {
-            PSD_GEMM(8, 8, 1, 8);
+            PSD_GEMM(8, 8, 1, kWideCT);
         }
     } else {
         const bool wide = L.wcls > 16;
@@ -1202,12 +1341,12 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     const int d = M.d, F = M.F, H = M.H, KV = M.KV, hd = M.hd, G = H / KV;
     const double act = (double)wmax * d * 4;
     const float inv_d = 1.0f / (float)d;
-    const bool c128 = wmax > 32;   // prompt ingestion: operands with 8 column tiles in their own buffers
+    const bool c128 = wmax > 32;   // prompt ingestion: operands with 32 column tiles in their own buffers
     void* xb = c128 ? M.xbw : M.xb;
     void* xb2 = c128 ? M.xbw2 : M.xb2;
     float* ss = c128 ? M.ssw : M.ss;
     L.begin("embed", act);
-    if (c128) embed_pack<8, 8><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
+    if (c128) embed_pack<kWideCT, kWideCT><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     else if (wmax <= 16) embed_pack<1, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     else embed_pack<2, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     L.end();
@@ -1241,7 +1380,7 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
             L.end();
         } else {
             L.begin("attn_combine", act);
-            if (c128) attn_combine_bf16<8><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
+            if (c128) attn_combine_bf16<kWideCT><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
             else attn_combine_bf16<2><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
             L.end();
             launch_gemm_bf16<EPI_RESID>(L, "gemm_o", a);
@@ -1263,8 +1402,10 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
 }
 
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err) {
-    if (wmax != 4 && wmax != 16 && wmax != 32 && wmax != kCols) PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
-    if (wmax == kCols && (M.dtype != PSD_BF16 || logits)) PSD_FAIL(PSD_EINVAL, err, "forward: 128-token passes are for bf16 prompt ingestion only");
+    const bool ingest = wmax > kMaxW;
+    if (ingest ? (wmax % 128 != 0 || wmax > M.ingest_max) : (wmax != 4 && wmax != 16 && wmax != 32))
+        PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
+    if (ingest && (M.dtype != PSD_BF16 || logits)) PSD_FAIL(PSD_EINVAL, err, "forward: passes wider than %d tokens are for bf16 prompt ingestion only", kMaxW);
     Launch L{M, stream, prof, wmax, {0}};
     int rc = M.dtype == PSD_BF16 ? forward_bf16(M, wmax, logits, L) : forward_f32(M, wmax, logits, L);
     if (rc != PSD_OK) return rc;

@@ -122,6 +122,39 @@ def test_bf16_prompt_ingestion_in_128_token_passes_is_bit_exact(scramble):
     ctx.close()
 
 
+WIDE = (ModelShape(2, 256, 4, 2, 352, 1000), ModelShape(2, 512, 8, 2, 2304, 1000), ModelShape(2, 1024, 8, 4, 2560, 1000))
+
+
+def test_bf16_prompt_ingestion_in_512_token_passes_is_bit_exact():
+    # passes of up to 512 tokens (several 128-column groups per launch, weights and operand shared through LDS) leave
+    # the same KV cache, bit for bit, as 128-token, 32-token and ragged passes; row-tile counts that are not
+    # multiples of 16, K ranges of one step, both K splits (8 and 16 ranges); and the logits match the oracle
+    shapes = WIDE
+    blobs = [synth.target_weights(s, 40 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    n = 700
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 768)
+    toks = synth.tokens(11, 0, n + 5, 1000)
+    for which in (1, 2):
+        out = []
+        for widths in ([512, 188], [128] * 5 + [60], [32] * 21 + [28], [300, 400], [1, 511, 129, 59]):
+            assert sum(widths) == n
+            pos = 0
+            for w in widths:
+                ctx.forward(which, toks[pos:pos + w], pos, want_logits=False)
+                pos += w
+            out.append(ctx.forward(which, toks[n:n + 5], n))
+        for o in out[1:]:
+            assert np.array_equal(out[0], o)
+        om = oracle.Model(shapes[which], blobs[which], synth.DTYPE_BF16, 10000.0, 768)
+        ref = om.forward(toks, 0)[n:]
+        assert np.abs(out[0] - ref).max() <= TOL_BF16
+    with pytest.raises(psd.PsdError):
+        ctx.forward(0, toks[:129], 0, want_logits=False)   # a model too small for the widest kernel stays at 128
+    with pytest.raises(psd.PsdError):
+        ctx.forward(2, toks[:513], 0, want_logits=False)
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
