@@ -570,63 +570,68 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 }
 
 // Projections of a prompt-ingestion pass wider than 128 tokens.  A workgroup of eight waves owns 16 row tiles x
-// 128 columns (blockIdx.y picks the column group) and walks the whole of K: every K step's 16 weight blocks and
+// 32 TC columns (blockIdx.y picks the column group) and walks the whole of K: every K step's 16 weight blocks and
 // the column group's operand (hi and lo halves) go through LDS once, double-buffered, and each wave multiplies a
-// 4 x 4 block of tiles out of it, so a weight block fetched from memory is used for 128 columns and an operand
-// block for 256 rows.  The arithmetic is that of gemm_bf16 with NW waves: K is cut at the same NW boundaries, each
+// 4 x TC block of tiles out of it, so a weight block fetched from memory is used for 32 TC columns and an operand
+// block for 256 rows.  TC = 4 moves the fewest bytes per MFMA; TC = 2 doubles the workgroups of a projection with
+// few row tiles.  The arithmetic is that of gemm_bf16 with NW waves: K is cut at the same NW boundaries, each
 // range is accumulated from zero by the same MFMA sequence, and the ranges are added in order, so the result has
 // the same bits as the narrow kernels'.
-template <int NW, int EPI>
+template <int NW, int EPI, int TC>
 __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int tiles) {
     constexpr int CT = kWideCT;
     constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+    constexpr int GC = 32 * TC, GW = 4 * TC * 64;             // columns, and operand words per K step, of a column group
+    static_assert(TC == 2 || TC == 4, "column tiles per wave");
     __shared__ u32x4 smem[2 * 2 * 16 * 64];                   // 64 KB: weight blocks, then operand blocks, two buffers each
     u32x4 (*sA)[16][64] = reinterpret_cast<u32x4 (*)[16][64]>(smem);
     u32x4 (*sB)[16][64] = reinterpret_cast<u32x4 (*)[16][64]>(smem + 2 * 16 * 64);   // [column tile][hi, lo][lane] flattened
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, cc = lane & 15;
-    const int wr = wave >> 1, wc = wave & 1;     // rows 4 wr .. + 4 of the 16 tiles, column tiles 4 wc .. + 4 of the 8
+    const int wr = wave >> 1, wc = wave & 1;     // rows 4 wr .. + 4 of the 16 tiles, column tiles TC wc .. + TC of the group's
     const int tile0 = blockIdx.x * 16, cg = blockIdx.y, KS = a.KS;
     constexpr int kBStep = CT * 128;
     // what this thread stages per K step: two weight words and two operand words
     const int ta = tile0 + (tid >> 6);
     const u32x4* pa0 = a.Wt + (size_t)(ta < tiles ? ta : tiles - 1) * KS * 64 + lane;
     const u32x4* pa1 = a.Wt + (size_t)(ta + 8 < tiles ? ta + 8 : tiles - 1) * KS * 64 + lane;
-    const u32x4* pb = a.XB + (size_t)cg * 1024 + tid;
+    const u32x4* pb = a.XB + (size_t)cg * GW + tid;
     struct Stage { u32x4 a0, a1, b0, b1; };
     auto fetch = [&](Stage& s, int ks) {
         s.a0 = __builtin_nontemporal_load(pa0 + (size_t)ks * 64);
         s.a1 = __builtin_nontemporal_load(pa1 + (size_t)ks * 64);
         s.b0 = pb[(size_t)ks * kBStep];
-        s.b1 = pb[(size_t)ks * kBStep + 512];
+        if constexpr (GW > 512) s.b1 = pb[(size_t)ks * kBStep + 512];
     };
     Stage s0, s1;
     fetch(s0, 0);
     if (KS > 1) fetch(s1, 1);
-    float rs[4] = {1.f, 1.f, 1.f, 1.f};
+    float rs[TC];
+#pragma unroll
+    for (int t = 0; t < TC; ++t) rs[t] = 1.f;
     if constexpr (kScaled) {
         // the narrow kernels' 4 NW strided partial sums of the input's sums of squares, per column, added in slot order
-        float (*ssp)[128] = reinterpret_cast<float (*)[128]>(smem);
-        const int col = tid & 127;
-        for (int slot = tid >> 7; slot < 4 * NW; slot += 4) {
+        float (*ssp)[GC] = reinterpret_cast<float (*)[GC]>(smem);
+        const int col = tid % GC;
+        for (int slot = tid / GC; slot < 4 * NW; slot += 512 / GC) {
             float sum = 0.f;
-            for (int st = slot; st < a.ss_tiles; st += 4 * NW) sum += a.ss_in[st * (16 * CT) + cg * 128 + col];
+            for (int st = slot; st < a.ss_tiles; st += 4 * NW) sum += a.ss_in[st * (16 * CT) + cg * GC + col];
             ssp[slot][col] = sum;
         }
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < TC; ++t) {
             float ssum = 0.f;
 #pragma unroll
-            for (int u = 0; u < 4 * NW; ++u) ssum += ssp[u][(wc * 4 + t) * 16 + cc];
+            for (int u = 0; u < 4 * NW; ++u) ssum += ssp[u][(wc * TC + t) * 16 + cc];
             rs[t] = rsqrtf(ssum * a.inv_d + a.eps);
         }
         __syncthreads();
     }
-    f32x4 cur[4][4], tot[4][4];
+    f32x4 cur[4][TC], tot[4][TC];
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { cur[r][t] = f32x4{0.f, 0.f, 0.f, 0.f}; tot[r][t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        for (int t = 0; t < TC; ++t) { cur[r][t] = f32x4{0.f, 0.f, 0.f, 0.f}; tot[r][t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
     // K ranges end at KS (v + 1) / NW; the launcher guarantees KS >= NW, so none is empty.  A range's sum starts from
     // +0 and can therefore never be -0: adding it to a zero total leaves its bits as they are.
     int v = 0, nb = KS / NW;
@@ -634,7 +639,7 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < TC; ++t) {
                 tot[r][t] += cur[r][t];
                 cur[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -645,15 +650,15 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
         sA[buf][tid >> 6][lane] = s.a0;
         sA[buf][8 + (tid >> 6)][lane] = s.a1;
         (&sB[buf][0][0])[tid] = s.b0;
-        (&sB[buf][0][0])[tid + 512] = s.b1;
+        if constexpr (GW > 512) (&sB[buf][0][0])[tid + 512] = s.b1;
     };
     auto multiply = [&](int buf) {
         u32x4 wv[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) wv[r] = sA[buf][wr * 4 + r][lane];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const u32x4 bh = sB[buf][(wc * 4 + t) * 2][lane], bl = sB[buf][(wc * 4 + t) * 2 + 1][lane];
+        for (int t = 0; t < TC; ++t) {
+            const u32x4 bh = sB[buf][(wc * TC + t) * 2][lane], bl = sB[buf][(wc * TC + t) * 2 + 1][lane];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 cur[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
@@ -685,8 +690,8 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
     fold();
     const int w = a.desc->w;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int c = cg * 128 + (wc * 4 + t) * 16 + cc;
+    for (int t = 0; t < TC; ++t) {
+        const int c = cg * GC + (wc * TC + t) * 16 + cc;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int tile = tile0 + wr * 4 + r;
@@ -788,31 +793,26 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDesc* desc, const uint16_t* kv,
                                                  const int32_t* page_table, float* part, int layer, int L, int H,
-                                                 int KV, int nqkv) {
+                                                 int KV, int nqkv, int qt_per_wg) {
     constexpr int KSQ = HD / 32, JT = HD / 16;
     __shared__ float mrg[4][16][HD + 2];
-    const int gkv = blockIdx.x, split = blockIdx.y, qt = blockIdx.z;
+    const int gkv = blockIdx.x, split = blockIdx.y;
     const int w = desc->w, pos0 = desc->pos0;
     const int key0 = split * kAttnSplit, kv_max = pos0 + w;
     const int G = H / KV, R = w * G;
-    if (key0 >= kv_max || qt * 16 >= R) return;
-    // every key of this split lies after the tile's last query: nothing to attend to, and the merge never reads it
-    if (key0 > pos0 + ((qt * 16 + 15 < R ? qt * 16 + 15 : R - 1) / G)) return;
+    if (key0 >= kv_max || (int)blockIdx.z * qt_per_wg * 16 >= R) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, cq = lane & 15;
     const int wkey0 = key0 + wave * 32;
     const bool wave_live = wkey0 < kv_max;
-    const int rho = qt * 16 + cq;
-    float m = -INFINITY, l = 0.f;
-    f32x4 O[JT];
-#pragma unroll
-    for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the wave's keys and values stay in registers for all of the workgroup's query tiles
+    u32x4 ka[2][KSQ], kb[2][KSQ];   // hi and lo halves
+    uint2 vraw[JT][2], vlow[JT][2];
     if (wave_live) {
         // this wave's 32 keys sit inside one page: K rows are the A operand of S^T, V^T columns the B operand of P V
         const int page = page_table[wkey0 / kPage], slot0 = wkey0 % kPage;
         constexpr size_t kPlane = (size_t)kPage * HD;
         const uint16_t* Kp = kv + kv_plane(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
         const uint16_t* Vp = kv + kv_plane(page, layer, L, gkv, KV, 2, HD) + slot0;
-        u32x4 ka[2][KSQ], kb[2][KSQ];   // hi and lo halves
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -821,7 +821,6 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
                 ka[kt][ks] = *reinterpret_cast<const u32x4*>(p);
                 kb[kt][ks] = *reinterpret_cast<const u32x4*>(p + kPlane);
             }
-        uint2 vraw[JT][2], vlow[JT][2];
 #pragma unroll
         for (int j = 0; j < JT; ++j)
 #pragma unroll
@@ -830,6 +829,18 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
                 vraw[j][kt] = *reinterpret_cast<const uint2*>(p);
                 vlow[j][kt] = *reinterpret_cast<const uint2*>(p + kPlane);
             }
+    }
+    for (int qi = 0; qi < qt_per_wg; ++qi) {
+    const int qt = blockIdx.z * qt_per_wg + qi;
+    if (qt * 16 >= R) break;
+    // every key of this split lies after the tile's last query: nothing to attend to, and the merge never reads it
+    if (key0 > pos0 + ((qt * 16 + 15 < R ? qt * 16 + 15 : R - 1) / G)) continue;
+    const int rho = qt * 16 + cq;
+    float m = -INFINITY, l = 0.f;
+    f32x4 O[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (wave_live) {
         // query row rho as B operand: lane (g, c) holds head dims 32 ks + 8 g .. + 8 of row c, scaled by 1/sqrt(hd)
         const float scale = rsqrtf((float)HD);
         u32x4 qh[KSQ], ql[KSQ];
@@ -928,6 +939,8 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
             out[2 + i] = o;
             if (i == 0) { out[0] = M; out[1] = Ls; }
         }
+    }
+    __syncthreads();   // the merge buffer is reused by the next query tile
     }
 }
 
@@ -1307,9 +1320,17 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
 #define PSD_GEMM(NT_, NW_, RT_, CT_) gemm_bf16<NT_, NW_, RT_, EPI, CT_><<<tiles / RT_, 64 * NW_, 0, L.s>>>(a)
     if (L.wcls > 128) {   // several column groups of 128: weights and operand shared through LDS
         if constexpr (EPI != EPI_LOGITS) {
-            const dim3 pgrid((tiles + 15) / 16, L.wcls / 128);
-            if (tiles <= 256) gemm_panel<16, EPI><<<pgrid, 512, 0, L.s>>>(a, tiles);   // same K split as the narrow kernels
-            else gemm_panel<8, EPI><<<pgrid, 512, 0, L.s>>>(a, tiles);
+            // NW: the K split of the narrow kernels.  Column groups of 64 where groups of 128 would leave CUs idle.
+            const int rg = (tiles + 15) / 16;
+            if (rg * (L.wcls / 128) >= 192) {
+                const dim3 pgrid(rg, L.wcls / 128);
+                if (tiles <= 256) gemm_panel<16, EPI, 4><<<pgrid, 512, 0, L.s>>>(a, tiles);
+                else gemm_panel<8, EPI, 4><<<pgrid, 512, 0, L.s>>>(a, tiles);
+            } else {
+                const dim3 pgrid(rg, L.wcls / 64);
+                if (tiles <= 256) gemm_panel<16, EPI, 2><<<pgrid, 512, 0, L.s>>>(a, tiles);
+                else gemm_panel<8, EPI, 2><<<pgrid, 512, 0, L.s>>>(a, tiles);
+            }
         }
     } else if (L.wcls > 32) {   // 128 columns: every weight block is used 8 times as often, so more row tiles share an operand load
         if (tiles <= 256) {
@@ -1350,7 +1371,8 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     else if (wmax <= 16) embed_pack<1, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     else embed_pack<2, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     L.end();
-    const int qt_max = (wmax * G + 15) / 16;
+    const int qt_per_wg = wmax > kMaxW ? 4 : 1;   // wide passes: four query tiles share one load of the keys and values
+    const int qt_max = ((wmax * G + 15) / 16 + qt_per_wg - 1) / qt_per_wg;
     // narrow passes of small models: the o projection merges the attention split partials itself (one launch less)
     const bool fold_merge = wmax <= 4 && d <= 2048 && d / 16 <= 256 && H * hd == d;
     GemmArgs base{};
@@ -1366,9 +1388,9 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
         L.begin("attn", 0);
         const dim3 agrid(KV, M.nsplit_max, qt_max);
-        if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
-        else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
-        else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv);
+        if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
+        else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
+        else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
         L.end();
         a = base;
         a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)xb2; a.N = d; a.KS = (H * hd) / 32;
