@@ -570,7 +570,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 }
 
 // Projections of a prompt-ingestion pass wider than 128 tokens.  A workgroup of eight waves owns 16 row tiles x
-// 32 TC columns (blockIdx.y picks the column group) and walks the whole of K: every K step's 16 weight blocks and
+// 32 TC columns (ncg column groups per launch) and walks the whole of K: every K step's 16 weight blocks and
 // the column group's operand (hi and lo halves) go through LDS once, double-buffered, and each wave multiplies a
 // 4 x TC block of tiles out of it, so a weight block fetched from memory is used for 32 TC columns and an operand
 // block for 256 rows.  TC = 4 moves the fewest bytes per MFMA; TC = 2 doubles the workgroups of a projection with
@@ -578,7 +578,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 // range is accumulated from zero by the same MFMA sequence, and the ranges are added in order, so the result has
 // the same bits as the narrow kernels'.
 template <int NW, int EPI, int TC>
-__global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int tiles) {
+__global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int tiles, const int ncg) {
     constexpr int CT = kWideCT;
     constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
     constexpr int GC = 32 * TC, GW = 4 * TC * 64;             // columns, and operand words per K step, of a column group
@@ -588,7 +588,12 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
     u32x4 (*sB)[16][64] = reinterpret_cast<u32x4 (*)[16][64]>(smem + 2 * 16 * 64);   // [column tile][hi, lo][lane] flattened
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, cc = lane & 15;
     const int wr = wave >> 1, wc = wave & 1;     // rows 4 wr .. + 4 of the 16 tiles, column tiles TC wc .. + TC of the group's
-    const int tile0 = blockIdx.x * 16, cg = blockIdx.y, KS = a.KS;
+    // Workgroups go to the eight XCDs (one L2 each) round-robin in launch order.  The ncg column groups of a row
+    // group take consecutive slots of one XCD, so they run side by side and its weights come from memory once.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int rgi = (slot / ncg) * 8 + xcd, cg = slot % ncg, KS = a.KS;
+    if (rgi * 16 >= tiles) return;
+    const int tile0 = rgi * 16;
     constexpr int kBStep = CT * 128;
     // what this thread stages per K step: two weight words and two operand words
     const int ta = tile0 + (tid >> 6);
@@ -1321,15 +1326,15 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     if (L.wcls > 128) {   // several column groups of 128: weights and operand shared through LDS
         if constexpr (EPI != EPI_LOGITS) {
             // NW: the K split of the narrow kernels.  Column groups of 64 where groups of 128 would leave CUs idle.
-            const int rg = (tiles + 15) / 16;
+            const int rg = (tiles + 15) / 16, rg8 = (rg + 7) / 8 * 8;
             if (rg * (L.wcls / 128) >= 192) {
-                const dim3 pgrid(rg, L.wcls / 128);
-                if (tiles <= 256) gemm_panel<16, EPI, 4><<<pgrid, 512, 0, L.s>>>(a, tiles);
-                else gemm_panel<8, EPI, 4><<<pgrid, 512, 0, L.s>>>(a, tiles);
+                const int ncg = L.wcls / 128;
+                if (tiles <= 256) gemm_panel<16, EPI, 4><<<rg8 * ncg, 512, 0, L.s>>>(a, tiles, ncg);
+                else gemm_panel<8, EPI, 4><<<rg8 * ncg, 512, 0, L.s>>>(a, tiles, ncg);
             } else {
-                const dim3 pgrid(rg, L.wcls / 64);
-                if (tiles <= 256) gemm_panel<16, EPI, 2><<<pgrid, 512, 0, L.s>>>(a, tiles);
-                else gemm_panel<8, EPI, 2><<<pgrid, 512, 0, L.s>>>(a, tiles);
+                const int ncg = L.wcls / 64;
+                if (tiles <= 256) gemm_panel<16, EPI, 2><<<rg8 * ncg, 512, 0, L.s>>>(a, tiles, ncg);
+                else gemm_panel<8, EPI, 2><<<rg8 * ncg, 512, 0, L.s>>>(a, tiles, ncg);
             }
         }
     } else if (L.wcls > 32) {   // 128 columns: every weight block is used 8 times as often, so more row tiles share an operand load
