@@ -648,13 +648,13 @@ __global__ __launch_bounds__(kAccThreads) void sample_partial(const float* logit
     if (threadIdx.x == 0) parts[(size_t)r * nch + ch] = best;
 }
 
-__global__ void sample_final(const KeyIdx* parts, int nch, int32_t* tokens_out) {
+// one wave per row; the order of the comparisons is free: equal keys always resolve to the lowest index
+__global__ __launch_bounds__(64) void sample_final(const KeyIdx* parts, int nch, int32_t* tokens_out) {
     const int r = blockIdx.x;
-    if (threadIdx.x == 0) {
-        KeyIdx best{-INFINITY, 0x7fffffff};
-        for (int c = 0; c < nch; ++c) best = better(best, parts[(size_t)r * nch + c]);
-        tokens_out[r] = best.idx;
-    }
+    KeyIdx best{-INFINITY, 0x7fffffff};
+    for (int c = threadIdx.x; c < nch; c += kWave) best = better(best, parts[(size_t)r * nch + c]);
+    best = wave_best(best);
+    if (threadIdx.x == 0) tokens_out[r] = best.idx;
 }
 
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,

@@ -24,7 +24,7 @@ enum { EPI_STORE = 0, EPI_RESID = 1, EPI_LOGITS = 2 };
 
 // ---- operand packing ----------------------------------------------------------------------------
 // GEMM input X[c][f] (c < 16 CT tokens, f < K features), bf16 path: [K/32][CT col tiles][hi, lo][64 lanes][8]
-// (CT = 2 for passes of up to 32 tokens, 8 for the 128-token passes that ingest a prompt),
+// (CT = 2 for passes of up to 32 tokens, 32 for the passes of up to 512 tokens that ingest a prompt),
 // lane = ((f % 32) / 8) * 16 + c % 16: exactly the B operand of v_mfma_f32_16x16x32_bf16.
 // fp32 path: plain rows [c][K].
 template <bool BF16, int CT = 2>
