@@ -2,8 +2,8 @@
 """Benchmark of the three-model speculative loop on one MI355X.
 
 A step is one psd_generate call: prefill of the synthetic prompt by the three models, then the
-draft -> qualifier -> target loop until n_new tokens exist.  Prints ONE JSON line (see README /
-the design doc for the fields).  Weights, prompt and every random draw are seeded and synthetic.
+draft -> qualifier -> target loop until n_new tokens exist.  Prints ONE JSON line: throughput, per-pass times, the
+dominant kernel's roofline, the CPU oracle's speed on a sample, comparison runs.  Weights, prompt and every random draw are seeded and synthetic.
 """
 from __future__ import annotations
 
@@ -141,7 +141,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs the batch-1 loop on ONE GPU; --gpus N with N > 1 is not supported "
-            "(the loop is a dependency chain; see DESIGN.md for how it would shard)")
+            "(the loop is a dependency chain: it would shard by model placement or tensor-parallel projections)")
         return 2
 
     import paper_2510_12966_amd as psd
