@@ -210,3 +210,33 @@ def test_expired_wait_falls_back_to_two_launches_and_still_matches_oracle():
         psd.set_accept_path(0)
     assert psd.get_accept_path() == 0
     assert _compare(lp, lq, x, 0.2, 1.0, 9, 40, 2, True) in ("exact", "tie")
+
+
+def test_accept_statistics_over_many_trials():
+    """1024 trials per threshold in one launch sequence (vocabulary of three chunks with a ragged tail, k = 6):
+    every trial against the oracle, the accept-length histograms, the mean accepted length per threshold, and
+    its monotone growth with the threshold (Section 3.2: a larger threshold only ever accepts more)."""
+    k, V, B, rho = 6, 12345, 1024, 0.8
+    rng = np.random.default_rng(17)
+    P = (3.0 * rng.standard_normal((B, k + 1, V))).astype(np.float32)
+    Q = (rho * P[:, :k] + math.sqrt(1 - rho * rho) * 3.0 * rng.standard_normal((B, k, V))).astype(np.float32)
+    X = np.array([[oracle.sample_row(Q[b, i], 1.0, 900 + b, 1000 + i)[0] for i in range(k)] for b in range(B)],
+                 dtype=np.int32)
+    means, ties = [], 0
+    for T in (0.0, 0.3, 0.45):     # the divergences of these rows lie between 0.15 and 0.4
+        na, nt, dv = _batched(list(P), list(Q), list(X), T, 1.0, 100, 50, 2, True)
+        hist_g, hist_o = np.bincount(na, minlength=k + 1), np.zeros(k + 1, dtype=np.int64)
+        for b in range(B):
+            res, odiv = oracle.accept(P[b], Q[b], X[b], T, 1.0, 100 + b, 50, 2, True)
+            hist_o[res.n_accepted] += 1
+            assert np.abs(dv[b] - odiv).max() <= DIV_TOL
+            if na[b] != res.n_accepted or nt[b] != res.next_token:
+                assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN or res.margin_race < TIE_RACE
+                ties += 1
+                hist_o[res.n_accepted] -= 1
+                hist_o[na[b]] += 1          # a tie moves one trial between neighbouring bins, nothing else
+        assert np.array_equal(hist_g, hist_o)
+        assert 0 <= nt.min() and nt.max() < V
+        means.append(float(na.mean()))
+    assert ties <= 3
+    assert means[0] < means[1] < means[2] and means[0] > 0.05 and means[2] < k
