@@ -65,6 +65,8 @@ SETTINGS = [  # (T_q, T_t, k1, k2, temperature); the first row is the tiny confi
     (0.006, 0.0, 5, 5, 0.7),
     (0.004, 0.012, 1, 1, 1.0),
     (0.01, 0.01, 8, 3, 1.0),     # k1 > k2: rounds are capped by the window
+    (0.3, 0.2, 30, 31, 1.0),     # the largest windows the interface takes: 32-token target passes
+    (0.004, 0.012, 30, 31, 1.0), # the same with rejections in both stages
 ]
 
 
@@ -144,6 +146,17 @@ def test_small_bf16_stack_replay_and_baseline_settings():
     print("small stack, tight:", st, "ties", rp.ties, flush=True)
     assert rp.ties <= 1
     ctx.close()
+    # the largest windows the interface takes (bf16 kernels of the 32-column class inside the loop)
+    for T_q, T_t in ((cfg.T_q, cfg.T_t), (0.05, 0.05)):
+        ctx = _ctx(cfg, (d, q, t), cfg.n_prompt + 80 + 31 + 2, T_q, T_t, 30, 31, flags=psd.FLAG_GRAPH)
+        rp = Replay(5, T_q, T_t)
+        ctx.set_trace(rp)
+        out, st = ctx.generate(prompt, 80, 5)
+        ctx.set_trace(None)
+        print("small stack, k1 30, k2 31:", st, "ties", rp.ties, flush=True)
+        assert rp.ties <= 1 and rp.events >= 3
+        assert st["proposed_t"] == 31 * st["passes_t"]
+        ctx.close()
 
 
 def test_generate_argument_errors(tiny_stack):
