@@ -111,6 +111,21 @@ def test_tiny_stack_exact_token_parity_over_seeds(tiny_stack):
     ctx.close()
 
 
+def test_shortest_prompts_match_oracle(tiny_stack):
+    # a one-token prompt has nothing to ingest (the caches start empty); two tokens ingest exactly one
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx(cfg, (d, q, t), 2 + 24 + 10, 0.004, 0.012, 4, 8)
+    for n_prompt in (1, 2):
+        rp = Replay(4, 0.004, 0.012)
+        ctx.set_trace(rp)
+        out, st = ctx.generate(prompt[:n_prompt], 24, 4)
+        ctx.set_trace(None)
+        ref, ost = _oracle_run(cfg, (d, q, t), prompt[:n_prompt], 24, 4, 4, 8, 0.004, 0.012)
+        assert rp.ties > 0 or np.array_equal(out, ref)
+        assert out.size == 24
+    ctx.close()
+
+
 def test_identical_models_accept_everything_and_equal_plain_sampling(tiny_stack):
     cfg, d, q, t, prompt = tiny_stack
     shapes = (cfg.qualifier,) * 3
