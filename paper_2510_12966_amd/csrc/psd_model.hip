@@ -383,14 +383,44 @@ __device__ inline void pack2(void* xb, int c, int f0, float v0, float v1) {
     *reinterpret_cast<uint32_t*>(p + 512) = l0 | ((uint32_t)l1 << 16);
 }
 
-// value tile of one lane: rows n0 + 4 g + r (r = 0..3) of column c
-template <int EPI, int CT>
-__device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w, f32x4 v, float rs) {
+// the pass descriptor's scalars, asked for when a kernel starts so that nothing waits for them at its end
+struct DescVals { int w, pos0, n_logit, row0; };
+__device__ inline DescVals load_desc(const PassDesc* d) { return DescVals{d->w, d->pos0, d->n_logit, d->logit_row0}; }
+
+// What an epilogue reads from memory besides its own result.  The narrow kernels ask for it while the weights
+// stream, so that the answers are there when the K loop ends; the arithmetic is the same either way.
+template <int EPI> struct EpiPre {};
+template <> struct EpiPre<EPI_RESID> { float4 x, gn; };
+template <> struct EpiPre<EPI_QKV> { int page; float2 cs[2]; };
+
+template <int EPI>
+__device__ inline void epi_prefetch(const GemmArgs& a, const DescVals& dv, int tile, int g, int c, EpiPre<EPI>& p) {
     const int n = tile * 16 + g * 4;
+    if constexpr (EPI == EPI_RESID) {
+        p.x = *reinterpret_cast<const float4*>(a.Y + (size_t)c * a.ldy + n);
+        p.gn = *reinterpret_cast<const float4*>(a.gain_out + n);
+    } else if constexpr (EPI == EPI_QKV) {
+        const int hd = a.hd, half = hd >> 1;
+        const int head = (tile * 16) / hd, t_in = ((tile * 16) % hd) >> 4;
+        const int pos = dv.pos0 + c;
+        p.page = a.page_table[pos / kPage];
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr)
+            if (head < a.H + a.KV) p.cs[pr] = a.rope[(size_t)pos * half + t_in * 8 + g * 2 + pr];
+    }
+}
+
+// value tile of one lane: rows n0 + 4 g + r (r = 0..3) of column c
+// PRE: `pre` was filled by epi_prefetch; otherwise the reads happen here
+template <int EPI, int CT, bool PRE>
+__device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile, int g, int c, f32x4 v, float rs,
+                                const EpiPre<EPI>& pre) {
+    const int n = tile * 16 + g * 4;
+    const int w = dv.w;
     if constexpr (EPI == EPI_LOGITS) {
-        const int first = w - a.desc->n_logit;
+        const int first = w - dv.n_logit;
         if (c < first || n >= a.N) return;
-        float* dst = a.Y + (size_t)(a.desc->logit_row0 + c - first) * a.ldy + n;
+        float* dst = a.Y + (size_t)(dv.row0 + c - first) * a.ldy + n;
         if ((a.ldy & 3) == 0 && n + 3 < a.N) {
             *reinterpret_cast<float4*>(dst) = make_float4(v[0] * rs, v[1] * rs, v[2] * rs, v[3] * rs);
         } else {
@@ -400,10 +430,11 @@ __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w
         }
     } else if constexpr (EPI == EPI_RESID) {
         float* dst = a.Y + (size_t)c * a.ldy + n;
-        float4 o = *reinterpret_cast<float4*>(dst);
+        float4 o, gn;
+        if constexpr (PRE) { o = pre.x; gn = pre.gn; } else { o = *reinterpret_cast<const float4*>(dst); }
         o.x += v[0]; o.y += v[1]; o.z += v[2]; o.w += v[3];
         *reinterpret_cast<float4*>(dst) = o;
-        const float4 gn = *reinterpret_cast<const float4*>(a.gain_out + n);
+        if constexpr (!PRE) gn = *reinterpret_cast<const float4*>(a.gain_out + n);
         const float pk[4] = {o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w};
         pack4<CT>(a.xb_out, c, n, pk);
         float ss = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
@@ -418,14 +449,17 @@ __device__ inline void epilogue(const GemmArgs& a, int tile, int g, int c, int w
         // weight rows are permuted inside every head: tile row 2e, 2e + 1 = rotary pair (j, j + hd/2), j = 8 t + e
         const int hd = a.hd, half = hd >> 1;
         const int head = (tile * 16) / hd, t_in = ((tile * 16) % hd) >> 4;
-        const int pos = a.desc->pos0 + c;
-        const int page = a.page_table[pos / kPage], slot = pos % kPage;
+        const int pos = dv.pos0 + c;
+        int page;
+        if constexpr (PRE) page = pre.page; else page = a.page_table[pos / kPage];
+        const int slot = pos % kPage;
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
             const int j = t_in * 8 + g * 2 + pr;
             float x0 = v[2 * pr] * rs, x1 = v[2 * pr + 1] * rs;
             if (head < a.H + a.KV) {
-                const float2 cs = a.rope[(size_t)pos * half + j];
+                float2 cs;
+                if constexpr (PRE) cs = pre.cs[pr]; else cs = a.rope[(size_t)pos * half + j];
                 const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
                 x0 = r0; x1 = r1;
             }
@@ -469,6 +503,21 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     const int tile0 = blockIdx.x * RT, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int k0 = (int)(((long)a.KS * wave) / NW), k1 = (int)(((long)a.KS * (wave + 1)) / NW);
     const int g = lane >> 4, cc = lane & 15;
+    const DescVals dv = load_desc(a.desc);
+    // the epilogue's own reads: the narrow kernels' finishing wave asks for them once its first weights are on the way
+    constexpr bool kEarly = NT <= 2;
+    EpiPre<EPI> pre[kEarly ? RT : 1][kEarly ? NT : 1];
+    bool want_pre = kEarly && wave == 0;
+    auto prefetch_all = [&]() {
+        if constexpr (kEarly) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    if (t * 16 + cc < dv.w) epi_prefetch<EPI>(a, dv, tile0 + r, g, t * 16 + cc, pre[r][t]);
+        }
+        want_pre = false;
+    };
     float ss_mine[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) ss_mine[t] = 0.f;
@@ -516,6 +565,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+        if (want_pre) prefetch_all();
 #pragma unroll
         for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep);
         a_ptr += (size_t)U * 64;
@@ -525,6 +575,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
         u32x4 wv[RT];
 #pragma unroll
         for (int r = 0; r < RT; ++r) wv[r] = __builtin_nontemporal_load(a_ptr + r * tile_stride);
+        if (want_pre) prefetch_all();
         step(wv, b_ptr);
         a_ptr += 64;
         b_ptr += kBStep;
@@ -533,8 +584,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) ssp[wave * 4 + g][t * 16 + cc] = ss_mine[t];
     }
+    if (want_pre) prefetch_all();   // a wave without K steps
     // the waves' partial sums meet in LDS TG column tiles at a time and are added in wave order
-    int w = 0;
+    const int w = dv.w;
 #pragma unroll
     for (int t0 = 0; t0 < NT; t0 += TG) {
         if (t0 > 0) __syncthreads();   // wave 0 has read the previous group
@@ -546,7 +598,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
         }
         __syncthreads();
         if (wave != 0) continue;
-        if (t0 == 0) w = a.desc->w;
 #pragma unroll
         for (int tt = 0; tt < TG; ++tt) {
             const int t = t0 + tt;
@@ -563,7 +614,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
                 for (int v = 0; v < NW - 1; ++v) acc[r][t] += red[v][r][tt][lane];
                 // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
-                if (c < w) epilogue<EPI, CT>(a, tile0 + r, g, c, w, acc[r][t], rs);
+                if (c < w) {
+                    epilogue<EPI, CT, kEarly>(a, dv, tile0 + r, g, c, acc[r][t], rs, pre[kEarly ? r : 0][kEarly ? t : 0]);
+                }
             }
         }
     }
@@ -693,7 +746,8 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
         __syncthreads();
     }
     fold();
-    const int w = a.desc->w;
+    const DescVals dv = load_desc(a.desc);
+    const int w = dv.w;
 #pragma unroll
     for (int t = 0; t < TC; ++t) {
         const int c = cg * GC + (wc * TC + t) * 16 + cc;
@@ -701,7 +755,7 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
         for (int r = 0; r < 4; ++r) {
             const int tile = tile0 + wr * 4 + r;
             // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
-            if (tile < tiles && c < w) epilogue<EPI, CT>(a, tile, g, c, w, tot[r][t], rs[t]);
+            if (tile < tiles && c < w) epilogue<EPI, CT, false>(a, dv, tile, g, c, tot[r][t], rs[t], EpiPre<EPI>{});
         }
     }
 }
@@ -722,7 +776,10 @@ __global__ __launch_bounds__(1024) void gemm_o_narrow(const GemmArgs a, const fl
 #pragma unroll
     for (int u = 0; u < 4; ++u)
         if (k0 + u < k1) wv[u] = __builtin_nontemporal_load(a_ptr + (size_t)u * 64);
-    const int w = a.desc->w, pos0 = a.desc->pos0, K = a.KS * 32;
+    const DescVals dv = load_desc(a.desc);
+    const int w = dv.w, pos0 = dv.pos0, K = a.KS * 32;
+    EpiPre<EPI_RESID> pre;
+    if (wave == 0 && cc < w) epi_prefetch<EPI_RESID>(a, dv, tile, g, cc, pre);   // answered while the partials are merged
     uint16_t* sB16 = reinterpret_cast<uint16_t*>(sB);
     // pairs of adjacent head dims: for one token that is exactly one pair per thread, i.e. one memory round trip
     for (int pidx = threadIdx.x; pidx < 2 * K; pidx += 1024) {
@@ -753,7 +810,7 @@ __global__ __launch_bounds__(1024) void gemm_o_narrow(const GemmArgs a, const fl
     if (wave != 0) return;
 #pragma unroll
     for (int v = 0; v < NW - 1; ++v) acc += red[v][lane];
-    if (cc < w) epilogue<EPI_RESID, 2>(a, tile, g, cc, w, acc, 1.f);
+    if (cc < w) epilogue<EPI_RESID, 2, true>(a, dv, tile, g, cc, acc, 1.f, pre);
 }
 
 // token embedding: x = E[token]; also the first RMSNorm's operand and sum-of-squares partials.  grid d/16, 64 threads
