@@ -446,43 +446,53 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
         const float g0 = v[0] * rs, u0 = v[1] * rs, g1 = v[2] * rs, u1 = v[3] * rs;
         pack2<CT>(a.xb_out, c, tile * 8 + g * 2, g0 / (1.f + expf(-g0)) * u0, g1 / (1.f + expf(-g1)) * u1);
     } else if constexpr (EPI == EPI_QKV) {
-        // weight rows are permuted inside every head: tile row 2e, 2e + 1 = rotary pair (j, j + hd/2), j = 8 t + e
+        // weight rows are permuted inside every head: tile row 2e, 2e + 1 = rotary pair (j, j + hd/2), j = 8 t + e;
+        // a lane holds the pairs j0 and j0 + 1, so every store below covers two adjacent head dims
         const int hd = a.hd, half = hd >> 1;
         const int head = (tile * 16) / hd, t_in = ((tile * 16) % hd) >> 4;
         const int pos = dv.pos0 + c;
         int page;
         if constexpr (PRE) page = pre.page; else page = a.page_table[pos / kPage];
         const int slot = pos % kPage;
+        const int j0 = t_in * 8 + g * 2;
+        float x0[2], x1[2];
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
-            const int j = t_in * 8 + g * 2 + pr;
-            float x0 = v[2 * pr] * rs, x1 = v[2 * pr + 1] * rs;
+            x0[pr] = v[2 * pr] * rs;
+            x1[pr] = v[2 * pr + 1] * rs;
             if (head < a.H + a.KV) {
                 float2 cs;
-                if constexpr (PRE) cs = pre.cs[pr]; else cs = a.rope[(size_t)pos * half + j];
-                const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
-                x0 = r0; x1 = r1;
+                if constexpr (PRE) cs = pre.cs[pr]; else cs = a.rope[(size_t)pos * half + j0 + pr];
+                const float r0 = x0[pr] * cs.x - x1[pr] * cs.y, r1 = x1[pr] * cs.x + x0[pr] * cs.y;
+                x0[pr] = r0; x1[pr] = r1;
             }
-            if (head < a.H) {
-                float* q = a.Y + (size_t)c * a.ldy + (size_t)head * hd;
-                q[j] = x0;
-                q[j + half] = x1;
-            } else if (head < a.H + a.KV) {   // K planes: [slot][hd]
-                uint16_t* kh = a.kv + kv_plane(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
-                uint16_t* kl = kh + (size_t)kPage * hd;
-                const uint16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
-                kh[j] = h0;
-                kh[j + half] = h1;
-                kl[j] = f32_to_bf16(x0 - bf16_to_f32(h0));
-                kl[j + half] = f32_to_bf16(x1 - bf16_to_f32(h1));
-            } else {                          // V planes, transposed: [hd][slot]
-                uint16_t* vh = a.kv + kv_plane(page, a.layer, a.L, head - a.H - a.KV, a.KV, 2, hd);
-                uint16_t* vl = vh + (size_t)kPage * hd;
-                const uint16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+        }
+        auto pack_hi = [](float p, float q) { return (uint32_t)f32_to_bf16(p) | ((uint32_t)f32_to_bf16(q) << 16); };
+        auto pack_lo = [](float p, float q) {
+            return (uint32_t)f32_to_bf16(p - bf16_to_f32(f32_to_bf16(p))) | ((uint32_t)f32_to_bf16(q - bf16_to_f32(f32_to_bf16(q))) << 16);
+        };
+        if (head < a.H) {
+            float* q = a.Y + (size_t)c * a.ldy + (size_t)head * hd;
+            *reinterpret_cast<float2*>(q + j0) = make_float2(x0[0], x0[1]);
+            *reinterpret_cast<float2*>(q + j0 + half) = make_float2(x1[0], x1[1]);
+        } else if (head < a.H + a.KV) {   // K planes: [slot][hd]
+            uint16_t* kh = a.kv + kv_plane(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
+            uint16_t* kl = kh + (size_t)kPage * hd;
+            *reinterpret_cast<uint32_t*>(kh + j0) = pack_hi(x0[0], x0[1]);
+            *reinterpret_cast<uint32_t*>(kh + j0 + half) = pack_hi(x1[0], x1[1]);
+            *reinterpret_cast<uint32_t*>(kl + j0) = pack_lo(x0[0], x0[1]);
+            *reinterpret_cast<uint32_t*>(kl + j0 + half) = pack_lo(x1[0], x1[1]);
+        } else {                          // V planes, transposed: [hd][slot]
+            uint16_t* vh = a.kv + kv_plane(page, a.layer, a.L, head - a.H - a.KV, a.KV, 2, hd);
+            uint16_t* vl = vh + (size_t)kPage * hd;
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {
+                const int j = j0 + pr;
+                const uint16_t h0 = f32_to_bf16(x0[pr]), h1 = f32_to_bf16(x1[pr]);
                 vh[(size_t)j * kPage + slot] = h0;
                 vh[(size_t)(j + half) * kPage + slot] = h1;
-                vl[(size_t)j * kPage + slot] = f32_to_bf16(x0 - bf16_to_f32(h0));
-                vl[(size_t)(j + half) * kPage + slot] = f32_to_bf16(x1 - bf16_to_f32(h1));
+                vl[(size_t)j * kPage + slot] = f32_to_bf16(x0[pr] - bf16_to_f32(h0));
+                vl[(size_t)(j + half) * kPage + slot] = f32_to_bf16(x1[pr] - bf16_to_f32(h1));
             }
         }
     }
