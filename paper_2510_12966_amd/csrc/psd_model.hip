@@ -517,28 +517,31 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     // the epilogue's own reads: the narrow kernels' finishing wave asks for them once its first weights are on the way
     constexpr bool kEarly = NT <= 2;
     EpiPre<EPI> pre[kEarly ? RT : 1][kEarly ? NT : 1];
-    bool want_pre = kEarly && wave == 0;
+    float ss_mine[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) ss_mine[t] = 0.f;
+    // Side reads (sum-of-squares partials for every wave, the epilogue's inputs for the finishing wave) are issued
+    // right after a wave's first weight loads, never before them: the weight stream starts at once.
+    bool want_pre = true;
     auto prefetch_all = [&]() {
+        want_pre = false;
+        if constexpr (kScaled) {
+            const int gi = wave * 4 + g;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll 8
+                for (int st = gi; st < a.ss_tiles; st += 4 * NW) ss_mine[t] += a.ss_in[st * (16 * CT) + t * 16 + cc];
+            }
+        }
         if constexpr (kEarly) {
+            if (wave != 0) return;
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
                     if (t * 16 + cc < dv.w) epi_prefetch<EPI>(a, dv, tile0 + r, g, t * 16 + cc, pre[r][t]);
         }
-        want_pre = false;
     };
-    float ss_mine[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) ss_mine[t] = 0.f;
-    if constexpr (kScaled) {
-        const int gi = wave * 4 + g;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-#pragma unroll 8
-            for (int st = gi; st < a.ss_tiles; st += 4 * NW) ss_mine[t] += a.ss_in[st * (16 * CT) + t * 16 + cc];
-        }
-    }
     const u32x4* a_ptr = a.Wt + ((size_t)tile0 * a.KS + k0) * 64 + lane;
     const size_t tile_stride = (size_t)a.KS * 64;
     constexpr int kBStep = CT * 128;   // 16-byte words of the operand per K step
@@ -590,11 +593,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
         a_ptr += 64;
         b_ptr += kBStep;
     }
+    if (want_pre) prefetch_all();   // a wave without K steps
     if constexpr (kScaled) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) ssp[wave * 4 + g][t * 16 + cc] = ss_mine[t];
     }
-    if (want_pre) prefetch_all();   // a wave without K steps
     // the waves' partial sums meet in LDS TG column tiles at a time and are added in wave order
     const int w = dv.w;
 #pragma unroll
