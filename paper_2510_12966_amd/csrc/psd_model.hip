@@ -1422,8 +1422,9 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
         const bool wide = L.wcls > 16;
         if (tiles <= 256) {
             if (wide) PSD_GEMM(2, 16, 1, 2); else PSD_GEMM(1, 16, 1, 2);
-        } else if (!wide && EPI == EPI_SWIGLU && tiles % 7 == 0 && tiles / 7 >= 256) {
-            PSD_GEMM(1, 8, 7, 2);   // one workgroup per CU for the target's gate/up projection (1792 tiles): 44 us against 47
+        } else if (EPI == EPI_SWIGLU && tiles % 7 == 0 && tiles / 7 >= 256) {
+            // one workgroup per CU for the target's gate/up projection (1792 tiles): 44 us against 47
+            if (wide) PSD_GEMM(2, 8, 7, 2); else PSD_GEMM(1, 8, 7, 2);
         } else if (!wide && EPI == EPI_SWIGLU && tiles == 1024 && a.KS >= 96) {
             PSD_GEMM(1, 8, 4, 2);   // likewise the qualifier's (1024 tiles, K 3072): 20.2 us against 21.1; not for K 2048
         } else if (tiles % 2 == 0) {
