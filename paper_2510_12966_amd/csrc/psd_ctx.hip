@@ -94,8 +94,8 @@ struct psd_ctx {
     int stage_next = 0, stage_since_sync = 0;
     RoundResult* res = nullptr;
     // graphs: [model][width class 4 / 16 / 32]
-    GraphSlot graphs[3][3];
-    GraphSlot chain_graphs[3][3];  // sampling steps: [proposer][model whose pass descriptor receives the tokens]
+    GraphSlot graphs[3][kNumNarrowClasses];   // [model][launch class]
+    GraphSlot chain_graphs[3][3][kNumNarrowClasses];  // sampling steps: [proposer][model whose pass descriptor receives the tokens][launch class]
     Profiler prof;
     StageTimer timer;
     psd_trace_fn trace = nullptr;
@@ -141,8 +141,9 @@ static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
     return PSD_OK;
 }
 
-// launch class of a pass of w tokens: 4, 16, 32, or (prompt ingestion only) the next multiple of 128
-static int wclass(int w) { return w <= 4 ? 4 : (w <= 16 ? 16 : (w <= kMaxW ? 32 : (w + 127) / 128 * 128)); }
+// launch class of a pass of w tokens: the smallest narrow class that holds it, or (prompt ingestion only) the next
+// multiple of 128
+static int wclass(int w) { return w <= kMaxW ? kNarrowClasses[narrow_class_index(w)] : (w + 127) / 128 * 128; }
 
 // bytes of a pass descriptor that have to travel: the header and the token slots the pass can read
 static size_t desc_bytes(const PassDesc& d) {
@@ -170,7 +171,7 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
         return PSD_OK;
     };
     if (!use_graph) return enqueue(&c->prof);
-    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier] : c->graphs[mi][wcls == 4 ? 0 : (wcls == 16 ? 1 : 2)];
+    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier][narrow_class_index(wcls)] : c->graphs[mi][narrow_class_index(wcls)];
     if (!g.exec) {
         hipGraph_t graph = nullptr;
         PSD_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal), c->err);
@@ -189,9 +190,10 @@ static void drop_graphs(psd_ctx* c) {
     for (auto& row : c->graphs)
         for (auto& g : row)
             if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
-    for (auto& row : c->chain_graphs)
-        for (auto& g : row)
-            if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+    for (auto& plane : c->chain_graphs)
+        for (auto& row : plane)
+            for (auto& g : row)
+                if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
 }
 
 // host-known tokens seq[from, to) go into a pass descriptor that starts at KV row `from`
@@ -499,8 +501,9 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             if ((rc = upload(c, Q.desc, &qd, desc_bytes(qd))) != PSD_OK) return rc;
             if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
             c->timer.begin(c->stream, 0);
+            // the first step also ingests what the draft has not cached (1 to 3 tokens), the others one token each
             for (int i = 0; i < m; ++i)
-                if ((rc = run_pass(c, 0, 4, c->DL, true, true)) != PSD_OK) return rc;
+                if ((rc = run_pass(c, 0, wclass(i == 0 ? L - D.len : 1), c->DL, true, true)) != PSD_OK) return rc;
             c->timer.end(c->stream);
             st.passes_d += m;
             c->timer.begin(c->stream, 1);
@@ -660,7 +663,7 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
         if ((rc = upload(c, c->chain, &sc, sizeof(sc))) != PSD_OK) return rc;
         c->timer.begin(c->stream, proposer);
         for (int i = 0; i < k; ++i)
-            if ((rc = run_pass(c, proposer, 4, c->QL, true, true, 2)) != PSD_OK) return rc;
+            if ((rc = run_pass(c, proposer, wclass(i == 0 ? C - P.len : 1), c->QL, true, true, 2)) != PSD_OK) return rc;
         c->timer.end(c->stream);
         (proposer == 0 ? st.passes_d : st.passes_q) += k;
         c->timer.begin(c->stream, 2);
@@ -729,7 +732,7 @@ extern "C" int psd_generate_plain(psd_ctx* c, int32_t which, const int32_t* prom
         PassDesc d;
         fill_desc(d, seq.data(), M.len, L, 0, 1, 0);
         if ((rc = upload(c, M.desc, &d, desc_bytes(d))) != PSD_OK) return rc;
-        if ((rc = run_pass(c, which, 4, c->HL, false)) != PSD_OK) return rc;
+        if ((rc = run_pass(c, which, wclass(L - M.len), c->HL, false)) != PSD_OK) return rc;
         if ((rc = sample_launch(c->HL, 1, c->V, c->prm.temperature, seed, (uint32_t)L, nullptr, c->samp_tok, c->samp_part, c->stream, c->err,
                                 (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0)) != PSD_OK) return rc;
         PSD_HIP(hipMemcpyAsync(c->res->tok, c->samp_tok, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream), c->err);

@@ -15,6 +15,17 @@ constexpr int kMaxW = PSD_MAX_WIDTH;   // widest pass that can produce logits (a
 constexpr int kCols = 512;             // widest pass at all: prompt ingestion of bf16 models, no logits
 constexpr int kWideCT = kCols / 16;    // column tiles of the operand buffers those passes use
 
+// Launch classes of the passes that can produce logits: a pass of w tokens is launched as the smallest class >= w.
+// Kernels never load operand columns beyond their class, so a finer class moves fewer bytes; each class has its own
+// captured graph.
+constexpr int kNarrowClasses[] = {1, 2, 4, 6, 8, 12, 16, 24, 32};
+constexpr int kNumNarrowClasses = sizeof(kNarrowClasses) / sizeof(kNarrowClasses[0]);
+inline int narrow_class_index(int w) {   // -1 when w is wider than the widest class
+    for (int i = 0; i < kNumNarrowClasses; ++i)
+        if (w <= kNarrowClasses[i]) return i;
+    return -1;
+}
+
 // What one forward pass has to do; lives in DEVICE memory so that a captured graph can be replayed
 // with new contents.  Written by the host before a pass, or by the sampling kernel for the draft chain.
 struct PassDesc {
@@ -115,7 +126,7 @@ int model_init(Model& M, const psd_model_desc& desc, const char* tag, int max_se
 // Makes sure KV pages exist for positions < upto and frees pages wholly beyond `keep`; uploads the table if it changed.
 int model_map_pages(Model& M, int keep, int upto, hipStream_t stream, char* err);
 
-// Enqueues one pass described by *M.desc (already on the device).  wmax: 4, 16 or 32 = widest pass the launch must cover;
+// Enqueues one pass described by *M.desc (already on the device).  wmax: one of kNarrowClasses = widest pass the launch must cover;
 // 128, 256, 384 or 512 (bf16 models, logits == nullptr): prompt ingestion.
 // logits: device [rows][V] destination (may be null when the pass produces none).
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err);

@@ -343,7 +343,7 @@ struct GemmArgs {
     const u32x4* Wt;       // tiled weights [Npad/16][KS][64] x 16 B
     const u32x4* XB;       // packed activations [KS][CT][2][64] x 16 B
     int N, KS;
-    int wcap;              // widest pass this launch is meant for (4, 16 or 32): operand columns >= wcap are not loaded
+    int wcap;              // widest pass this launch is meant for (its launch class): operand columns >= wcap are not loaded
     const PassDesc* desc;
     // rms scale of the input (EPI_QKV, EPI_SWIGLU, EPI_LOGITS): partial sums of squares [d/16][16 CT]
     const float* ss_in;
@@ -1317,7 +1317,7 @@ struct Launch {
     Model& M;
     hipStream_t s;
     Profiler* prof;
-    int wcls;  // 16 or 32
+    int wcls;  // launch class: one of kNarrowClasses, or a multiple of 128
     char name[48];
     void begin(const char* family, double bytes) {
         if (!prof || !prof->on) return;
@@ -1505,7 +1505,7 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
 
 int model_forward(Model& M, int wmax, float* logits, hipStream_t stream, Profiler* prof, char* err) {
     const bool ingest = wmax > kMaxW;
-    if (ingest ? (wmax % 128 != 0 || wmax > M.ingest_max) : (wmax != 4 && wmax != 16 && wmax != 32))
+    if (ingest ? (wmax % 128 != 0 || wmax > M.ingest_max) : (narrow_class_index(wmax) < 0 || kNarrowClasses[narrow_class_index(wmax)] != wmax))
         PSD_FAIL(PSD_EINVAL, err, "forward: width class %d", wmax);
     if (ingest && (M.dtype != PSD_BF16 || logits)) PSD_FAIL(PSD_EINVAL, err, "forward: passes wider than %d tokens are for bf16 prompt ingestion only", kMaxW);
     Launch L{M, stream, prof, wmax, {0}};
