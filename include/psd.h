@@ -160,7 +160,7 @@ int psd_generate_sd(psd_ctx* ctx, int32_t proposer, int32_t k, float tau, const 
 
 /* Per-step statistics of the behaviour analysis (Section 4): entropy in nats and largest probability of
  * softmax(row / temperature) for n_rows logits rows [n_rows][vocab].  where: 0 host pointers, 1 device pointers
- * (device logits must be 16-byte aligned).  entropy, max_prob: [n_rows] floats. */
+ * (device logits must be 16-byte aligned; 4-byte when the vocabulary is not a multiple of 4).  entropy, max_prob: [n_rows] floats. */
 int psd_row_stats(const float* logits, int32_t n_rows, int32_t vocab, float temperature, int32_t where,
                   float* entropy, float* max_prob);
 

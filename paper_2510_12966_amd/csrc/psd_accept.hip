@@ -567,8 +567,10 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     if (workspace_bytes < accept_workspace_bytes(n_trials, k, vocab))
         PSD_FAIL(PSD_ENOMEM, errbuf, "accept: workspace %zu < %zu bytes", workspace_bytes,
                  accept_workspace_bytes(n_trials, k, vocab));
-    if (((uintptr_t)workspace & 15) || ((uintptr_t)logits_p & 15) || ((uintptr_t)logits_q & 15))
-        PSD_FAIL(PSD_EINVAL, errbuf, "accept: logits and workspace must be 16-byte aligned");
+    // rows are read 16 bytes at a time only when every row starts on a 16-byte boundary (vocabulary a multiple of 4)
+    const uintptr_t row_mask = (vocab & 3) == 0 ? 15 : 3;
+    if (((uintptr_t)workspace & 15) || ((uintptr_t)logits_p & row_mask) || (logits_q && ((uintptr_t)logits_q & row_mask)))
+        PSD_FAIL(PSD_EINVAL, errbuf, "accept: workspace must be 16-byte aligned, logits %d-byte aligned", (int)row_mask + 1);
     const int nch = accept_chunks(vocab), nsw = sweep_chunks(vocab);
     const int pairs = n_trials * k;
     if ((long long)pairs * nsw > 0x7fffffffLL) PSD_FAIL(PSD_EINVAL, errbuf, "accept: n_trials * k * chunks overflows the grid");
@@ -662,7 +664,7 @@ int sample_launch(const float* logits, int n_rows, int vocab, float temperature,
     if (!logits || !tokens_out || !partial) PSD_FAIL(PSD_EINVAL, errbuf, "sample: null pointer");
     if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
         PSD_FAIL(PSD_EINVAL, errbuf, "sample: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
-    if ((uintptr_t)logits & 15) PSD_FAIL(PSD_EINVAL, errbuf, "sample: logits must be 16-byte aligned");
+    if ((uintptr_t)logits & ((vocab & 3) == 0 ? 15 : 3)) PSD_FAIL(PSD_EINVAL, errbuf, "sample: logits rows must be 16-byte aligned (4-byte when the vocabulary is not a multiple of 4)");
     const int nch = accept_chunks(vocab);
     sample_partial<<<dim3(nch, n_rows), kAccThreads, 0, stream>>>(logits, vocab, nch, 1.0f / temperature, seed,
                                                                    position0, ctl, (KeyIdx*)partial, greedy);
@@ -755,7 +757,7 @@ int row_stats_launch(const float* logits, int n_rows, int vocab, float temperatu
     if (!logits || !workspace) PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: null pointer");
     if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
         PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
-    if ((uintptr_t)logits & 15) PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: logits must be 16-byte aligned");
+    if ((uintptr_t)logits & ((vocab & 3) == 0 ? 15 : 3)) PSD_FAIL(PSD_EINVAL, errbuf, "row_stats: logits rows must be 16-byte aligned (4-byte when the vocabulary is not a multiple of 4)");
     const int nch = accept_chunks(vocab);
     row_stats_partial<<<dim3(nch, n_rows), kAccThreads, 0, stream>>>(logits, vocab, nch, 1.0f / temperature,
                                                                     (StatPart*)workspace);

@@ -247,3 +247,54 @@ def test_generation_survives_expired_waits(tiny_stack):
     finally:
         psd.set_accept_path(0)
     ctx.close()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_randomised_bf16_stacks_replay(case):
+    """Seeded random shapes, windows, thresholds and prompt lengths (through the 128- and 512-token ingestion passes
+    and every narrow launch class): each sampling step and ACCEPT stage is replayed through the oracle on the GPU's
+    own logits, and the target's logits over the finished sequence are compared with the oracle's forward."""
+    from paper_2510_12966_amd.synth import ModelShape
+    rng = np.random.default_rng(1000 + case)
+    vocab = int(rng.choice([1000, 2051, 4096]))
+
+    def shape():
+        d = int(rng.choice([256, 512]))
+        h, kv = [(4, 2), (8, 2), (4, 4), (8, 8)][int(rng.integers(4))]
+        return ModelShape(int(rng.integers(1, 4)), d, h, kv, int(rng.choice([352, 704, 1024])), vocab)
+
+    shapes = (shape(), shape(), shape())
+    blobs = [synth.target_weights(s, 500 + 10 * case + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    k1, k2 = int(rng.integers(1, 9)), int(rng.integers(1, 13))
+    T_q, T_t = float(rng.uniform(0.0, 0.3)), float(rng.uniform(0.0, 0.3))
+    temp = float(rng.choice([1.0, 0.7]))
+    n_prompt, n_new = int(rng.choice([3, 40, 150, 600])), 30
+    prompt = synth.tokens(77 + case, 0, n_prompt, vocab)
+    max_seq = n_prompt + n_new + k2 + 2
+    descs = [_desc(s, b, synth.DTYPE_BF16, 10000.0) for s, b in zip(shapes, blobs)]
+    ctx = psd.Context(descs[0], descs[1], descs[2], T_q, T_t, k1, k2, max_seq, temperature=temp,
+                      flags=psd.FLAG_GRAPH if case % 2 else 0)
+    rp = Replay(case, T_q, T_t, temp)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, case)
+    ctx.set_trace(None)
+    print("case", case, shapes, "k1", k1, "k2", k2, "T", round(T_q, 3), round(T_t, 3), "prompt", n_prompt, st, "ties", rp.ties, flush=True)
+    assert rp.events >= 3 and rp.ties <= 1
+    assert out.size == n_new and (out >= 0).all() and (out < vocab).all()
+    assert st["accepted_q"] <= st["proposed_q"] and st["accepted_t"] <= st["proposed_t"]
+    seq = np.concatenate([prompt, out]).astype(np.int32)
+    om = oracle.Model(shapes[2], blobs[2], synth.DTYPE_BF16, 10000.0, max_seq)
+    ref = om.forward(seq, 0)[-4:]
+    pos, widest = 0, 512
+    while pos < len(seq) - 4:                       # re-ingest in the widest passes this model takes, then 4 logit rows
+        w = min(widest, len(seq) - 4 - pos)
+        try:
+            ctx.forward(2, seq[pos:pos + w], pos, want_logits=False)
+        except psd.PsdError:
+            assert widest == 512                    # a model with very short projections stays at 128-token passes
+            widest = 128
+            continue
+        pos += w
+    got = ctx.forward(2, seq[-4:], len(seq) - 4)
+    assert np.abs(got - ref).max() <= 3e-2
+    ctx.close()
