@@ -284,3 +284,61 @@ def test_greedy_loop_is_lossless_on_a_bf16_stack():
     assert np.array_equal(sd, want)
     print("greedy small stack:", st, st2, flush=True)
     ctx.close()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_randomised_bf16_stacks_variants(case):
+    """Seeded random bf16 shapes (ragged vocabularies included), windows, temperatures and prompt lengths through
+    the two-model baseline, the assisted loop and greedy decoding: every step decided again by the oracle on the
+    GPU's own logits; greedy runs must also equal the target's own greedy continuation bit for bit, whatever mix
+    of launch classes and ingestion widths produced the caches."""
+    from paper_2510_12966_amd.synth import ModelShape
+    rng = np.random.default_rng(2000 + case)
+    vocab = int(rng.choice([1000, 2051, 4096]))
+
+    def shape():
+        d = int(rng.choice([256, 512]))
+        h, kv = [(4, 2), (8, 2), (4, 4), (8, 8)][int(rng.integers(4))]
+        return ModelShape(int(rng.integers(1, 4)), d, h, kv, int(rng.choice([352, 704, 1024])), vocab)
+
+    shapes = (shape(), shape(), shape())
+    blobs = [synth.target_weights(s, 700 + 10 * case + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    k1, k2 = int(rng.integers(1, 9)), int(rng.integers(1, 13))
+    tau = float(rng.uniform(0.0, 0.3))
+    temp = float(rng.choice([1.0, 0.7]))
+    n_prompt, n_new = int(rng.choice([3, 40, 150, 600])), 30
+    prompt = synth.tokens(177 + case, 0, n_prompt, vocab)
+    max_seq = n_prompt + n_new + max(k1, k2) + 2
+    descs = [_desc(s, b, synth.DTYPE_BF16, 10000.0) for s, b in zip(shapes, blobs)]
+    graph = psd.FLAG_GRAPH if case % 2 else 0
+    mode = case % 3
+    flags = graph | (psd.FLAG_ASSISTED if mode == 1 else 0) | (psd.FLAG_GREEDY if mode == 2 else 0)
+    ctx = psd.Context(descs[0], descs[1], descs[2], tau, tau, k1, k2, max_seq, temperature=temp, flags=flags)
+    if mode == 0:
+        proposer = int(rng.integers(2))
+        rp = Replay(case, tau, temp)
+        ctx.set_trace(rp)
+        k = min(k1, k2)                     # the baseline's window is bounded by the context's k2
+        out, st = ctx.generate_sd(proposer, k, tau, prompt, n_new, case)
+        ctx.set_trace(None)
+        assert rp.kinds == 0b101 and rp.ties <= 1
+        assert st["proposed_t"] == k * st["passes_t"]
+    elif mode == 1:
+        rp = Replay(case, tau, temp)
+        ctx.set_trace(rp)
+        out, st = ctx.generate(prompt, n_new, case)
+        ctx.set_trace(None)
+        assert rp.kinds == 0b1101 and rp.ties <= 1 and st["fuzzy_q"] == 0
+    else:
+        rp = GreedyReplay()
+        ctx.set_trace(rp)
+        out, st = ctx.generate(prompt, n_new, case)
+        ctx.set_trace(None)
+        assert rp.kinds == (1 << 4) | (1 << 5) | (1 << 6)
+        want, _ = ctx.generate_plain(2, prompt, n_new, 0)
+        assert np.array_equal(out, want)
+        sd, _ = ctx.generate_sd(int(rng.integers(2)), min(k1, k2), 0.0, prompt, n_new, 0)
+        assert np.array_equal(sd, want)
+    print("case", case, "mode", mode, shapes, "k1", k1, "k2", k2, "tau", round(tau, 3), "prompt", n_prompt, st, flush=True)
+    assert out.size == n_new and (out >= 0).all() and (out < vocab).all()
+    ctx.close()
