@@ -301,3 +301,46 @@ def test_randomised_stacks_replay(case):
     got = ctx.forward(2, seq[-4:], len(seq) - 4)
     assert np.abs(got - ref).max() <= tol
     ctx.close()
+
+
+@pytest.mark.parametrize("case", range(4))
+def test_randomised_medium_stacks_long_context(case):
+    """Head dimension 128, query groups of up to 8, contexts past 1000 tokens on scrambled pages: replay of every
+    stage through the oracle, and the bit-for-bit agreement of the widest ingestion passes with 32-token passes."""
+    from paper_2510_12966_amd.synth import ModelShape
+    rng = np.random.default_rng(3000 + case)
+    vocab = int(rng.choice([4099, 32000]))
+
+    def shape():
+        d = int(rng.choice([1024, 2048]))
+        h = d // 128
+        kv = int(rng.choice([k for k in (1, 2, 4, 8) if h % k == 0 and k <= h]))
+        return ModelShape(int(rng.integers(1, 3)), d, h, kv, int(rng.choice([2816, 5632])), vocab)
+
+    shapes = (shape(), shape(), shape())
+    blobs = [synth.target_weights(s, 900 + 10 * case + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    k1, k2 = int(rng.integers(2, 9)), int(rng.integers(4, 17))
+    T_q, T_t = float(rng.uniform(0.0, 0.3)), float(rng.uniform(0.0, 0.3))
+    n_prompt, n_new = int(rng.choice([700, 1300])), 24
+    prompt = synth.tokens(277 + case, 0, n_prompt, vocab)
+    max_seq = n_prompt + n_new + k2 + 2
+    descs = [_desc(s, b, synth.DTYPE_BF16, 500000.0) for s, b in zip(shapes, blobs)]
+    ctx = psd.Context(descs[0], descs[1], descs[2], T_q, T_t, k1, k2, max_seq, flags=psd.FLAG_GRAPH | 0x100)
+    rp = Replay(case, T_q, T_t)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, case)
+    ctx.set_trace(None)
+    print("case", case, shapes, "k1", k1, "k2", k2, "T", round(T_q, 3), round(T_t, 3), "prompt", n_prompt, st, "ties", rp.ties, flush=True)
+    assert rp.events >= 3 and rp.ties <= 1 and out.size == n_new
+    seq = np.concatenate([prompt, out]).astype(np.int32)
+    n = len(seq) - 4
+    for which in range(3):
+        rows = []
+        for widths in ([512] * (n // 512) + ([n % 512] if n % 512 else []), [32] * (n // 32) + ([n % 32] if n % 32 else [])):
+            pos = 0
+            for w in widths:
+                ctx.forward(which, seq[pos:pos + w], pos, want_logits=False)
+                pos += w
+            rows.append(ctx.forward(which, seq[n:], n))
+        assert np.array_equal(rows[0], rows[1])
+    ctx.close()
