@@ -240,3 +240,47 @@ def test_accept_statistics_over_many_trials():
         means.append(float(na.mean()))
     assert ties <= 3
     assert means[0] < means[1] < means[2] and means[0] > 0.05 and means[2] < k
+
+
+def test_accept_randomised_shapes_and_row_patterns():
+    """40 seeded random (vocabulary, window, temperature, threshold) settings, 6 trials each, rows that are flat,
+    peaked, masked with -inf, or equal in both stacks: every trial against the oracle."""
+    rng = np.random.default_rng(23)
+    ties = total = 0
+    for case in range(40):
+        V = int(rng.choice([1, 2, 3, 5, 64, 257, 1000, 4099, 5120, 5121, 10240, 20011]))
+        k = int(rng.integers(0, 13))
+        B = 6
+        temp = float(rng.choice([1.0, 0.7, 1.5]))
+        T = float(rng.choice([0.0, 0.05, 0.2, 0.5, math.log(2)]))
+        scale = float(rng.choice([0.3, 3.0, 12.0]))            # flat ... sharply peaked
+        P = (scale * rng.standard_normal((B, k + 1, V))).astype(np.float32)
+        rho = float(rng.choice([0.0, 0.8, 1.0]))               # rho 1: both stacks equal, divergence exactly 0
+        Q = (rho * P[:, :k] + math.sqrt(1 - rho * rho) * scale * rng.standard_normal((B, k, V))).astype(np.float32)
+        if V > 4 and rng.random() < 0.4:                        # the same masked entries in both stacks
+            mask = rng.random(V) < 0.3
+            mask[int(rng.integers(V))] = False
+            P[:, :, mask] = -np.inf
+            Q[:, :, mask] = -np.inf
+        X = np.zeros((B, k), dtype=np.int32)
+        for b in range(B):
+            for i in range(k):
+                X[b, i] = oracle.sample_row(Q[b, i], temp, 50 + b, 1000 + i)[0]
+        bonus = bool(rng.integers(2))
+        stage = int(rng.integers(1, 3))
+        if k == 0:
+            for b in range(B):
+                total += 1
+                ties += _compare(P[b], Q[b], X[b], T, temp, 100 + b, 7, stage, True) == "tie"
+            continue
+        na, nt, dv = _batched(list(P), list(Q), list(X), T, temp, 100, 7, stage, bonus)
+        for b in range(B):
+            total += 1
+            res, odiv = oracle.accept(P[b], Q[b], X[b], T, temp, 100 + b, 7, stage, bonus)
+            assert np.abs(dv[b] - odiv).max(initial=0.0) <= DIV_TOL, (case, V, k)
+            if rho == 1.0:
+                assert (dv[b] == 0.0).all() and na[b] == k
+            if na[b] != res.n_accepted or nt[b] != res.next_token:
+                assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN or res.margin_race < TIE_RACE, (case, V, k, b)
+                ties += 1
+    assert total == 240 and ties <= 4
