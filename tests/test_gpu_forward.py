@@ -155,6 +155,27 @@ def test_bf16_prompt_ingestion_in_512_token_passes_is_bit_exact():
     ctx.close()
 
 
+def test_bf16_ingestion_at_page_split_and_pass_boundaries():
+    # prompt lengths around the KV page (64), the attention key range (128) and the pass widths (128, 512):
+    # the widest passes, 32-token passes and a ragged mix leave identical logits for the tokens that follow
+    shapes = WIDE
+    blobs = [synth.target_weights(s, 40 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 1100)
+    toks = synth.tokens(12, 0, 1100, 1000)
+    for n in (1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 511, 512, 513, 640, 1023, 1024, 1025):
+        for which in (1, 2):
+            rows = []
+            for chunk in (512, 32, 100):
+                pos = 0
+                while pos < n:
+                    w = min(chunk, n - pos)
+                    ctx.forward(which, toks[pos:pos + w], pos, want_logits=False)
+                    pos += w
+                rows.append(ctx.forward(which, toks[n:n + 3], n))
+            assert np.array_equal(rows[0], rows[1]) and np.array_equal(rows[0], rows[2]), (n, which)
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
