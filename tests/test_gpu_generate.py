@@ -276,11 +276,16 @@ def test_randomised_stacks_replay(case):
     max_seq = n_prompt + n_new + k2 + 2
     descs = [_desc(s, b, dtype, 10000.0) for s, b in zip(shapes, blobs)]
     ctx = psd.Context(descs[0], descs[1], descs[2], T_q, T_t, k1, k2, max_seq, temperature=temp,
-                      flags=psd.FLAG_GRAPH if case % 2 else 0)
+                      flags=(psd.FLAG_GRAPH if case % 2 else 0) | (psd.FLAG_ROW_STATS if case % 3 == 0 else 0))
     rp = Replay(case, T_q, T_t, temp)
     ctx.set_trace(rp)
     out, st = ctx.generate(prompt, n_new, case)
     ctx.set_trace(None)
+    if case % 3 == 0:      # the behaviour statistics ride along: one row per draft step, per judged qualifier / target row
+        rs = ctx.row_stats()
+        assert rs["draft"][0] == st["passes_d"] and rs["qualifier"][0] > 0 and rs["target"][0] > 0
+        for rows, h, pmax in rs.values():
+            assert 0.0 < h <= np.log(vocab) + 1e-4 and 1.0 / vocab - 1e-7 <= pmax <= 1.0
     print("case", case, shapes, "k1", k1, "k2", k2, "T", round(T_q, 3), round(T_t, 3), "prompt", n_prompt, st, "ties", rp.ties, flush=True)
     assert rp.events >= 3 and rp.ties <= 1
     assert out.size == n_new and (out >= 0).all() and (out < vocab).all()
