@@ -349,3 +349,24 @@ def test_randomised_medium_stacks_long_context(case):
             rows.append(ctx.forward(which, seq[n:], n))
         assert np.array_equal(rows[0], rows[1])
     ctx.close()
+
+
+def test_two_contexts_alive_at_once_do_not_disturb_each_other(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    from paper_2510_12966_amd.synth import ModelShape
+    a = _ctx(cfg, (d, q, t), 16 + 32 + 10, 0.004, 0.012, 4, 8, flags=psd.FLAG_GRAPH)
+    ref_a, _ = a.generate(prompt, 32, 2)
+    shapes = (ModelShape(1, 256, 4, 2, 352, 1000), ModelShape(2, 512, 8, 2, 704, 1000), ModelShape(1, 512, 4, 4, 1024, 1000))
+    blobs = [synth.target_weights(s, 60 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    descs = [_desc(s, w, synth.DTYPE_BF16, 10000.0) for s, w in zip(shapes, blobs)]
+    b = psd.Context(descs[0], descs[1], descs[2], 0.1, 0.1, 3, 6, 200 + 32 + 8, flags=psd.FLAG_GRAPH)
+    pb = synth.tokens(5, 0, 200, 1000)
+    ref_b, _ = b.generate(pb, 32, 3)
+    for _ in range(2):      # interleaved calls on both contexts repeat their own answers
+        out_a, _ = a.generate(prompt, 32, 2)
+        out_b, _ = b.generate(pb, 32, 3)
+        assert np.array_equal(out_a, ref_a) and np.array_equal(out_b, ref_b)
+    a.close()
+    out_b, _ = b.generate(pb, 32, 3)
+    assert np.array_equal(out_b, ref_b)
+    b.close()
