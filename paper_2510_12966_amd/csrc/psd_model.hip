@@ -554,7 +554,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = (NT > 2 ? (NW > 8 ? 4 : 8) : 16) / RT;   // weight loads of 16 bytes in flight per lane and row tile
+    // K steps per batch: about 16 weight loads of 16 bytes in flight per lane; 28 with seven row tiles per wave (one
+    // workgroup per CU, so registers do not limit residency there; measured: 71 -> 67 ms per 1504 launches); for the
+    // four-tile variant 24 or 32 in flight were slower than 16
+    constexpr int U = RT == 7 ? 4 : (NT > 2 ? (NW > 8 ? 4 : 8) : 16) / RT;
     static_assert(U >= 1, "too many row tiles per wave");
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
     auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp) {
@@ -571,27 +574,31 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             }
         }
     };
-    int ks = k0;
-    for (; ks + U <= k1; ks += U) {
+    // batches of U K steps; the last batch of a range may be short (its loads still go out together)
+    for (int ks = k0; ks < k1; ks += U) {
         u32x4 wv[U][RT];
+        if (ks + U <= k1) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
-        if (want_pre) prefetch_all();
+                for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+            if (want_pre) prefetch_all();
 #pragma unroll
-        for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep);
+            for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ks + u < k1) {
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+                }
+            if (want_pre) prefetch_all();
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ks + u < k1) step(wv[u], b_ptr + (size_t)u * kBStep);
+        }
         a_ptr += (size_t)U * 64;
         b_ptr += (size_t)U * kBStep;
-    }
-    for (; ks < k1; ++ks) {
-        u32x4 wv[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) wv[r] = __builtin_nontemporal_load(a_ptr + r * tile_stride);
-        if (want_pre) prefetch_all();
-        step(wv, b_ptr);
-        a_ptr += 64;
-        b_ptr += kBStep;
     }
     if (want_pre) prefetch_all();   // a wave without K steps
     if constexpr (kScaled) {
@@ -1420,13 +1427,20 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
         }
     } else {
         const bool wide = L.wcls > 16;
-        if (tiles <= 256) {
+        bool done = false;
+        if constexpr (EPI == EPI_SWIGLU) {   // shapes measured one by one; only the gate/up kernels have such variants
+            if (tiles % 7 == 0 && tiles / 7 >= 256) {
+                // one workgroup per CU for the target's gate/up projection (1792 tiles): 44 us against 47
+                if (wide) PSD_GEMM(2, 8, 7, 2); else PSD_GEMM(1, 8, 7, 2);
+                done = true;
+            } else if (!wide && tiles == 1024 && a.KS >= 96) {
+                PSD_GEMM(1, 8, 4, 2);   // likewise the qualifier's (1024 tiles, K 3072): 20.2 us against 21.1; not for K 2048
+                done = true;
+            }
+        }
+        if (done) {
+        } else if (tiles <= 256) {
             if (wide) PSD_GEMM(2, 16, 1, 2); else PSD_GEMM(1, 16, 1, 2);
-        } else if (EPI == EPI_SWIGLU && tiles % 7 == 0 && tiles / 7 >= 256) {
-            // one workgroup per CU for the target's gate/up projection (1792 tiles): 44 us against 47
-            if (wide) PSD_GEMM(2, 8, 7, 2); else PSD_GEMM(1, 8, 7, 2);
-        } else if (!wide && EPI == EPI_SWIGLU && tiles == 1024 && a.KS >= 96) {
-            PSD_GEMM(1, 8, 4, 2);   // likewise the qualifier's (1024 tiles, K 3072): 20.2 us against 21.1; not for K 2048
         } else if (tiles % 2 == 0) {
             if (wide) PSD_GEMM(2, 8, 2, 2); else PSD_GEMM(1, 8, 2, 2);
         } else {
