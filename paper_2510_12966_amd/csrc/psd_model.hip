@@ -560,11 +560,28 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     constexpr int U = RT == 7 ? 4 : (NT > 2 ? (NW > 8 ? 4 : 8) : 16) / RT;
     static_assert(U >= 1, "too many row tiles per wave");
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp) {
+    // kBPre: the operand blocks of a whole batch are asked for together with its weights (they come from L2 and are
+    // there long before the weights); otherwise a step loads its own, one L2 round trip per step.  Costs up to 64
+    // registers, so it is on only in the variants that run at most one workgroup per CU anyway (q/k/v of the
+    // qualifier 39.8 -> 34.7 ms per 2632 launches); with it the draft's gate/up and the LM heads lose residency and
+    // get slower (17.6 -> 18.5 us)
+    constexpr bool kBPre = NT == 1 && U <= 8 && (RT >= 4 || EPI == EPI_QKV);
+    u32x4 bpre[kBPre ? U : 1][kBPre ? NT : 1][2];
+    auto load_b = [&](int u, const u32x4* bp) {
+        if constexpr (kBPre) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                bpre[u][t][0] = zero; bpre[u][t][1] = zero;
+                if (col_live[t]) { bpre[u][t][0] = bp[t * 128]; bpre[u][t][1] = bp[t * 128 + 64]; }
+            }
+        }
+    };
+    auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp, int u) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             u32x4 bh = zero, bl = zero;
-            if (col_live[t]) { bh = bp[t * 128]; bl = bp[t * 128 + 64]; }
+            if constexpr (kBPre) { bh = bpre[u][t][0]; bl = bpre[u][t][1]; }
+            else if (col_live[t]) { bh = bp[t * 128]; bl = bp[t * 128 + 64]; }
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
                 acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
@@ -582,20 +599,23 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+#pragma unroll
+            for (int u = 0; u < U; ++u) load_b(u, b_ptr + (size_t)u * kBStep);
             if (want_pre) prefetch_all();
 #pragma unroll
-            for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep);
+            for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep, u);
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (ks + u < k1) {
 #pragma unroll
                     for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+                    load_b(u, b_ptr + (size_t)u * kBStep);
                 }
             if (want_pre) prefetch_all();
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ks + u < k1) step(wv[u], b_ptr + (size_t)u * kBStep);
+                if (ks + u < k1) step(wv[u], b_ptr + (size_t)u * kBStep, u);
         }
         a_ptr += (size_t)U * 64;
         b_ptr += (size_t)U * kBStep;
