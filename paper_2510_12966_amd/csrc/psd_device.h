@@ -106,9 +106,20 @@ __device__ inline KeyIdx block_best(KeyIdx v, KeyIdx* sm) {
 
 // ---- bf16 ------------------------------------------------------------------
 __device__ inline float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
-__device__ inline uint16_t f32_to_bf16(float f) { // round to nearest even (finite inputs)
-    uint32_t x = __float_as_uint(f);
-    return (uint16_t)((x + 0x7FFFu + ((x >> 16) & 1u)) >> 16);
+// float -> bf16, round to nearest even, on the hardware's packed conversion.  For every input that is not a NaN
+// (denormals and infinities included) it returns what the integer form (x + 0x7FFF + bit 16 of x) >> 16 returns:
+// compared on the device over all 2^32 bit patterns.
+typedef float psd_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 psd_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t f32x2_to_bf16(float a, float b) {   // a in the low half
+    const psd_f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, psd_bf16x2));
+}
+__device__ inline uint16_t f32_to_bf16(float f) { return (uint16_t)f32x2_to_bf16(f, f); }
+// two values as bf16 hi + lo pairs (value = hi + lo to 2^-17 relative), each pair packed with a in the low half
+__device__ inline void f32x2_split(float a, float b, uint32_t& hi, uint32_t& lo) {
+    hi = f32x2_to_bf16(a, b);
+    lo = f32x2_to_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
 }
 
 }  // namespace psd

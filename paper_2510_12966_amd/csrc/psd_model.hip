@@ -367,20 +367,20 @@ template <int CT>
 __device__ inline void pack4(void* xb, int c, int f0, const float v[4]) {
     const int ks = f0 >> 5, gq = (f0 & 31) >> 3, e = f0 & 7, t = c >> 4, cc = c & 15;
     uint16_t* p = (uint16_t*)xb + ((((size_t)ks * CT + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
-    uint16_t hi[4], lo[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) { hi[r] = f32_to_bf16(v[r]); lo[r] = f32_to_bf16(v[r] - bf16_to_f32(hi[r])); }
-    *reinterpret_cast<uint2*>(p) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-    *reinterpret_cast<uint2*>(p + 512) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+    uint32_t hi[2], lo[2];
+    f32x2_split(v[0], v[1], hi[0], lo[0]);
+    f32x2_split(v[2], v[3], hi[1], lo[1]);
+    *reinterpret_cast<uint2*>(p) = make_uint2(hi[0], hi[1]);
+    *reinterpret_cast<uint2*>(p + 512) = make_uint2(lo[0], lo[1]);
 }
 template <int CT>
 __device__ inline void pack2(void* xb, int c, int f0, float v0, float v1) {
     const int ks = f0 >> 5, gq = (f0 & 31) >> 3, e = f0 & 7, t = c >> 4, cc = c & 15;
     uint16_t* p = (uint16_t*)xb + ((((size_t)ks * CT + t) * 2) * 64 + gq * 16 + cc) * 8 + e;
-    const uint16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
-    const uint16_t l0 = f32_to_bf16(v0 - bf16_to_f32(h0)), l1 = f32_to_bf16(v1 - bf16_to_f32(h1));
-    *reinterpret_cast<uint32_t*>(p) = h0 | ((uint32_t)h1 << 16);
-    *reinterpret_cast<uint32_t*>(p + 512) = l0 | ((uint32_t)l1 << 16);
+    uint32_t hi, lo;
+    f32x2_split(v0, v1, hi, lo);
+    *reinterpret_cast<uint32_t*>(p) = hi;
+    *reinterpret_cast<uint32_t*>(p + 512) = lo;
 }
 
 // the pass descriptor's scalars, asked for when a kernel starts so that nothing waits for them at its end
@@ -467,10 +467,6 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
                 x0[pr] = r0; x1[pr] = r1;
             }
         }
-        auto pack_hi = [](float p, float q) { return (uint32_t)f32_to_bf16(p) | ((uint32_t)f32_to_bf16(q) << 16); };
-        auto pack_lo = [](float p, float q) {
-            return (uint32_t)f32_to_bf16(p - bf16_to_f32(f32_to_bf16(p))) | ((uint32_t)f32_to_bf16(q - bf16_to_f32(f32_to_bf16(q))) << 16);
-        };
         if (head < a.H) {
             float* q = a.Y + (size_t)c * a.ldy + (size_t)head * hd;
             *reinterpret_cast<float2*>(q + j0) = make_float2(x0[0], x0[1]);
@@ -478,21 +474,25 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
         } else if (head < a.H + a.KV) {   // K planes: [slot][hd]
             uint16_t* kh = a.kv + kv_plane(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
             uint16_t* kl = kh + (size_t)kPage * hd;
-            *reinterpret_cast<uint32_t*>(kh + j0) = pack_hi(x0[0], x0[1]);
-            *reinterpret_cast<uint32_t*>(kh + j0 + half) = pack_hi(x1[0], x1[1]);
-            *reinterpret_cast<uint32_t*>(kl + j0) = pack_lo(x0[0], x0[1]);
-            *reinterpret_cast<uint32_t*>(kl + j0 + half) = pack_lo(x1[0], x1[1]);
+            uint32_t h0, l0, h1, l1;
+            f32x2_split(x0[0], x0[1], h0, l0);
+            f32x2_split(x1[0], x1[1], h1, l1);
+            *reinterpret_cast<uint32_t*>(kh + j0) = h0;
+            *reinterpret_cast<uint32_t*>(kh + j0 + half) = h1;
+            *reinterpret_cast<uint32_t*>(kl + j0) = l0;
+            *reinterpret_cast<uint32_t*>(kl + j0 + half) = l1;
         } else {                          // V planes, transposed: [hd][slot]
             uint16_t* vh = a.kv + kv_plane(page, a.layer, a.L, head - a.H - a.KV, a.KV, 2, hd);
             uint16_t* vl = vh + (size_t)kPage * hd;
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
                 const int j = j0 + pr;
-                const uint16_t h0 = f32_to_bf16(x0[pr]), h1 = f32_to_bf16(x1[pr]);
-                vh[(size_t)j * kPage + slot] = h0;
-                vh[(size_t)(j + half) * kPage + slot] = h1;
-                vl[(size_t)j * kPage + slot] = f32_to_bf16(x0[pr] - bf16_to_f32(h0));
-                vl[(size_t)(j + half) * kPage + slot] = f32_to_bf16(x1[pr] - bf16_to_f32(h1));
+                uint32_t hi, lo;
+                f32x2_split(x0[pr], x1[pr], hi, lo);
+                vh[(size_t)j * kPage + slot] = (uint16_t)hi;
+                vh[(size_t)(j + half) * kPage + slot] = (uint16_t)(hi >> 16);
+                vl[(size_t)j * kPage + slot] = (uint16_t)lo;
+                vl[(size_t)(j + half) * kPage + slot] = (uint16_t)(lo >> 16);
             }
         }
     }
@@ -909,11 +909,11 @@ __global__ __launch_bounds__(1024) void gemm_o_narrow(const GemmArgs a, const fl
         const int c = pidx / (K >> 1), k = (pidx % (K >> 1)) * 2;
         float v[2] = {0.f, 0.f};
         if (c < w) attn_merge<2>(attn_part, (pos0 + c + kAttnSplit) / kAttnSplit, c, k / a.hd, a.H, a.hd, k % a.hd, v);
-        const uint16_t h0 = f32_to_bf16(v[0]), h1 = f32_to_bf16(v[1]);
-        const uint16_t l0 = f32_to_bf16(v[0] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[1] - bf16_to_f32(h1));
+        uint32_t hi, lo;
+        f32x2_split(v[0], v[1], hi, lo);
         const int ks = k >> 5, gq = (k & 31) >> 3, e = k & 7;
-        *reinterpret_cast<uint32_t*>(sB16 + ((((ks * 2 + 0) * 4 + gq) * 4 + c) << 3) + e) = h0 | ((uint32_t)h1 << 16);
-        *reinterpret_cast<uint32_t*>(sB16 + ((((ks * 2 + 1) * 4 + gq) * 4 + c) << 3) + e) = l0 | ((uint32_t)l1 << 16);
+        *reinterpret_cast<uint32_t*>(sB16 + ((((ks * 2 + 0) * 4 + gq) * 4 + c) << 3) + e) = hi;
+        *reinterpret_cast<uint32_t*>(sB16 + ((((ks * 2 + 1) * 4 + gq) * 4 + c) << 3) + e) = lo;
     }
     __syncthreads();
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -981,6 +981,8 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
                                                  int KV, int nqkv, int qt_per_wg) {
     constexpr int KSQ = HD / 32, JT = HD / 16;
     __shared__ float mrg[4][16][HD + 2];
+    __shared__ float fac[4][16];
+    __shared__ int row_head[16];
     const int gkv = blockIdx.x, split = blockIdx.y;
     const int w = desc->w, pos0 = desc->pos0;
     const int key0 = split * kAttnSplit, kv_max = pos0 + w;
@@ -1044,10 +1046,7 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
             uint32_t hw[4], lw[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float x0 = v[2 * e] * scale, x1 = v[2 * e + 1] * scale;
-                const uint16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
-                hw[e] = h0 | ((uint32_t)h1 << 16);
-                lw[e] = f32_to_bf16(x0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(x1 - bf16_to_f32(h1)) << 16);
+                f32x2_split(v[2 * e] * scale, v[2 * e + 1] * scale, hw[e], lw[e]);
             }
             qh[ks] = u32x4{hw[0], hw[1], hw[2], hw[3]};
             ql[ks] = u32x4{lw[0], lw[1], lw[2], lw[3]};
@@ -1079,15 +1078,19 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
         const float msafe = m == -INFINITY ? 0.f : m;
         s16x4 Ph[2], Pl[2];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt) {
+            float p[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float p = expf(Sx[kt][r] - msafe);   // exp(-inf) = 0 for masked keys
-                l += p;
-                const uint16_t hi = f32_to_bf16(p);
-                Ph[kt][r] = (short)hi;
-                Pl[kt][r] = (short)f32_to_bf16(p - bf16_to_f32(hi));
+                p[r] = expf(Sx[kt][r] - msafe);   // exp(-inf) = 0 for masked keys
+                l += p[r];
             }
+            uint2 ph, pl;
+            f32x2_split(p[0], p[1], ph.x, pl.x);
+            f32x2_split(p[2], p[3], ph.y, pl.y);
+            Ph[kt] = __builtin_bit_cast(s16x4, ph);
+            Pl[kt] = __builtin_bit_cast(s16x4, pl);
+        }
         l += __shfl_xor(l, 16, kWave);
         l += __shfl_xor(l, 32, kWave);
 #pragma unroll
@@ -1107,22 +1110,36 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
 #pragma unroll
         for (int r = 0; r < 4; ++r) mrg[wave][g * 4 + r][2 + j * 16 + cq] = O[j][r];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
-        const int qr = idx / HD, i = idx % HD, rr = qt * 16 + qr;
+    // per query row, once: the four waves' rescaling factors, the merged (max, sum) and where the row goes
+    if (threadIdx.x < 16) {
+        const int qr = threadIdx.x, rr = qt * 16 + qr;
+        int rh = -1;
         if (rr < R) {
             float M = -INFINITY;
 #pragma unroll
             for (int v = 0; v < 4; ++v) M = fmaxf(M, mrg[v][qr][0]);
-            float Ls = 0.f, o = 0.f;
+            float Ls = 0.f;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float f = mrg[v][qr][0] == -INFINITY ? 0.f : expf(mrg[v][qr][0] - M);
                 Ls = fmaf(mrg[v][qr][1], f, Ls);
-                o = fmaf(mrg[v][qr][2 + i], f, o);
+                fac[v][qr] = f;
             }
-            float* out = part + (((size_t)split * kCols + rr / G) * H + gkv * G + rr % G) * (HD + 2);
-            out[2 + i] = o;
-            if (i == 0) { out[0] = M; out[1] = Ls; }
+            rh = (rr / G) * H + gkv * G + rr % G;
+            float* out = part + ((size_t)split * kCols * H + rh) * (HD + 2);
+            out[0] = M;
+            out[1] = Ls;
+        }
+        row_head[qr] = rh;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+        const int qr = idx / HD, i = idx % HD, rh = row_head[qr];
+        if (rh >= 0) {
+            float o = 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o = fmaf(mrg[v][qr][2 + i], fac[v][qr], o);
+            part[((size_t)split * kCols * H + rh) * (HD + 2) + 2 + i] = o;
         }
     }
     __syncthreads();   // the merge buffer is reused by the next query tile
