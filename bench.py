@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by a copy kernel of known size);
 # the runs are summarised in profiles/gemm_gate_up_paper_hbm_counters.md.  Keyed by kernel family and model.
 MEASURED_TRAFFIC_BYTES = {
-    ("paper", "gemm_gate_up draft"): 67.93e6,
+    ("paper", "gemm_gate_up draft"): 67.92e6,
     ("paper", "gemm_gate_up target"): 238.0e6,
     ("paper", "gemm_gate_up qualifier"): 102.7e6,
 }
