@@ -560,144 +560,107 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     constexpr int U = RT == 7 ? 4 : (NT > 2 ? (NW > 8 ? 4 : 8) : 16) / RT;
     static_assert(U >= 1, "too many row tiles per wave");
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    auto mfma_step = [&](const u32x4 (&wv)[RT], int t, const u32x4 bh, const u32x4 bl) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
+                                                                __builtin_bit_cast(bf16x8, bh), acc[r][t], 0, 0, 0);
+            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
+                                                                __builtin_bit_cast(bf16x8, bl), acc[r][t], 0, 0, 0);
+        }
+    };
     if constexpr (NT == 1) {
         // Operand blocks come from L2.  BG steps' worth of them is asked for at a time; the first group goes out with the
         // batch's weights and is there long before them, every later group costs one exposed L2 round trip.  The whole
         // batch at once (BG = U) takes up to 64 registers: on in the variants that run at most one workgroup per CU
-        // anyway (qualifier q/k/v 39.8 -> 34.7 ms per 2632 launches), where it costs residency (the draft's gate/up,
-        // the LM heads: 17.6 -> 18.5 us) groups of 2 are used.  Kernels with several column tiles load tile by tile
-        // inside a step, as their operand blocks would not fit.
-        constexpr int BG = NT > 1 ? 1 : (U <= 8 && (RT >= 4 || EPI == EPI_QKV)) ? U : (U < 2 ? U : 2);
+        // anyway (qualifier q/k/v 39.8 -> 34.7 ms per 2632 launches); where it would cost residency (the draft's gate/up,
+        // the LM heads: 17.6 -> 18.5 us) groups of 2 are used (17.6 -> 16.7 us).
+        constexpr int BG = (U <= 8 && (RT >= 4 || EPI == EPI_QKV)) ? U : (U < 2 ? U : 2);
         static_assert(U % BG == 0, "operand groups must tile a batch");
-        const u32x4* bslot[BG];            // NT > 1: where a step finds its blocks
-        u32x4 bpre[BG][NT == 1 ? 2 : 1];   // NT == 1: the blocks themselves
+        u32x4 bpre[BG][2];
         auto load_b = [&](int slot, const u32x4* bp) {
-            if constexpr (NT == 1) {
-                bpre[slot][0] = zero; bpre[slot][1] = zero;
-                if (col_live[0]) { bpre[slot][0] = bp[0]; bpre[slot][1] = bp[64]; }
-            } else {
-                bslot[slot] = bp;
-            }
-        };
-        auto step = [&](const u32x4 (&wv)[RT], int slot) {
-    #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                u32x4 bh = zero, bl = zero;
-                if constexpr (NT == 1) { bh = bpre[slot][0]; bl = bpre[slot][1]; }
-                else if (col_live[t]) { bh = bslot[slot][t * 128]; bl = bslot[slot][t * 128 + 64]; }
-    #pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
-                                                                        __builtin_bit_cast(bf16x8, bh), acc[r][t], 0, 0, 0);
-                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
-                                                                        __builtin_bit_cast(bf16x8, bl), acc[r][t], 0, 0, 0);
-                }
-            }
+            bpre[slot][0] = zero; bpre[slot][1] = zero;
+            if (col_live[0]) { bpre[slot][0] = bp[0]; bpre[slot][1] = bp[64]; }
         };
         // batches of U K steps; the last batch of a range may be short (its loads still go out together)
         for (int ks = k0; ks < k1; ks += U) {
             u32x4 wv[U][RT];
             if (ks + U <= k1) {
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u)
-    #pragma unroll
+#pragma unroll
                     for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < BG; ++u) load_b(u, b_ptr + (size_t)u * kBStep);
                 if (want_pre) prefetch_all();
-    #pragma unroll
+#pragma unroll
                 for (int g0 = 0; g0 < U; g0 += BG) {
                     if (g0 > 0) {
-    #pragma unroll
+#pragma unroll
                         for (int u = 0; u < BG; ++u) load_b(u, b_ptr + (size_t)(g0 + u) * kBStep);
                     }
-    #pragma unroll
-                    for (int u = 0; u < BG; ++u) step(wv[g0 + u], u);
+#pragma unroll
+                    for (int u = 0; u < BG; ++u) mfma_step(wv[g0 + u], 0, bpre[u][0], bpre[u][1]);
                 }
             } else {
                 const int cnt = k1 - ks;
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u)
                     if (u < cnt) {
-    #pragma unroll
+#pragma unroll
                         for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
                     }
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < BG; ++u)
                     if (u < cnt) load_b(u, b_ptr + (size_t)u * kBStep);
                 if (want_pre) prefetch_all();
-    #pragma unroll
+#pragma unroll
                 for (int g0 = 0; g0 < U; g0 += BG) {
                     if (g0 > 0) {
-    #pragma unroll
+#pragma unroll
                         for (int u = 0; u < BG; ++u)
                             if (g0 + u < cnt) load_b(u, b_ptr + (size_t)(g0 + u) * kBStep);
                     }
-    #pragma unroll
+#pragma unroll
                     for (int u = 0; u < BG; ++u)
-                        if (g0 + u < cnt) step(wv[g0 + u], u);
+                        if (g0 + u < cnt) mfma_step(wv[g0 + u], 0, bpre[u][0], bpre[u][1]);
                 }
             }
             a_ptr += (size_t)U * 64;
             b_ptr += (size_t)U * kBStep;
         }
     } else {
-        // kBPre: the operand blocks of a whole batch are asked for together with its weights (they come from L2 and are
-        // there long before the weights); otherwise a step loads its own, one L2 round trip per step.  Costs up to 64
-        // registers, so it is on only in the variants that run at most one workgroup per CU anyway (q/k/v of the
-        // qualifier 39.8 -> 34.7 ms per 2632 launches); with it the draft's gate/up and the LM heads lose residency and
-        // get slower (17.6 -> 18.5 us)
-        constexpr bool kBPre = false;
-        u32x4 bpre[kBPre ? U : 1][kBPre ? NT : 1][2];
-        auto load_b = [&](int u, const u32x4* bp) {
-            if constexpr (kBPre) {
-    #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    bpre[u][t][0] = zero; bpre[u][t][1] = zero;
-                    if (col_live[t]) { bpre[u][t][0] = bp[t * 128]; bpre[u][t][1] = bp[t * 128 + 64]; }
-                }
-            }
-        };
-        auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp, int u) {
-    #pragma unroll
+        // Several column tiles per wave: a step loads its operand blocks tile by tile right before it uses them (a group
+        // of steps' blocks would not fit the registers: 302 spilled registers when tried)
+        auto step = [&](const u32x4 (&wv)[RT], const u32x4* bp) {
+#pragma unroll
             for (int t = 0; t < NT; ++t) {
                 u32x4 bh = zero, bl = zero;
-                if constexpr (kBPre) { bh = bpre[u][t][0]; bl = bpre[u][t][1]; }
-                else if (col_live[t]) { bh = bp[t * 128]; bl = bp[t * 128 + 64]; }
-    #pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
-                                                                        __builtin_bit_cast(bf16x8, bh), acc[r][t], 0, 0, 0);
-                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[r]),
-                                                                        __builtin_bit_cast(bf16x8, bl), acc[r][t], 0, 0, 0);
-                }
+                if (col_live[t]) { bh = bp[t * 128]; bl = bp[t * 128 + 64]; }
+                mfma_step(wv, t, bh, bl);
             }
         };
-        // batches of U K steps; the last batch of a range may be short (its loads still go out together)
         for (int ks = k0; ks < k1; ks += U) {
             u32x4 wv[U][RT];
             if (ks + U <= k1) {
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u)
-    #pragma unroll
+#pragma unroll
                     for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
-    #pragma unroll
-                for (int u = 0; u < U; ++u) load_b(u, b_ptr + (size_t)u * kBStep);
                 if (want_pre) prefetch_all();
-    #pragma unroll
-                for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep, u);
+#pragma unroll
+                for (int u = 0; u < U; ++u) step(wv[u], b_ptr + (size_t)u * kBStep);
             } else {
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u)
                     if (ks + u < k1) {
-    #pragma unroll
+#pragma unroll
                         for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
-                        load_b(u, b_ptr + (size_t)u * kBStep);
                     }
                 if (want_pre) prefetch_all();
-    #pragma unroll
+#pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (ks + u < k1) step(wv[u], b_ptr + (size_t)u * kBStep, u);
+                    if (ks + u < k1) step(wv[u], b_ptr + (size_t)u * kBStep);
             }
             a_ptr += (size_t)U * 64;
             b_ptr += (size_t)U * kBStep;
