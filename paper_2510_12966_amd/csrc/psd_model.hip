@@ -507,7 +507,8 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
 template <int NT, int NW, int RT, int EPI, int CT>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     constexpr int TG = NT > 2 ? 2 : NT;   // column tiles whose partials cross LDS together
-    __shared__ f32x4 red[NW - 1][RT][TG][64];
+    static_assert(RT <= NW, "one finishing wave per row tile");
+    __shared__ f32x4 red[NW][RT][TG][64];
     constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
     __shared__ float ssp[kScaled ? 4 * NW : 1][16 * NT];
     const int tile0 = blockIdx.x * RT, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     const DescVals dv = load_desc(a.desc);
     // the epilogue's own reads: the narrow kernels' finishing wave asks for them once its first weights are on the way
     constexpr bool kEarly = NT <= 2;
-    EpiPre<EPI> pre[kEarly ? RT : 1][kEarly ? NT : 1];
+    EpiPre<EPI> pre[kEarly ? NT : 1];   // wave r finishes row tile r
     float ss_mine[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) ss_mine[t] = 0.f;
@@ -534,12 +535,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             }
         }
         if constexpr (kEarly) {
-            if (wave != 0) return;
+            if (wave >= RT) return;
 #pragma unroll
-            for (int r = 0; r < RT; ++r)
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    if (t * 16 + cc < dv.w) epi_prefetch<EPI>(a, dv, tile0 + r, g, t * 16 + cc, pre[r][t]);
+            for (int t = 0; t < NT; ++t)
+                if (t * 16 + cc < dv.w) epi_prefetch<EPI>(a, dv, tile0 + wave, g, t * 16 + cc, pre[t]);
         }
     };
     const u32x4* a_ptr = a.Wt + ((size_t)tile0 * a.KS + k0) * 64 + lane;
@@ -671,19 +670,18 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) ssp[wave * 4 + g][t * 16 + cc] = ss_mine[t];
     }
-    // the waves' partial sums meet in LDS TG column tiles at a time and are added in wave order
+    // the waves' partial sums meet in LDS TG column tiles at a time; wave r adds up row tile r in wave order and
+    // finishes it, so the RT epilogues of a workgroup run side by side
     const int w = dv.w;
 #pragma unroll
     for (int t0 = 0; t0 < NT; t0 += TG) {
-        if (t0 > 0) __syncthreads();   // wave 0 has read the previous group
-        if (wave > 0) {
+        if (t0 > 0) __syncthreads();   // the finishing waves have read the previous group
 #pragma unroll
-            for (int r = 0; r < RT; ++r)
+        for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int tt = 0; tt < TG; ++tt) red[wave - 1][r][tt][lane] = acc[r][t0 + tt];
-        }
+            for (int tt = 0; tt < TG; ++tt) red[wave][r][tt][lane] = acc[r][t0 + tt];
         __syncthreads();
-        if (wave != 0) continue;
+        if (wave >= RT) continue;
 #pragma unroll
         for (int tt = 0; tt < TG; ++tt) {
             const int t = t0 + tt;
@@ -695,15 +693,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
                 rs = rsqrtf(ssum * a.inv_d + a.eps);
             }
             const int c = t * 16 + cc;
+            f32x4 sum = red[0][wave][tt][lane];
 #pragma unroll
-            for (int r = 0; r < RT; ++r) {
-#pragma unroll
-                for (int v = 0; v < NW - 1; ++v) acc[r][t] += red[v][r][tt][lane];
-                // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
-                if (c < w) {
-                    epilogue<EPI, CT, kEarly>(a, dv, tile0 + r, g, c, acc[r][t], rs, pre[kEarly ? r : 0][kEarly ? t : 0]);
-                }
-            }
+            for (int v = 1; v < NW; ++v) sum += red[v][wave][tt][lane];
+            // whole 16-lane groups agree on c < w, and the shuffles inside the epilogue cross g only
+            if (c < w) epilogue<EPI, CT, kEarly>(a, dv, tile0 + wave, g, c, sum, rs, pre[kEarly ? t : 0]);
         }
     }
 }
