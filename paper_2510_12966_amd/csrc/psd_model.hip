@@ -510,7 +510,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     static_assert(RT <= NW, "one finishing wave per row tile");
     __shared__ f32x4 red[NW][RT][TG][64];
     constexpr bool kScaled = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LOGITS);
-    __shared__ float ssp[kScaled ? 4 * NW : 1][16 * NT];
+    __shared__ float ssp[kScaled ? NW : 1][16 * NT];
     const int tile0 = blockIdx.x * RT, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int k0 = (int)(((long)a.KS * wave) / NW), k1 = (int)(((long)a.KS * (wave + 1)) / NW);
     const int g = lane >> 4, cc = lane & 15;
@@ -667,8 +667,14 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     }
     if (want_pre) prefetch_all();   // a wave without K steps
     if constexpr (kScaled) {
+        // a wave's four strided partial sums are folded pairwise, (0 + 1) + (2 + 3); the waves' results are added in
+        // wave order by whoever needs the scale
 #pragma unroll
-        for (int t = 0; t < NT; ++t) ssp[wave * 4 + g][t * 16 + cc] = ss_mine[t];
+        for (int t = 0; t < NT; ++t) {
+            float sw = ss_mine[t] + __shfl_xor(ss_mine[t], 16, kWave);
+            sw = sw + __shfl_xor(sw, 32, kWave);
+            if (g == 0) ssp[wave][t * 16 + cc] = sw;
+        }
     }
     // the waves' partial sums meet in LDS TG column tiles at a time; wave r adds up row tile r in wave order and
     // finishes it, so the RT epilogues of a workgroup run side by side
@@ -689,7 +695,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             if constexpr (kScaled) {
                 float ssum = 0.f;
 #pragma unroll
-                for (int v = 0; v < 4 * NW; ++v) ssum += ssp[v][t * 16 + cc];
+                for (int v = 0; v < NW; ++v) ssum += ssp[v][t * 16 + cc];
                 rs = rsqrtf(ssum * a.inv_d + a.eps);
             }
             const int c = t * 16 + cc;
@@ -747,7 +753,8 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
 #pragma unroll
     for (int t = 0; t < TC; ++t) rs[t] = 1.f;
     if constexpr (kScaled) {
-        // the narrow kernels' 4 NW strided partial sums of the input's sums of squares, per column, added in slot order
+        // the narrow kernels' 4 NW strided partial sums of the input's sums of squares, per column, folded as there:
+        // (0 + 1) + (2 + 3) within each group of four, the groups added in order
         float (*ssp)[GC] = reinterpret_cast<float (*)[GC]>(smem);
         const int col = tid % GC;
         for (int slot = tid / GC; slot < 4 * NW; slot += 512 / GC) {
@@ -760,7 +767,10 @@ __global__ __launch_bounds__(512) void gemm_panel(const GemmArgs a, const int ti
         for (int t = 0; t < TC; ++t) {
             float ssum = 0.f;
 #pragma unroll
-            for (int u = 0; u < 4 * NW; ++u) ssum += ssp[u][(wc * TC + t) * 16 + cc];
+            for (int u = 0; u < NW; ++u) {
+                const int col = (wc * TC + t) * 16 + cc;
+                ssum += (ssp[4 * u][col] + ssp[4 * u + 1][col]) + (ssp[4 * u + 2][col] + ssp[4 * u + 3][col]);
+            }
             rs[t] = rsqrtf(ssum * a.inv_d + a.eps);
         }
         __syncthreads();
