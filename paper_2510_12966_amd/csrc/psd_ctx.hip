@@ -94,8 +94,8 @@ struct psd_ctx {
     int stage_next = 0, stage_since_sync = 0;
     RoundResult* res = nullptr;
     // graphs: [model][width class 4 / 16 / 32]
-    GraphSlot graphs[3][kNumNarrowClasses];   // [model][launch class]
-    GraphSlot chain_graphs[3][3][kNumNarrowClasses];  // sampling steps: [proposer][model whose pass descriptor receives the tokens][launch class]
+    GraphSlot graphs[3][kNumNarrowClasses][2];   // [model][launch class][long-context variant]
+    GraphSlot chain_graphs[3][3][kNumNarrowClasses][2];  // sampling steps: [proposer][model whose pass descriptor receives the tokens][launch class][long-context variant]
     Profiler prof;
     StageTimer timer;
     psd_trace_fn trace = nullptr;
@@ -155,6 +155,8 @@ static size_t desc_bytes(const PassDesc& d) {
 static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sample, bool allow_graph = false,
                     int verifier = 1) {
     Model& M = c->M[mi];
+    // a few sampling steps may follow each other before the host mirror of the length moves: count them in
+    M.long_ctx = M.len + 2 * kMaxW > kFoldSplits * kAttnSplit;
     // only the decoding loop's three pass shapes are captured; prefill, the test hook and plain generation stay eager
     const bool use_graph = allow_graph && (c->prm.flags & PSD_FLAG_GRAPH) && !c->prof.on;
     auto enqueue = [&](Profiler* prof) -> int {
@@ -171,7 +173,8 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
         return PSD_OK;
     };
     if (!use_graph) return enqueue(&c->prof);
-    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier][narrow_class_index(wcls)] : c->graphs[mi][narrow_class_index(wcls)];
+    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier][narrow_class_index(wcls)][M.long_ctx]
+                               : c->graphs[mi][narrow_class_index(wcls)][M.long_ctx];
     if (!g.exec) {
         hipGraph_t graph = nullptr;
         PSD_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal), c->err);
@@ -187,13 +190,16 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
 }
 
 static void drop_graphs(psd_ctx* c) {
+    auto drop = [](GraphSlot& g) {
+        if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+    };
     for (auto& row : c->graphs)
-        for (auto& g : row)
-            if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+        for (auto& cls : row)
+            for (auto& g : cls) drop(g);
     for (auto& plane : c->chain_graphs)
         for (auto& row : plane)
-            for (auto& g : row)
-                if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+            for (auto& cls : row)
+                for (auto& g : cls) drop(g);
 }
 
 // host-known tokens seq[from, to) go into a pass descriptor that starts at KV row `from`

@@ -11,6 +11,7 @@ namespace psd {
 
 constexpr int kPage = 64;        // tokens per KV page
 constexpr int kAttnSplit = 128;  // keys per attention workgroup (two pages); boundaries are absolute positions
+constexpr int kFoldSplits = 12;  // up to this many key ranges the narrow o projection merges the partials itself
 constexpr int kMaxW = PSD_MAX_WIDTH;   // widest pass that can produce logits (and the widest the ABI takes)
 constexpr int kCols = 512;             // widest pass at all: prompt ingestion of bf16 models, no logits
 constexpr int kWideCT = kCols / 16;    // column tiles of the operand buffers those passes use
@@ -114,6 +115,7 @@ struct Model {
     // host mirror
     int len = 0;  // valid KV rows
     int ingest_max = 0;  // widest pass that may ingest a prompt (32 for fp32 models; 128 or 512 for bf16 ones)
+    bool long_ctx = false;  // launch-time hint: the pass attends to more than kFoldSplits key ranges (any value is correct)
     size_t weight_bytes = 0;  // bytes one pass streams (all matrices once)
 };
 

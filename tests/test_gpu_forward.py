@@ -176,6 +176,33 @@ def test_bf16_ingestion_at_page_split_and_pass_boundaries():
     ctx.close()
 
 
+def test_bf16_narrow_passes_across_the_merge_switch_are_bit_exact():
+    # passes of up to 4 tokens let the o projection merge the attention partials itself while the context spans at
+    # most a dozen key ranges, and hand the merge to a kernel of its own beyond that: on both sides of the switch
+    # their logits have the bits of 11-token passes (which always use the separate kernel), and match the oracle
+    shapes = MINI[0]
+    blobs = [synth.target_weights(s, 20 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    n0, n1 = 1408, 1672
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 1700)
+    toks = synth.tokens(13, 0, n1, 1000)
+    for which in (0, 2):
+        for pos in range(0, n0, 32):
+            ctx.forward(which, toks[pos:pos + 32], pos, want_logits=False)
+        pos, narrow, k = n0, [], 0
+        while pos < n1:
+            w = min((4, 1, 2, 3)[k % 4], n1 - pos)
+            narrow.append(ctx.forward(which, toks[pos:pos + w], pos))
+            pos += w
+            k += 1
+        narrow = np.concatenate(narrow)
+        wide = np.concatenate([ctx.forward(which, toks[p:p + 11], p) for p in range(n0, n1, 11)])   # rolls the cache back to n0 first
+        assert np.array_equal(narrow, wide)
+        om = oracle.Model(shapes[which], blobs[which], synth.DTYPE_BF16, 10000.0, 1700)
+        ref = om.forward(toks, 0)[n0:]
+        assert np.abs(narrow - ref).max() <= TOL_BF16
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
