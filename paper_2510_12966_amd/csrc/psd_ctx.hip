@@ -94,8 +94,8 @@ struct psd_ctx {
     int stage_next = 0, stage_since_sync = 0;
     RoundResult* res = nullptr;
     // graphs: [model][width class 4 / 16 / 32]
-    GraphSlot graphs[3][kNumNarrowClasses][2];   // [model][launch class][long-context variant]
-    GraphSlot chain_graphs[3][3][kNumNarrowClasses][2];  // sampling steps: [proposer][model whose pass descriptor receives the tokens][launch class][long-context variant]
+    GraphSlot graphs[3][kNumNarrowClasses][kNumCtxBuckets];   // [model][launch class][context bucket]
+    GraphSlot chain_graphs[3][3][kNumNarrowClasses][kNumCtxBuckets];  // sampling steps: [proposer][model whose pass descriptor receives the tokens][launch class][context bucket]
     Profiler prof;
     StageTimer timer;
     psd_trace_fn trace = nullptr;
@@ -155,8 +155,9 @@ static size_t desc_bytes(const PassDesc& d) {
 static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sample, bool allow_graph = false,
                     int verifier = 1) {
     Model& M = c->M[mi];
-    // a few sampling steps may follow each other before the host mirror of the length moves: count them in
-    M.long_ctx = M.len + 2 * kMaxW > kFoldSplits * kAttnSplit;
+    // Upper bound of the pass's last position.  The host mirror of the length moves once per round: a catch-up pass of
+    // up to kMaxW tokens and up to kMaxW - 1 single-token sampling steps may be launched from one value of it.
+    M.ctx_bucket = ctx_bucket_index(std::min(M.max_seq, M.len + std::max(wcls, 2 * kMaxW)));
     // only the decoding loop's three pass shapes are captured; prefill, the test hook and plain generation stay eager
     const bool use_graph = allow_graph && (c->prm.flags & PSD_FLAG_GRAPH) && !c->prof.on;
     auto enqueue = [&](Profiler* prof) -> int {
@@ -173,8 +174,8 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
         return PSD_OK;
     };
     if (!use_graph) return enqueue(&c->prof);
-    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier][narrow_class_index(wcls)][M.long_ctx]
-                               : c->graphs[mi][narrow_class_index(wcls)][M.long_ctx];
+    GraphSlot& g = with_sample ? c->chain_graphs[mi][verifier][narrow_class_index(wcls)][M.ctx_bucket]
+                               : c->graphs[mi][narrow_class_index(wcls)][M.ctx_bucket];
     if (!g.exec) {
         hipGraph_t graph = nullptr;
         PSD_HIP(hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal), c->err);

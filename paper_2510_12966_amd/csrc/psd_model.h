@@ -12,6 +12,20 @@ namespace psd {
 constexpr int kPage = 64;        // tokens per KV page
 constexpr int kAttnSplit = 128;  // keys per attention workgroup (two pages); boundaries are absolute positions
 constexpr int kFoldSplits = 12;  // up to this many key ranges the narrow o projection merges the partials itself
+constexpr int kQuadTileSplits = 16;  // beyond this many, one attention workgroup of a narrow pass takes four query tiles
+
+// Context buckets: a pass is launched for the smallest bucket of key ranges that holds every key it can attend to
+// (the host knows an upper bound of the pass's last position), so the attention grid does not grow with max_seq and
+// the choices that depend on the context length are fixed per captured graph.  The last bucket stands for "all
+// key ranges of the cache".
+constexpr int kCtxBuckets[] = {8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1 << 30};
+constexpr int kNumCtxBuckets = sizeof(kCtxBuckets) / sizeof(kCtxBuckets[0]);
+inline int ctx_bucket_index(int kv_upto) {   // kv_upto: upper bound of (first position + tokens) of the pass
+    const int ranges = (kv_upto + kAttnSplit - 1) / kAttnSplit;
+    int i = 0;
+    while (kCtxBuckets[i] < ranges) ++i;
+    return i;
+}
 constexpr int kMaxW = PSD_MAX_WIDTH;   // widest pass that can produce logits (and the widest the ABI takes)
 constexpr int kCols = 512;             // widest pass at all: prompt ingestion of bf16 models, no logits
 constexpr int kWideCT = kCols / 16;    // column tiles of the operand buffers those passes use
@@ -115,7 +129,7 @@ struct Model {
     // host mirror
     int len = 0;  // valid KV rows
     int ingest_max = 0;  // widest pass that may ingest a prompt (32 for fp32 models; 128 or 512 for bf16 ones)
-    bool long_ctx = false;  // launch-time hint: the pass attends to more than kFoldSplits key ranges (any value is correct)
+    int ctx_bucket = kNumCtxBuckets - 1;  // set by the caller before model_forward: bucket of the pass's last position
     size_t weight_bytes = 0;  // bytes one pass streams (all matrices once)
 };
 

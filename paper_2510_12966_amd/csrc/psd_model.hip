@@ -1552,12 +1552,16 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     else if (wmax <= 16) embed_pack<1, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     else embed_pack<2, 2><<<d / 16, 64, 0, stream>>>((const uint16_t*)M.embed, M.desc, M.x, xb, M.layers[0].attn_norm, ss, d, M.V);
     L.end();
-    const int qt_per_wg = wmax > kMaxW ? 4 : 1;   // wide passes: four query tiles share one load of the keys and values
+    // key ranges this launch covers: the bucket of the pass's last position (the caller's bound), never beyond the cache
+    const int nsplit = std::min(M.nsplit_max, kCtxBuckets[M.ctx_bucket]);
+    // wide passes, and narrow ones over long contexts: four query tiles share one load of the keys and values (narrow
+    // target pass at 3 K tokens of context 4.28 -> 4.06 ms, at 1 K 3.87 -> 3.92 ms)
+    const int qt_per_wg = (wmax > kMaxW || nsplit > kQuadTileSplits) ? 4 : 1;
     const int qt_max = ((wmax * G + 15) / 16 + qt_per_wg - 1) / qt_per_wg;
     // narrow passes of small models: the o projection merges the attention split partials itself (one launch less).
     // Every workgroup of it repeats the merge, so past a dozen key ranges the separate merge kernel is cheaper
     // (draft o projection at 36 ranges: 19.8 us against 4.2 + 6.5 us); both routes give the same bits.
-    const bool fold_merge = wmax <= 4 && d <= 2048 && d / 16 <= 256 && H * hd == d && !M.long_ctx;
+    const bool fold_merge = wmax <= 4 && d <= 2048 && d / 16 <= 256 && H * hd == d && nsplit <= kFoldSplits;
     GemmArgs base{};
     base.ss_in = ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
     base.rope = M.rope; base.kv = (uint16_t*)M.kv; base.page_table = M.page_table;
@@ -1570,7 +1574,7 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         a.Y = M.qkv; a.ldy = M.nqkv; a.layer = l;
         launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
         L.begin("attn", 0);
-        const dim3 agrid(KV, M.nsplit_max, qt_max);
+        const dim3 agrid(KV, nsplit, qt_max);
         if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
         else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
         else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);

@@ -203,6 +203,30 @@ def test_bf16_narrow_passes_across_the_merge_switch_are_bit_exact():
     ctx.close()
 
 
+def test_bf16_context_length_switches_are_bit_exact():
+    # the launch shape depends on how far the context reaches (who merges the attention partials past 12 key ranges,
+    # four query tiles per attention workgroup past 16): the same token at the same position has the same logits
+    # bits when it is computed just before and just after each switch
+    shapes = MINI[0]
+    blobs = [synth.target_weights(s, 20 + i, synth.DTYPE_BF16, sigma=0.03) for i, s in enumerate(shapes)]
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 2100)
+    toks = synth.tokens(14, 0, 2100, 1000)
+    for which in (0, 2):
+        pos = 0
+        for edge, w in ((12 * 128, 4), (16 * 128, 11)):
+            a = edge - 64 - w + 2            # a pass of w tokens from here is bounded by edge - 2 + ... : before the switch
+            while pos < a:
+                n = min(32, a - pos)
+                ctx.forward(which, toks[pos:pos + n], pos, want_logits=False)
+                pos += n
+            before = ctx.forward(which, toks[a:a + w], a)                 # context bound a + 64 <= edge
+            ctx.forward(which, toks[a:a + w - 1], a, want_logits=False)   # rolls back, keeps w - 1 of them
+            after = ctx.forward(which, toks[a + w - 1:a + 2 * w - 1], a + w - 1)   # bound a + w - 1 + 64 > edge
+            assert np.array_equal(before[w - 1], after[0]), (which, edge)
+            pos = a + 2 * w - 1
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
