@@ -262,6 +262,10 @@ def main() -> int:
         _, pst = ctx.generate(prompt, n_new, cfg.sample_seed)
         kernels = ctx.kernel_stats()
         ctx.profile(False)
+        # one more row: an event pair around a kernel that does nothing, once per pass (what the intervals below
+        # hold besides kernel time; rocprofv3's begin/end timestamps do not contain it)
+        empty = [r for r in kernels if r["name"].startswith("empty kernel")]
+        kernels = [r for r in kernels if not r["name"].startswith("empty kernel")]
         kernels.sort(key=lambda r: -r["ms_total"])
         tot = sum(r["ms_total"] for r in kernels)
         for r in kernels:
@@ -275,7 +279,8 @@ def main() -> int:
                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom["name"].rsplit(" w<=", 1)[0])),
                     "avg_launch_us": round(dom["ms_total"] / dom["launches"] * 1e3, 2),
                     "bytes_per_launch": round(dom["bytes_total"] / dom["launches"]),
-                    "all_gemm_GBps": None}
+                    "all_gemm_GBps": None,
+                    "empty_kernel_event_pair_us": round(empty[0]["ms_total"] / empty[0]["launches"] * 1e3, 2) if empty else None}
         g = [r for r in kernels if r["name"].startswith("gemm")]
         if g:
             roofline["all_gemm_GBps"] = round(sum(r["bytes_total"] for r in g) / sum(r["ms_total"] for r in g) / 1e6, 1)
