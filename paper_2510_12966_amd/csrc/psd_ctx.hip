@@ -101,6 +101,9 @@ struct psd_ctx {
     psd_trace_fn trace = nullptr;
     void* trace_user = nullptr;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    // prompt ingestion: one stream per model, so that the three independent ingestions share the device
+    hipStream_t aux[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t aux_ready[3] = {nullptr, nullptr, nullptr}, aux_done[3] = {nullptr, nullptr, nullptr};
 };
 
 namespace psd {
@@ -153,15 +156,16 @@ static size_t desc_bytes(const PassDesc& d) {
 // enqueues one pass of model `mi`; the descriptor is already on the device.  with_sample: the draft step
 // also samples its token and advances the chain.
 static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sample, bool allow_graph = false,
-                    int verifier = 1) {
+                    int verifier = 1, hipStream_t on_stream = nullptr) {
     Model& M = c->M[mi];
+    hipStream_t stream = on_stream ? on_stream : c->stream;   // other than the context's: eager passes without sampling only
     // Upper bound of the pass's last position.  The host mirror of the length moves once per round: a catch-up pass of
     // up to kMaxW tokens and up to kMaxW - 1 single-token sampling steps may be launched from one value of it.
     M.ctx_bucket = ctx_bucket_index(std::min(M.max_seq, M.len + std::max(wcls, 2 * kMaxW)));
     // only the decoding loop's three pass shapes are captured; prefill, the test hook and plain generation stay eager
     const bool use_graph = allow_graph && (c->prm.flags & PSD_FLAG_GRAPH) && !c->prof.on;
     auto enqueue = [&](Profiler* prof) -> int {
-        int rc = model_forward(M, wcls, logits, c->stream, prof, c->err);
+        int rc = model_forward(M, wcls, logits, stream, prof, c->err);
         if (rc != PSD_OK) return rc;
         if (with_sample) {
             if (prof && prof->on) prof->begin(c->stream, prof->row_of("sample draft"), (double)c->V * 4);
@@ -227,6 +231,51 @@ static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
         M.len += w;
     }
     return PSD_OK;
+}
+
+// Ingests seq[len, upto) into all three models at once.  The ingestions are independent and their launches are too
+// small to fill the device one model at a time, so each model's passes run on a stream of their own; the context's
+// stream carries the descriptors and page tables and is where everything meets again.
+static int prefill_all(psd_ctx* c, const int32_t* seq, int upto) {
+    if (c->prof.on) {   // per-kernel timing: one model after the other on the context's stream
+        for (int mi = 0; mi < 3; ++mi) {
+            int rc = prefill(c, mi, seq, upto);
+            if (rc != PSD_OK) return rc;
+        }
+        return PSD_OK;
+    }
+    bool used[3] = {false, false, false};
+    auto enqueue = [&]() -> int {
+        for (bool more = true; more;) {
+            more = false;
+            for (int mi = 0; mi < 3; ++mi) {
+                Model& M = c->M[mi];
+                if (M.len >= upto) continue;
+                const int w = std::min(M.ingest_max, upto - M.len);
+                // the model's descriptor and page table are free again once its previous pass is done
+                if (used[mi]) PSD_HIP(hipStreamWaitEvent(c->stream, c->aux_done[mi], 0), c->err);
+                int rc = model_map_pages(M, M.len, M.len + w, c->stream, c->err);
+                if (rc != PSD_OK) return rc;
+                PassDesc d;
+                fill_desc(d, seq, M.len, M.len + w, 0, 0, 0);
+                if ((rc = upload(c, M.desc, &d, desc_bytes(d))) != PSD_OK) return rc;
+                PSD_HIP(hipEventRecord(c->aux_ready[mi], c->stream), c->err);
+                PSD_HIP(hipStreamWaitEvent(c->aux[mi], c->aux_ready[mi], 0), c->err);
+                if ((rc = run_pass(c, mi, wclass(w), nullptr, false, false, 1, c->aux[mi])) != PSD_OK) return rc;
+                PSD_HIP(hipEventRecord(c->aux_done[mi], c->aux[mi]), c->err);
+                used[mi] = true;
+                M.len += w;
+                more = more || M.len < upto;
+            }
+        }
+        for (int mi = 0; mi < 3; ++mi)
+            if (used[mi]) PSD_HIP(hipStreamWaitEvent(c->stream, c->aux_done[mi], 0), c->err);
+        return PSD_OK;
+    };
+    const int rc = enqueue();
+    if (rc != PSD_OK)   // nothing of this context is left running on the side when an error is reported
+        for (auto& st : c->aux) (void)hipStreamSynchronize(st);
+    return rc;
 }
 
 // behaviour statistics (Section 4) of `rows` logits rows model `mi` has just produced; only when asked for
@@ -375,6 +424,9 @@ extern "C" int psd_create(const psd_model_desc* draft, const psd_model_desc* qua
     CK(hipHostMalloc((void**)&c->stage, (size_t)kStageSlots * kStageSlotBytes, hipHostMallocDefault));
     CK(hipHostMalloc((void**)&c->res, sizeof(RoundResult), hipHostMallocDefault));
     for (auto& e : c->ev) CK(hipEventCreate(&e));
+    for (auto& st : c->aux) CK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    for (auto& e : c->aux_ready) CK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    for (auto& e : c->aux_done) CK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     CK(hipStreamSynchronize(c->stream));
 #undef CK
     *out = c;
@@ -385,9 +437,12 @@ extern "C" void psd_destroy(psd_ctx* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream) (void)hipStreamSynchronize(c->stream);
+    for (auto& st : c->aux) if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
     drop_graphs(c);
     c->prof.clear();
     for (auto& e : c->ev) if (e) (void)hipEventDestroy(e);
+    for (auto& e : c->aux_ready) if (e) (void)hipEventDestroy(e);
+    for (auto& e : c->aux_done) if (e) (void)hipEventDestroy(e);
     if (c->stage) (void)hipHostFree(c->stage);
     if (c->res) (void)hipHostFree(c->res);
     if (c->pool_mem) (void)hipFree(c->pool_mem);
@@ -486,8 +541,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     PSD_HIP(hipMemsetAsync(c->rs_acc, 0, 9 * sizeof(double), c->stream), c->err);
 
     PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
-    for (int i = 0; i < 3; ++i)
-        if ((rc = prefill(c, i, seq.data(), C - 1)) != PSD_OK) return rc;
+    if ((rc = prefill_all(c, seq.data(), C - 1)) != PSD_OK) return rc;
     PSD_HIP(hipEventRecord(c->ev[1], c->stream), c->err);
 
     while (C - n_prompt < n_new) {
