@@ -233,12 +233,13 @@ static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
     return PSD_OK;
 }
 
-// Ingests seq[len, upto) into all three models at once.  The ingestions are independent and their launches are too
-// small to fill the device one model at a time, so each model's passes run on a stream of their own; the context's
-// stream carries the descriptors and page tables and is where everything meets again.
-static int prefill_all(psd_ctx* c, const int32_t* seq, int upto) {
+// Ingests seq[len, upto) into several models at once (`models`: bit i = model i).  The ingestions are independent
+// and their launches are too small to fill the device one model at a time, so each model's passes run on a stream of
+// their own; the context's stream carries the descriptors and page tables and is where everything meets again.
+static int prefill_all(psd_ctx* c, const int32_t* seq, int upto, unsigned models = 7u) {
     if (c->prof.on) {   // per-kernel timing: one model after the other on the context's stream
         for (int mi = 0; mi < 3; ++mi) {
+            if (!(models >> mi & 1u)) continue;
             int rc = prefill(c, mi, seq, upto);
             if (rc != PSD_OK) return rc;
         }
@@ -250,7 +251,7 @@ static int prefill_all(psd_ctx* c, const int32_t* seq, int upto) {
             more = false;
             for (int mi = 0; mi < 3; ++mi) {
                 Model& M = c->M[mi];
-                if (M.len >= upto) continue;
+                if (!(models >> mi & 1u) || M.len >= upto) continue;
                 const int w = std::min(M.ingest_max, upto - M.len);
                 // the model's descriptor and page table are free again once its previous pass is done
                 if (used[mi]) PSD_HIP(hipStreamWaitEvent(c->stream, c->aux_done[mi], 0), c->err);
@@ -704,8 +705,7 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
     P.len = 0; T.len = 0;
     PSD_HIP(hipMemsetAsync(c->rs_acc, 0, 9 * sizeof(double), c->stream), c->err);
     PSD_HIP(hipEventRecord(c->ev[0], c->stream), c->err);
-    if ((rc = prefill(c, proposer, seq.data(), C - 1)) != PSD_OK) return rc;
-    if ((rc = prefill(c, 2, seq.data(), C - 1)) != PSD_OK) return rc;
+    if ((rc = prefill_all(c, seq.data(), C - 1, (1u << proposer) | 4u)) != PSD_OK) return rc;
     PSD_HIP(hipEventRecord(c->ev[1], c->stream), c->err);
     while (C - n_prompt < n_new) {
         // the proposer's first step ingests the host-known uncached suffix (two tokens after a fully accepted
