@@ -661,14 +661,14 @@ __global__ __launch_bounds__(64) void sample_final(const KeyIdx* parts, int nch,
 
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
                   const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf, int greedy) {
-    if (!logits || !tokens_out || !partial) PSD_FAIL(PSD_EINVAL, errbuf, "sample: null pointer");
+    if (!logits || !partial) PSD_FAIL(PSD_EINVAL, errbuf, "sample: null pointer");
     if (n_rows < 1 || n_rows > 65535 || vocab < 1 || !(temperature > 0.f))
         PSD_FAIL(PSD_EINVAL, errbuf, "sample: n_rows=%d vocab=%d temperature=%g", n_rows, vocab, temperature);
     if ((uintptr_t)logits & ((vocab & 3) == 0 ? 15 : 3)) PSD_FAIL(PSD_EINVAL, errbuf, "sample: logits rows must be 16-byte aligned (4-byte when the vocabulary is not a multiple of 4)");
     const int nch = accept_chunks(vocab);
     sample_partial<<<dim3(nch, n_rows), kAccThreads, 0, stream>>>(logits, vocab, nch, 1.0f / temperature, seed,
                                                                    position0, ctl, (KeyIdx*)partial, greedy);
-    sample_final<<<n_rows, 64, 0, stream>>>((const KeyIdx*)partial, nch, tokens_out);
+    if (tokens_out) sample_final<<<n_rows, 64, 0, stream>>>((const KeyIdx*)partial, nch, tokens_out);
     PSD_HIP(hipGetLastError(), errbuf);
     return PSD_OK;
 }

@@ -108,11 +108,16 @@ struct psd_ctx {
 
 namespace psd {
 
-// single thread: publishes the token just sampled to the next draft pass and to the qualifier pass
-__global__ void draft_advance(const int32_t* samp_tok, SampleCtl* chain, PassDesc* d_desc, PassDesc* q_desc,
-                              int32_t* round_tok) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const int t = samp_tok[0], step = chain->row;
+// one wave: picks the winner among the per-chunk winners of the sampling race (the comparisons of sample_final; equal
+// keys resolve to the lowest index) and publishes the token to the next draft pass and to the qualifier pass
+__global__ __launch_bounds__(64) void draft_pick_advance(const KeyIdx* parts, int nch, int32_t* samp_tok, SampleCtl* chain,
+                                                         PassDesc* d_desc, PassDesc* q_desc, int32_t* round_tok) {
+    KeyIdx best{-INFINITY, 0x7fffffff};
+    for (int ch = threadIdx.x; ch < nch; ch += kWave) best = better(best, parts[ch]);
+    best = wave_best(best);
+    if (threadIdx.x != 0) return;
+    const int t = best.idx, step = chain->row;
+    samp_tok[0] = t;
     if (step < kMaxW) round_tok[step] = t;
     if (q_desc && chain->q_base >= 0 && chain->q_base + step < kMaxW) q_desc->tok[chain->q_base + step] = t;
     d_desc->pos0 += d_desc->w;
@@ -169,10 +174,11 @@ static int run_pass(psd_ctx* c, int mi, int wcls, float* logits, bool with_sampl
         if (rc != PSD_OK) return rc;
         if (with_sample) {
             if (prof && prof->on) prof->begin(c->stream, prof->row_of("sample draft"), (double)c->V * 4);
-            rc = sample_launch(logits, 1, c->V, c->prm.temperature, 0, 0, c->chain, c->samp_tok, c->samp_part,
+            rc = sample_launch(logits, 1, c->V, c->prm.temperature, 0, 0, c->chain, nullptr, c->samp_part,
                                c->stream, c->err, (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0);
             if (rc != PSD_OK) return rc;
-            draft_advance<<<1, 64, 0, c->stream>>>(c->samp_tok, c->chain, M.desc, c->M[verifier].desc, c->round_tok);
+            draft_pick_advance<<<1, 64, 0, c->stream>>>((const KeyIdx*)c->samp_part, accept_chunks(c->V), c->samp_tok, c->chain,
+                                                         M.desc, c->M[verifier].desc, c->round_tok);
             if (prof && prof->on) prof->end(c->stream);
         }
         return PSD_OK;

@@ -69,6 +69,8 @@ struct SampleCtl {
 // Fresh samples: row r -> token for position position0 + r.  partial: n_rows * accept_chunks(vocab) * 8 bytes.
 // ctl (optional, device): when non-null, seed / position0 / first logits row come from *ctl instead.
 // greedy: the top prediction of every row instead of a sample.
+// tokens_out may be null: then the per-chunk winners stay in `partial` ([n_rows][accept_chunks(vocab)] KeyIdx) and the
+// caller picks among them (in a kernel of its own that has more to do with the token).
 int sample_launch(const float* logits, int n_rows, int vocab, float temperature, uint64_t seed, uint32_t position0,
                   const SampleCtl* ctl, int32_t* tokens_out, void* partial, hipStream_t stream, char* errbuf,
                   int greedy = 0);
