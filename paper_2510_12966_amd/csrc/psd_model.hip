@@ -344,6 +344,7 @@ struct GemmArgs {
     const u32x4* XB;       // packed activations [KS][CT][2][64] x 16 B
     int N, KS;
     int wcap;              // widest pass this launch is meant for (its launch class): operand columns >= wcap are not loaded
+    int lb_slots;          // LB kernels: 16-byte slots of a wave's staging area in LDS (64 per two K steps of its range)
     const PassDesc* desc;
     // rms scale of the input (EPI_QKV, EPI_SWIGLU, EPI_LOGITS): partial sums of squares [d/16][16 CT]
     const float* ss_in;
@@ -504,8 +505,15 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
 // Small projections get more waves and fewer tiles per workgroup so that enough loads are in flight.
 // The rms scale of the input is gathered on the side: every thread loads a few sum-of-squares partials before
 // the K loop and they are folded through LDS, in a fixed order, when the loop is done.
-template <int NT, int NW, int RT, int EPI, int CT>
+// LB (passes of at most 4 tokens, NT == 1): the few operand lanes that carry data are so little that a wave stages the
+// operand of its whole K range in LDS before it asks for any weights: direct-to-LDS loads, 64 lanes x 16 bytes = the
+// live blocks (4 columns x 4 k groups x hi, lo) of two K steps per instruction, no registers.  Loads return in order, so
+// the staged blocks are there before the first weight block, and a K step then reads its operand from LDS (~100
+// cycles) instead of L2 (~1400 cycles, of which a wave's two MFMAs per step hide nothing).
+template <int NT, int NW, int RT, int EPI, int CT, bool LB = false>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
+    static_assert(!LB || NT == 1, "LDS staging of the operand is for one column tile");
+    extern __shared__ u32x4 lb_buf[];
     constexpr int TG = NT > 2 ? 2 : NT;   // column tiles whose partials cross LDS together
     static_assert(RT <= NW, "one finishing wave per row tile");
     __shared__ f32x4 red[NW][RT][TG][64];
@@ -545,6 +553,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     const size_t tile_stride = (size_t)a.KS * 64;
     constexpr int kBStep = CT * 128;   // 16-byte words of the operand per K step
     const u32x4* b_ptr = a.XB + (size_t)k0 * kBStep + lane;
+    const u32x4* const b_base = b_ptr;
     bool col_live[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) col_live[t] = t * 16 + cc < a.wcap;   // known at launch: nothing waits for the descriptor
@@ -577,9 +586,45 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
         constexpr int BG = (U <= 8 && (RT >= 4 || EPI == EPI_QKV)) ? U : (U < 2 ? U : 2);
         static_assert(U % BG == 0, "operand groups must tile a batch");
         u32x4 bpre[BG][2];
+        const u32x4* my_b = nullptr;   // LB: this wave's staged operand, [pair of steps][step parity][hi, lo][k group][column < 4]
+        if constexpr (LB) {
+            const int n = k1 - k0;
+            u32x4* stage = lb_buf + __builtin_amdgcn_readfirstlane(wave) * a.lb_slots;
+            const int par = lane >> 5, half = (lane >> 4) & 1, sg = (lane >> 2) & 3, sc = lane & 3;
+            for (int i = 0; 2 * i < n; ++i) {
+                // a range with an odd number of steps: the last instruction's upper lanes fetch the last step again, into
+                // slots no step reads
+                const int st = min(2 * i + par, n - 1);
+                const u32x4* src = a.XB + (size_t)(k0 + st) * kBStep + half * 64 + sg * 16 + sc;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)(stage + i * 64), 16, 0, 0);
+            }
+            my_b = stage + g * 4 + cc;
+            asm volatile("" ::: "memory");   // the staging loads stay ahead of every other load of the wave
+        }
+        bool staged_ready = !LB;
+        // LB: called once, right after the first batch's weight loads (`later` of them, and nothing else, were issued after
+        // the staging loads): when at most `later` loads are outstanding the staged operand is in LDS
+        auto staged_wait = [&](bool full_batch) {
+            if constexpr (LB) {
+                if (staged_ready) return;
+                staged_ready = true;
+                if (full_batch) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(U * RT < 63 ? U * RT : 63) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+        };
         auto load_b = [&](int slot, const u32x4* bp) {
             bpre[slot][0] = zero; bpre[slot][1] = zero;
-            if (col_live[0]) { bpre[slot][0] = bp[0]; bpre[slot][1] = bp[64]; }
+            if constexpr (LB) {
+                // bp counts K steps in units of kBStep from the operand's start: recover the step within the wave's range
+                const int s = (int)((bp - b_base) / kBStep);
+                if (col_live[0]) {
+                    const u32x4* q = my_b + (s >> 1) * 64 + (s & 1) * 32;
+                    bpre[slot][0] = q[0]; bpre[slot][1] = q[16];
+                }
+            } else {
+                if (col_live[0]) { bpre[slot][0] = bp[0]; bpre[slot][1] = bp[64]; }
+            }
         };
         // batches of U K steps; the last batch of a range may be short (its loads still go out together)
         for (int ks = k0; ks < k1; ks += U) {
@@ -589,6 +634,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
+                staged_wait(true);
 #pragma unroll
                 for (int u = 0; u < BG; ++u) load_b(u, b_ptr + (size_t)u * kBStep);
                 if (want_pre) prefetch_all();
@@ -609,6 +655,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
 #pragma unroll
                         for (int r = 0; r < RT; ++r) wv[u][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)u * 64);
                     }
+                staged_wait(false);
 #pragma unroll
                 for (int u = 0; u < BG; ++u)
                     if (u < cnt) load_b(u, b_ptr + (size_t)u * kBStep);
@@ -1200,10 +1247,24 @@ static int round16(int n) { return (n + 15) & ~15; }
 
 static int attn_lds_bytes(int hd) { return (2 * kAttnSplit * (hd + 1) + 4 * hd + 4 * kAttnSplit) * (int)sizeof(float); }
 
+// most LDS a narrow GEMM may use for staging its operand (beside its 16 KB of partial sums)
+constexpr size_t kLbMaxBytes = 128 * 1024;
+
+template <int EPI>
+static int lb_kernels_init(char* err) {
+    PSD_HIP(hipFuncSetAttribute((const void*)gemm_bf16<1, 16, 1, EPI, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLbMaxBytes), err);
+    PSD_HIP(hipFuncSetAttribute((const void*)gemm_bf16<1, 8, 2, EPI, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLbMaxBytes), err);
+    PSD_HIP(hipFuncSetAttribute((const void*)gemm_bf16<1, 8, 1, EPI, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLbMaxBytes), err);
+    return PSD_OK;
+}
+
 int model_kernels_init(char* err) {
     // attention stages two pages of K and V as fp32 in LDS: up to ~135 KB of the 160 KB a gfx950 CU has
     PSD_HIP(hipFuncSetAttribute((const void*)attn_partial<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 attn_lds_bytes(128)), err);
+    int rc;
+    if ((rc = lb_kernels_init<EPI_RESID>(err)) != PSD_OK) return rc;
+    if ((rc = lb_kernels_init<EPI_LOGITS>(err)) != PSD_OK) return rc;
     return PSD_OK;
 }
 
@@ -1525,14 +1586,28 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
                 done = true;
             }
         }
+        // passes of at most 4 tokens: the operand of a wave's whole K range is staged in LDS, 512 bytes per K step and wave
+        const int nw = tiles <= 256 ? 16 : 8;
+        const int lb_slots = 64 * (((a.KS + nw - 1) / nw + 1) / 2);
+        const size_t lb_bytes = (size_t)nw * lb_slots * sizeof(u32x4);
+        // Measured on the draft's shapes: long K ranges gain (down projection, 16 steps per wave: 14.3 -> 13.3 us) and
+        // so does the LM head (89.6 -> 86.4 us); ranges of 4 or 8 steps lose 0.2 us to the wait for the staged blocks
+        constexpr bool kHasLb = EPI == EPI_RESID || EPI == EPI_LOGITS;
+        const bool lb = kHasLb && L.wcls <= 4 && lb_bytes <= kLbMaxBytes && (EPI == EPI_LOGITS || (a.KS + nw - 1) / nw >= 12);
+        a.lb_slots = lb_slots;
+#define PSD_GEMM_LB(NW_, RT_)                                                                                      \
+    do {                                                                                                           \
+        if constexpr (kHasLb) gemm_bf16<1, NW_, RT_, EPI, 2, true><<<tiles / RT_, 64 * NW_, lb_bytes, L.s>>>(a);   \
+    } while (0)
         if (done) {
         } else if (tiles <= 256) {
-            if (wide) PSD_GEMM(2, 16, 1, 2); else PSD_GEMM(1, 16, 1, 2);
+            if (lb) PSD_GEMM_LB(16, 1); else if (wide) PSD_GEMM(2, 16, 1, 2); else PSD_GEMM(1, 16, 1, 2);
         } else if (tiles % 2 == 0) {
-            if (wide) PSD_GEMM(2, 8, 2, 2); else PSD_GEMM(1, 8, 2, 2);
+            if (lb) PSD_GEMM_LB(8, 2); else if (wide) PSD_GEMM(2, 8, 2, 2); else PSD_GEMM(1, 8, 2, 2);
         } else {
-            if (wide) PSD_GEMM(2, 8, 1, 2); else PSD_GEMM(1, 8, 1, 2);
+            if (lb) PSD_GEMM_LB(8, 1); else if (wide) PSD_GEMM(2, 8, 1, 2); else PSD_GEMM(1, 8, 1, 2);
         }
+#undef PSD_GEMM_LB
     }
 #undef PSD_GEMM
     L.end();
