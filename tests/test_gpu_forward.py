@@ -227,6 +227,30 @@ def test_bf16_context_length_switches_are_bit_exact():
     ctx.close()
 
 
+def test_bf16_narrow_passes_with_long_k_ranges_are_bit_exact():
+    # passes of up to 4 tokens read the operand of a down projection with long K ranges (here 12 and 13 K steps per
+    # wave, odd and even, and a ragged split of K over the waves) and of every LM head from LDS instead of registers:
+    # same bits as 5- and 11-token passes, which never do, and the logits match the oracle
+    shapes = (ModelShape(2, 256, 4, 2, 6144, 1000), ModelShape(1, 512, 4, 4, 6560, 1000), ModelShape(1, 256, 4, 1, 6656, 1000))
+    blobs = [synth.target_weights(s, 60 + i, synth.DTYPE_BF16, sigma=0.02) for i, s in enumerate(shapes)]
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 10000.0, 160)
+    toks = synth.tokens(15, 0, 150, 1000)
+    for which in range(3):
+        pos, narrow, k = 0, [], 0
+        while pos < 132:
+            w = min((1, 4, 2, 3)[k % 4], 132 - pos)
+            narrow.append(ctx.forward(which, toks[pos:pos + w], pos))
+            pos += w
+            k += 1
+        narrow = np.concatenate(narrow)
+        wide = np.concatenate([ctx.forward(which, toks[p:p + 11], p) for p in range(0, 132, 11)])
+        five = np.concatenate([ctx.forward(which, toks[p:p + 5], p) for p in range(0, 130, 5)])
+        assert np.array_equal(narrow, wide) and np.array_equal(narrow[:130], five)
+        om = oracle.Model(shapes[which], blobs[which], synth.DTYPE_BF16, 10000.0, 160)
+        assert np.abs(narrow - om.forward(toks[:132], 0)).max() <= TOL_BF16
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
