@@ -229,6 +229,31 @@ int psd_accept_batch(const float* logits_p, const float* logits_q, const int32_t
                      uint32_t stage, int32_t take_bonus, int32_t* n_accepted, int32_t* next_token, float* div_out,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* psd_accept_batch for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and results as psd_accept_batch (all pointers
+ * DEVICE memory, the call only enqueues work on `stream`), but the scratch the kernels need comes from a fixed
+ * array of PSD_ACCEPT_NOALLOC_SCRATCH_BYTES inside the library's code object instead of a caller workspace; each
+ * GPU the library runs on holds that array until the process ends.  The call makes no hipMalloc / hipFree and no
+ * allocating library call.
+ *   - Limit: psd_accept_workspace_bytes(n_trials, k, vocab) <= psd_accept_noalloc_capacity() (e.g. one trial of
+ *     k = 31 at vocabulary 128256 needs 82 KB, 48 trials of k = 32 about 4.1 MB); larger requests return PSD_ENOMEM and
+ *     enqueue nothing.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different streams, or
+ *     different threads) race on it.  Serialise them, or use psd_accept_batch with separate workspaces.
+ *   - The array keeps what the last call left; every slot a call reads is written earlier in that call's own
+ *     launch sequence (a fill kernel, not a memset, so the sequence can be captured into a graph).
+ *   - psd_accept_noalloc_init() looks up the array's device address for the current device (no allocation);
+ *     psd_create calls it, and so does the first psd_accept_batch_noalloc on a device.  Call it once outside
+ *     stream capture if the first use would otherwise fall inside one.
+ * Errors: PSD_EINVAL, PSD_ENOMEM (request beyond the capacity), PSD_EHIP. */
+#define PSD_ACCEPT_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+size_t psd_accept_noalloc_capacity(void);
+int psd_accept_noalloc_init(void);
+int psd_accept_batch_noalloc(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t n_trials,
+                             int32_t k, int32_t vocab, float T, float temperature, uint64_t seed, uint32_t position0,
+                             uint32_t stage, int32_t take_bonus, int32_t* n_accepted, int32_t* next_token,
+                             float* div_out, void* stream);
+
 /* How the ACCEPT stage sweeps the logits (Section 3.2 divergence), process-wide; for measurement and tests.
  *   0  automatic: one launch that reads every logit once when a row has at most 64 chunks of 5120 entries,
  *      else two launches that read the logits twice

@@ -77,6 +77,8 @@ def lib():
         L.psd_accept_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                        C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.psd_accept_noalloc_capacity.restype = C.c_size_t
+        L.psd_accept_batch_noalloc.argtypes = L.psd_accept_batch.argtypes[:15] + [C.c_void_p]
         L.psd_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_uint32, C.c_int32,
                                  C.c_void_p]
         L.psd_dev_alloc.argtypes = [C.c_size_t, C.POINTER(C.c_void_p)]
@@ -227,6 +229,22 @@ def accept_batch(logits_p, logits_q, tokens, n_trials, k, vocab, T, temperature,
     _check(lib().psd_accept_batch(_ptr(logits_p), _ptr(logits_q), _ptr(tokens), n_trials, k, vocab, T, temperature,
                                   seed, position0, stage, int(take_bonus), _ptr(n_accepted), _ptr(next_token),
                                   _ptr(div_out), _ptr(workspace), workspace_bytes, stream))
+
+
+def accept_noalloc_capacity():
+    return lib().psd_accept_noalloc_capacity()
+
+
+def accept_noalloc_init():
+    _check(lib().psd_accept_noalloc_init())
+
+
+def accept_batch_noalloc(logits_p, logits_q, tokens, n_trials, k, vocab, T, temperature, seed, position0, stage,
+                         take_bonus, n_accepted, next_token, div_out, stream=None):
+    """psd_accept_batch_noalloc on device buffers: as accept_batch, scratch held by the library; only enqueues."""
+    _check(lib().psd_accept_batch_noalloc(_ptr(logits_p), _ptr(logits_q), _ptr(tokens), n_trials, k, vocab, T,
+                                          temperature, seed, position0, stage, int(take_bonus), _ptr(n_accepted),
+                                          _ptr(next_token), _ptr(div_out), stream))
 
 
 def sample(logits, temperature=1.0, seed=0, position0=0):

@@ -22,6 +22,9 @@
 // The assisted stage (Section 3.4) needs no softmax at all: accept_top finds the verifier's top prediction
 // per position, accept_decide_assisted compares tokens, and the replacement draw races over the verifier's
 // own row in log form.
+#include <atomic>
+#include <mutex>
+
 #include "psd_device.h"
 #include "psd_host.h"
 
@@ -803,4 +806,66 @@ extern "C" int psd_accept_batch(const float* logits_p, const float* logits_q, co
     int rc = accept_launch(logits_p, logits_q, tokens, n_trials, k, vocab, T, temperature, seed, position0, stage,
                            take_bonus, out, div_out, workspace, inner, st, err, n_accepted, next_token);
     return rc;
+}
+
+// ---- ACCEPT for callers that cannot allocate ------------------------------------------------------
+// The workspace of psd_accept_batch (per-chunk partials, race winners, per-trial results) lives in a file-scope
+// device array instead of caller memory.  The array's name is only a host-side handle: the address kernels and
+// copies use is asked for once per device (with that device current) and kept; every GPU has its own copy.
+constexpr size_t kNoallocScratchBytes = PSD_ACCEPT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoallocScratchBytes];
+
+namespace {
+constexpr int kNoallocMaxDevices = 64;
+std::atomic<void*> g_noalloc_ptr[kNoallocMaxDevices];
+std::mutex g_noalloc_mutex;
+
+// device address of the scratch array on the current device (no allocation: the array is part of the code object)
+int noalloc_scratch(void** out, char* err) {
+    int dev = -1;
+    PSD_HIP(hipGetDevice(&dev), err);
+    if (dev < 0 || dev >= kNoallocMaxDevices) PSD_FAIL(PSD_EINVAL, err, "psd_accept_batch_noalloc: device ordinal %d", dev);
+    void* p = g_noalloc_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+        p = g_noalloc_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            PSD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch)), err);
+            if (!p || ((uintptr_t)p & 255)) PSD_FAIL(PSD_EHIP, err, "psd_accept_batch_noalloc: bad scratch address %p", p);
+            g_noalloc_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return PSD_OK;
+}
+}  // namespace
+
+extern "C" size_t psd_accept_noalloc_capacity(void) { return kNoallocScratchBytes; }
+
+extern "C" int psd_accept_noalloc_init(void) {
+    void* p = nullptr;
+    return noalloc_scratch(&p, tls_error());
+}
+
+extern "C" int psd_accept_batch_noalloc(const float* logits_p, const float* logits_q, const int32_t* tokens,
+                                        int32_t n_trials, int32_t k, int32_t vocab, float T, float temperature,
+                                        uint64_t seed, uint32_t position0, uint32_t stage, int32_t take_bonus,
+                                        int32_t* n_accepted, int32_t* next_token, float* div_out, void* stream) {
+    char* err = tls_error();
+    if (!n_accepted || !next_token) PSD_FAIL(PSD_EINVAL, err, "psd_accept_batch_noalloc: null pointer");
+    if (n_trials < 1 || k < 0 || vocab < 1) PSD_FAIL(PSD_EINVAL, err, "psd_accept_batch_noalloc: bad sizes");
+    if (stage != 1 && stage != 2) PSD_FAIL(PSD_EINVAL, err, "psd_accept_batch_noalloc: stage must be 1 or 2");
+    const size_t need = psd_accept_workspace_bytes(n_trials, k, vocab);
+    if (need > kNoallocScratchBytes)
+        PSD_FAIL(PSD_ENOMEM, err, "psd_accept_batch_noalloc: n_trials=%d k=%d vocab=%d need %zu bytes of scratch, the library holds %zu",
+                 n_trials, k, vocab, need, kNoallocScratchBytes);
+    void* scratch = nullptr;
+    int rc = noalloc_scratch(&scratch, err);
+    if (rc != PSD_OK) return rc;
+    const size_t inner = accept_workspace_bytes(n_trials, k, vocab);
+    AcceptOut* out = (AcceptOut*)((char*)scratch + inner);
+    // every slot the kernels read is written earlier in the same launch sequence (accept_clear marks the per-chunk
+    // partials unwritten and clears the expiry flag), so whatever the previous call left behind is never seen
+    return accept_launch(logits_p, logits_q, tokens, n_trials, k, vocab, T, temperature, seed, position0, stage,
+                         take_bonus, out, div_out, scratch, inner, (hipStream_t)stream, err, n_accepted, next_token);
 }

@@ -404,6 +404,7 @@ extern "C" int psd_create(const psd_model_desc* draft, const psd_model_desc* qua
     c->pool.base = (char*)c->pool_mem;
     c->pool.size = pool_bytes;
     if ((rc = model_kernels_init(c->err)) != PSD_OK) return fail(rc);
+    if ((rc = psd_accept_noalloc_init()) != PSD_OK) { strncpy(c->err, tls_error(), 511); return fail(rc); }
     const char* tags[3] = {"draft", "qualifier", "target"};
     const bool scramble = (params->flags & 0x100) != 0;  // test aid: physical KV pages out of logical order
     for (int i = 0; i < 3; ++i)
