@@ -41,7 +41,10 @@ class Stats(C.Structure):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
+ROW_TRACE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_float), C.c_int)
+
 _LIB = None
+_ROW_TRACE_CB = None
 
 
 def lib():
@@ -88,6 +91,9 @@ def lib():
         L.orc_generate_plain.restype = C.c_int
         L.orc_generate_plain.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_int, C.c_int, C.c_uint64,
                                          C.c_void_p]
+        L.orc_philox_block.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
+        L.orc_residual.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.orc_set_row_trace.argtypes = [ROW_TRACE_FN, C.c_void_p]
         _LIB = L
     return _LIB
 
@@ -101,6 +107,34 @@ def philox4x32_10(ctr, key):
     out = np.zeros(4, dtype=np.uint32)
     lib().orc_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
     return out
+
+
+def philox_block(seed, c0, n, c1, c2, c3):
+    """Generator output [n, 4] (uint32) for the counters (c0 .. c0 + n - 1, c1, c2, c3) under key `seed`."""
+    out = np.empty((n, 4), dtype=np.uint32)
+    lib().orc_philox_block(seed, c0, n, c1, c2, c3, out.ctypes.data)
+    return out
+
+
+def residual(p, q):
+    """Un-normalised replacement weights max(0, p - q) of a rejected position."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    r = np.empty_like(p)
+    lib().orc_residual(p.ctypes.data, q.ctypes.data, p.size, r.ctypes.data)
+    return r
+
+
+def set_row_trace(fn):
+    """fn(which, prefix tokens (numpy copy), logits row (numpy copy)) for every row a generation loop consumes; None: off."""
+    global _ROW_TRACE_CB
+    if fn is None:
+        _ROW_TRACE_CB = ROW_TRACE_FN(0)
+    else:
+        def cb(user, which, prefix, n_prefix, row, V):
+            fn(which, np.ctypeslib.as_array(prefix, shape=(n_prefix,)).copy(), np.ctypeslib.as_array(row, shape=(V,)).copy())
+        _ROW_TRACE_CB = ROW_TRACE_FN(cb)
+    lib().orc_set_row_trace(_ROW_TRACE_CB, None)
 
 
 def uniform(seed, v, position, purpose, stage):

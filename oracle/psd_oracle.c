@@ -52,6 +52,16 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+/* The generator's output for n consecutive counters (c0 .. c0 + n - 1, c1, c2, c3) under one key:
+ * out[i][0..3].  A plain loop over the function above, for comparisons against other implementations. */
+void orc_philox_block(uint64_t seed, uint32_t c0, uint32_t n, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t* out) {
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t ctr[4] = {c0 + i, c1, c2, c3};
+        orc_philox4x32_10(ctr, key, out + 4 * (size_t)i);
+    }
+}
+
 /* Draw addressing.  One uniform per (seed, vocabulary index v, draw position,
  * purpose, stage): counter = (v / 4, position, purpose, stage), word v % 4,
  * key = the 64-bit seed.  u = (top 23 bits + 1/2) / 2^23 lies strictly inside
@@ -181,6 +191,13 @@ int orc_accept_scan(const double* p, const double* q, const int32_t* x, int k, i
     return k;
 }
 
+/* Un-normalised replacement distribution of a rejected position: the standard speculative-sampling
+ * residual r_v = max(0, p_v - q_v) (the fallback rule Section 3.4 names; with it tau = 0 reproduces the
+ * verifier's law, Section 3.1). */
+void orc_residual(const double* p, const double* q, int V, double* r) {
+    for (int v = 0; v < V; ++v) r[v] = p[v] > q[v] ? p[v] - q[v] : 0.0;
+}
+
 /* Full stage: softmax both logit stacks at `temperature`, scan, then draw the
  * replacement token: from norm(max(0, p_n - q_n)) at the first rejection n
  * (standard SD residual), or from p_k when every proposal was accepted and
@@ -208,7 +225,7 @@ void orc_accept(const float* logits_p, const float* logits_q, const int32_t* x, 
         double* r = (double*)malloc((size_t)V * sizeof(double));
         const double* pn = p + (size_t)n * V;
         const double* qn = q + (size_t)n * V;
-        for (int v = 0; v < V; ++v) r[v] = pn[v] > qn[v] ? pn[v] - qn[v] : 0.0;
+        orc_residual(pn, qn, V, r);
         int t = orc_race(r, V, seed, position0 + (uint32_t)n, ORC_DRAW_RESAMPLE, stage, &res->margin_race);
         if (t < 0) /* no residual mass (cannot happen in exact arithmetic): fall back to p_n */
             t = orc_race(pn, V, seed, position0 + (uint32_t)n, ORC_DRAW_RESAMPLE, stage, &res->margin_race);
@@ -461,15 +478,28 @@ typedef struct {
 
 static int imin(int a, int b) { return a < b ? a : b; }
 
+/* Observer for tests: called for every logits row a generation loop consumes, with the model that
+ * produced it (0 draft / proposer, 1 qualifier, 2 target), the tokens the row is conditioned on
+ * (prefix[0 .. n_prefix - 1], the loop's own sequence buffer) and the row itself.  Lets a test compare what
+ * the loop saw, after all its cache rollbacks, with a fresh recomputation of the same prefix. */
+typedef void (*orc_row_trace_fn)(void* user, int which, const int32_t* prefix, int n_prefix, const float* row, int V);
+static orc_row_trace_fn g_row_trace = NULL;
+static void* g_row_trace_user = NULL;
+void orc_set_row_trace(orc_row_trace_fn fn, void* user) { g_row_trace = fn; g_row_trace_user = user; }
+
 /* Runs model m over the tokens of seq it has not cached yet, up to index `upto`
  * (exclusive); writes the last n_rows logit rows as floats into rows_out. */
-static int run_model(orc_model* m, const int32_t* seq, int* len, int upto, int n_rows, float* rows_out) {
+static int run_model(orc_model* m, int which, const int32_t* seq, int* len, int upto, int n_rows, float* rows_out) {
     int w = upto - *len, V = m->vocab;
+    if (w < 1 || n_rows > w) return -4; /* the caller's cache bookkeeping is out of step with the sequence */
     double* lg = n_rows > 0 ? (double*)malloc((size_t)w * V * sizeof(double)) : NULL;
     int rc = orc_forward(m, seq + *len, w, *len, lg);
     if (rc == 0) {
         for (int j = 0; j < n_rows; ++j)
             for (int v = 0; v < V; ++v) rows_out[(size_t)j * V + v] = (float)lg[(size_t)(w - n_rows + j) * V + v];
+        if (g_row_trace)
+            for (int j = 0; j < n_rows; ++j)
+                g_row_trace(g_row_trace_user, which, seq, upto - n_rows + j + 1, rows_out + (size_t)j * V, V);
         *len = upto;
     }
     free(lg);
@@ -509,9 +539,9 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
     int C = n_prompt, lenD = 0, lenQ = 0, lenT = 0, rc = 0;
     /* prefill: everything but the last prompt token, which stays pending */
     if (C > 1) {
-        rc |= run_model(D, seq, &lenD, C - 1, 0, NULL);
-        rc |= run_model(Q, seq, &lenQ, C - 1, 0, NULL);
-        rc |= run_model(T, seq, &lenT, C - 1, 0, NULL);
+        rc |= run_model(D, 0, seq, &lenD, C - 1, 0, NULL);
+        rc |= run_model(Q, 1, seq, &lenQ, C - 1, 0, NULL);
+        rc |= run_model(T, 2, seq, &lenT, C - 1, 0, NULL);
     }
     orc_accept_result ar;
     while (rc == 0 && C - n_prompt < n_new) {
@@ -519,13 +549,13 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
         while (nbuf < k2) {
             int m = imin(k1, k2 - nbuf), L = C + nbuf;
             for (int i = 0; i < m; ++i) {
-                rc |= run_model(D, seq, &lenD, L + i, 1, dl + (size_t)i * V);
+                rc |= run_model(D, 0, seq, &lenD, L + i, 1, dl + (size_t)i * V);
                 st->passes_d++;
                 seq[L + i] = assisted == 2 ? row_argmax(dl + (size_t)i * V, V)
                                            : orc_sample_row(dl + (size_t)i * V, V, prm->temperature, seed, (uint32_t)(L + i),
                                                             ORC_DRAW_SAMPLE, 0u, NULL);
             }
-            rc |= run_model(Q, seq, &lenQ, L + m, m + 1, ql);
+            rc |= run_model(Q, 1, seq, &lenQ, L + m, m + 1, ql);
             st->passes_q++;
             int bonus = nbuf + m < k2;
             if (assisted == 2)
@@ -542,7 +572,7 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
             lenD = imin(lenD, L + n);
             st->proposed_q += m; st->accepted_q += n; st->fuzzy_q += ar.n_fuzzy;
         }
-        rc |= run_model(T, seq, &lenT, C + k2, k2 + 1, tl);
+        rc |= run_model(T, 2, seq, &lenT, C + k2, k2 + 1, tl);
         st->passes_t++;
         if (assisted == 2)
             orc_accept_greedy(tl, seq + C, k2, V, 1, &ar);
@@ -601,18 +631,18 @@ int orc_generate_sd(orc_model* P, orc_model* T, int k, double tau, double temper
     memset(st, 0, sizeof(*st));
     int C = n_prompt, lenP = 0, lenT = 0, rc = 0;
     if (C > 1) {
-        rc |= run_model(P, seq, &lenP, C - 1, 0, NULL);
-        rc |= run_model(T, seq, &lenT, C - 1, 0, NULL);
+        rc |= run_model(P, 0, seq, &lenP, C - 1, 0, NULL);
+        rc |= run_model(T, 2, seq, &lenT, C - 1, 0, NULL);
     }
     orc_accept_result ar;
     while (rc == 0 && C - n_prompt < n_new) {
         for (int i = 0; i < k; ++i) {
-            rc |= run_model(P, seq, &lenP, C + i, 1, pl + (size_t)i * V);
+            rc |= run_model(P, 0, seq, &lenP, C + i, 1, pl + (size_t)i * V);
             st->passes_d++;
             seq[C + i] = orc_sample_row(pl + (size_t)i * V, V, temperature, seed, (uint32_t)(C + i), ORC_DRAW_SAMPLE,
                                         0u, NULL);
         }
-        rc |= run_model(T, seq, &lenT, C + k, k + 1, tl);
+        rc |= run_model(T, 2, seq, &lenT, C + k, k + 1, tl);
         st->passes_t++;
         orc_accept(tl, pl, seq + C, k, V, tau, temperature, seed, (uint32_t)C, 2u, 1, &ar, NULL);
         int n = ar.n_accepted;
@@ -638,7 +668,7 @@ int orc_generate_plain(orc_model* M, double temperature, const int32_t* prompt, 
     int len = 0, rc = 0;
     for (int i = 0; i < n_new && rc == 0; ++i) {
         int L = n_prompt + i;
-        rc = run_model(M, seq, &len, L, 1, row);
+        rc = run_model(M, 0, seq, &len, L, 1, row);
         seq[L] = orc_sample_row(row, V, temperature, seed, (uint32_t)L, ORC_DRAW_SAMPLE, 0u, NULL);
     }
     if (rc == 0) memcpy(out_tokens, seq + n_prompt, (size_t)n_new * sizeof(int32_t));

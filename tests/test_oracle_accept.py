@@ -175,3 +175,69 @@ def test_k_zero_draws_only_the_bonus():
     lp = np.log(np.array([[0.25, 0.75]])).astype(np.float32)
     res, div = oracle.accept(lp, np.zeros((0, 2), np.float32), [], 0.3, 1.0, seed=2, position0=9, stage=1)
     assert res.n_accepted == 0 and res.next_token in (0, 1) and div.size == 0
+
+
+def _accept_threshold(p_rows, q_rows, x, pos):
+    """Largest coin value at which position `pos` is still accepted at tau = 0, found on the oracle's own scan:
+    the scan is monotone in every coin, so bisection on explicit coin values pins the switch to ~1e-16.  Earlier
+    positions get coin 0 (always accepted); the result is P(accept at pos | reached, x)."""
+    k = len(x)
+    passes = lambda u: oracle.accept_scan(p_rows, q_rows, x, 0.0, [0.0] * pos + [u] + [0.0] * (k - pos - 1))[0] > pos
+    if passes(np.nextafter(1.0, 0.0)):
+        return 1.0
+    lo, hi = 0.0, 1.0     # passes(lo) (coin 0 always passes when p(x) > 0), not passes(hi)
+    if not passes(0.0):
+        return 0.0
+    for _ in range(70):
+        mid = 0.5 * (lo + hi)
+        if passes(mid):
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def test_tau0_exact_enumeration_on_vocab8_length2_reproduces_the_target_chain():
+    # tau = 0 is standard speculative decoding (Section 3.1), whose output law is the verifier's, exactly.
+    # Enumerate every proposal pair (x0, x1); integrate the two coins exactly from the oracle's scan evaluated on
+    # explicit coin values (bisection: no formula of the rule is retyped here); take the replacement law from the
+    # oracle's residual weights, normalised.  The law of the emitted tokens must be the target chain to rounding.
+    V = 8
+    rng = np.random.default_rng(7)
+    q0, q1, p0, p1, p2 = _chain_tables(rng, V)
+    # make the case generic: a token the proposer over-weights, one it under-weights, one the verifier excludes
+    p0 = p0.copy(); p0[2] = 0.0; p0 /= p0.sum()
+    first = np.zeros(V)                 # law of the first emitted token
+    pair = np.zeros((V, V))             # law of the first two emitted tokens, when the first proposal was accepted
+    first_accepted = np.zeros(V)        # P(x0 = a and accepted)
+    triple_ok = 0.0
+    for x0 in range(V):
+        P = np.stack([p0, p1[x0]]); Q = np.stack([q0, q1[x0]])
+        a0 = _accept_threshold(P, Q, [x0, 0], 0)
+        first[x0] += q0[x0] * a0
+        first_accepted[x0] = q0[x0] * a0
+        r0 = oracle.residual(p0, q0)
+        if q0[x0] * (1 - a0) > 0:
+            assert r0.sum() > 0
+            first += q0[x0] * (1 - a0) * r0 / r0.sum()
+        for x1 in range(V):
+            a1 = _accept_threshold(P, Q, [x0, x1], 1)
+            w = q0[x0] * a0 * q1[x0][x1]
+            pair[x0, x1] += w * a1
+            r1 = oracle.residual(p1[x0], q1[x0])
+            if w * (1 - a1) > 0:
+                pair[x0] += w * (1 - a1) * r1 / r1.sum()
+            triple_ok += w * a1        # both accepted: the bonus token is a fresh sample of p2[x0, x1] (pinned elsewhere)
+    np.testing.assert_allclose(first, p0, rtol=0, atol=1e-12)
+    assert first[2] == 0.0                                  # a token outside the verifier's support never comes out
+    # given that x0 = a was accepted, the next emitted token follows p1[a]; P(x0 = a accepted) = min(p0, q0)[a]
+    np.testing.assert_allclose(first_accepted, np.minimum(p0, q0), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(pair, first_accepted[:, None] * p1, rtol=0, atol=1e-12)
+    # chain law of two emitted tokens: a first token that came out of a rejection is followed by a fresh stage whose
+    # first-token law is, by the statement just checked, its own verifier row p1[a]
+    rejected_first = first - first_accepted
+    joint = pair + rejected_first[:, None] * p1
+    np.testing.assert_allclose(joint, p0[:, None] * p1, rtol=0, atol=1e-12)
+    assert abs(triple_ok - sum(min(p0[a], q0[a]) * np.minimum(p1[a], q1[a]).sum() for a in range(V))) < 1e-12
+    # the enumeration separates the rule from near misses: the proposer's law and the plain mixture are far away
+    assert np.abs(first - q0).max() > 1e-2
