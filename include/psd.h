@@ -272,6 +272,14 @@ int psd_get_accept_path(void);
 int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, float temperature, uint64_t seed,
                uint32_t position0, int32_t where, int32_t* tokens_out);
 
+/* Test hook: the device's Philox4x32-10, the generator behind every draw above, for the n consecutive counters
+ * (c0 .. c0 + n - 1, c1, c2, c3) under key = seed.  out [n][4] uint32 raw words and / or u_out [n][4] floats (the
+ * uniforms the kernels derive from them: (top 23 bits + 1/2) / 2^23); either may be NULL.  where: 0 host pointers,
+ * 1 device pointers (16-byte aligned).  1 <= n <= 2^26.  Lets a test compare the generator with an independent
+ * implementation counter by counter. */
+int psd_philox_block(uint64_t seed, uint32_t c0, uint32_t n, uint32_t c1, uint32_t c2, uint32_t c3, int32_t where,
+                     uint32_t* out, float* u_out);
+
 /* Trace hook for tests: when set, psd_generate copies the inputs of every draft
  * sample (kind 0, k = 0, logits_p = the draft row) and every ACCEPT (kind 1 / 2 =
  * stage; kind 3 = stage 1 under the assisted rule; greedy decoding: kind 6 = proposal, 4 / 5 = stage 1 / 2)

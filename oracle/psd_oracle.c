@@ -394,7 +394,6 @@ int orc_forward(orc_model* m, const int32_t* tokens, int w, int pos0, double* lo
     double* o = (double*)malloc((size_t)w * d * sizeof(double));
     double* g = (double*)malloc((size_t)w * F * sizeof(double));
     double* u = (double*)malloc((size_t)w * F * sizeof(double));
-    double* sc = (double*)malloc((size_t)(pos0 + w) * sizeof(double));
     for (int c = 0; c < w; ++c)
         for (int i = 0; i < d; ++i) x[(size_t)c * d + i] = wload(m->blob, m->dtype, (size_t)tokens[c] * d + i);
     size_t off = (size_t)V * d;
@@ -421,9 +420,12 @@ int orc_forward(orc_model* m, const int32_t* tokens, int w, int pos0, double* lo
             memcpy(kc + (size_t)(pos0 + c) * kvw, kk + (size_t)c * kvw, kvw * sizeof(double));
             memcpy(vc + (size_t)(pos0 + c) * kvw, vv + (size_t)c * kvw, kvw * sizeof(double));
         }
+        /* every (token, head) pair is independent; the threads only share read-only data (speed, not arithmetic) */
+#pragma omp parallel for collapse(2) schedule(dynamic)
         for (int c = 0; c < w; ++c) {
-            int nk = pos0 + c + 1; /* causal: keys 0 .. own position */
             for (int h = 0; h < H; ++h) {
+                int nk = pos0 + c + 1; /* causal: keys 0 .. own position */
+                double* sc = (double*)malloc((size_t)nk * sizeof(double));
                 int kvh = h / G;
                 const double* qh = q + (size_t)c * qw + (size_t)h * hd;
                 double mx = -INFINITY;
@@ -440,6 +442,7 @@ int orc_forward(orc_model* m, const int32_t* tokens, int w, int pos0, double* lo
                     for (int t = 0; t < nk; ++t) a += sc[t] * vc[(size_t)t * kvw + (size_t)kvh * hd + i];
                     att[(size_t)c * qw + (size_t)h * hd + i] = a / den;
                 }
+                free(sc);
             }
         }
         matmul(m, o_wo, d, qw, att, w, o);
@@ -457,7 +460,7 @@ int orc_forward(orc_model* m, const int32_t* tokens, int w, int pos0, double* lo
         matmul(m, 0, V, d, xn, w, logits);
     }
     m->passes++;
-    free(x); free(xn); free(q); free(kk); free(vv); free(att); free(o); free(g); free(u); free(sc);
+    free(x); free(xn); free(q); free(kk); free(vv); free(att); free(o); free(g); free(u);
     return 0;
 }
 

@@ -79,6 +79,8 @@ def lib():
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.psd_accept_noalloc_capacity.restype = C.c_size_t
         L.psd_accept_batch_noalloc.argtypes = L.psd_accept_batch.argtypes[:15] + [C.c_void_p]
+        L.psd_philox_block.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
+                                       C.c_void_p, C.c_void_p]
         L.psd_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_uint32, C.c_int32,
                                  C.c_void_p]
         L.psd_dev_alloc.argtypes = [C.c_size_t, C.POINTER(C.c_void_p)]
@@ -245,6 +247,14 @@ def accept_batch_noalloc(logits_p, logits_q, tokens, n_trials, k, vocab, T, temp
     _check(lib().psd_accept_batch_noalloc(_ptr(logits_p), _ptr(logits_q), _ptr(tokens), n_trials, k, vocab, T,
                                           temperature, seed, position0, stage, int(take_bonus), _ptr(n_accepted),
                                           _ptr(next_token), _ptr(div_out), stream))
+
+
+def philox_block(seed, c0, n, c1, c2, c3):
+    """psd_philox_block into host arrays: (raw words [n, 4] uint32, uniforms [n, 4] float32)."""
+    out = np.empty((n, 4), dtype=np.uint32)
+    u = np.empty((n, 4), dtype=np.float32)
+    _check(lib().psd_philox_block(seed, c0, n, c1, c2, c3, 0, out.ctypes.data, u.ctypes.data))
+    return out, u
 
 
 def sample(logits, temperature=1.0, seed=0, position0=0):

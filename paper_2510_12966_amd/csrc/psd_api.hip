@@ -2,6 +2,7 @@
 // (they stage through temporary device buffers; the hot path never uses them).
 #include <string.h>
 
+#include "psd_device.h"
 #include "psd_host.h"
 
 namespace psd {
@@ -17,6 +18,16 @@ void set_error(char* dst, const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(dst, 512, fmt, ap);
     va_end(ap);
+}
+
+// the generator exactly as the sampling and ACCEPT kernels call it, one counter per thread
+__global__ void philox_block(uint64_t seed, uint32_t c0, uint32_t n, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t* out,
+                             float* u_out) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const U4 r = philox4x32_10(U4{c0 + i, c1, c2, c3}, (uint32_t)seed, (uint32_t)(seed >> 32));
+    if (out) reinterpret_cast<uint4*>(out)[i] = make_uint4(r.x, r.y, r.z, r.w);
+    if (u_out) reinterpret_cast<float4*>(u_out)[i] = make_float4(u01(r.x), u01(r.y), u01(r.z), u01(r.w));
 }
 
 struct DevBuf {  // frees on scope exit
@@ -170,6 +181,32 @@ extern "C" int psd_sample(const float* logits, int32_t n_rows, int32_t vocab, fl
     if (rc != PSD_OK) return rc;
     PSD_HIP(hipDeviceSynchronize(), err);
     if (where == 0) PSD_HIP(hipMemcpy(tokens_out, t, n_rows * sizeof(int32_t), hipMemcpyDeviceToHost), err);
+    return PSD_OK;
+}
+
+extern "C" int psd_philox_block(uint64_t seed, uint32_t c0, uint32_t n, uint32_t c1, uint32_t c2, uint32_t c3,
+                                int32_t where, uint32_t* out, float* u_out) {
+    char* err = tls_error();
+    if (!out && !u_out) PSD_FAIL(PSD_EINVAL, err, "psd_philox_block: no output");
+    if (n < 1 || n > (1u << 26)) PSD_FAIL(PSD_EINVAL, err, "psd_philox_block: n=%u outside [1, 2^26]", n);
+    if (where != 0 && where != 1) PSD_FAIL(PSD_EINVAL, err, "psd_philox_block: where must be 0 or 1");
+    DevBuf d_out, d_u;
+    uint32_t* o = out;
+    float* u = u_out;
+    const size_t bytes = (size_t)n * 16;
+    if (where == 0) {
+        if (out) { PSD_HIP(hipMalloc(&d_out.p, bytes), err); o = (uint32_t*)d_out.p; }
+        if (u_out) { PSD_HIP(hipMalloc(&d_u.p, bytes), err); u = (float*)d_u.p; }
+    } else if (((uintptr_t)out | (uintptr_t)u_out) & 15) {
+        PSD_FAIL(PSD_EINVAL, err, "psd_philox_block: device outputs must be 16-byte aligned");
+    }
+    philox_block<<<(n + 255) / 256, 256>>>(seed, c0, n, c1, c2, c3, o, u);
+    PSD_HIP(hipGetLastError(), err);
+    PSD_HIP(hipDeviceSynchronize(), err);
+    if (where == 0) {
+        if (out) PSD_HIP(hipMemcpy(out, o, bytes, hipMemcpyDeviceToHost), err);
+        if (u_out) PSD_HIP(hipMemcpy(u_out, u, bytes, hipMemcpyDeviceToHost), err);
+    }
     return PSD_OK;
 }
 

@@ -284,3 +284,40 @@ def test_accept_randomised_shapes_and_row_patterns():
                 assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN or res.margin_race < TIE_RACE, (case, V, k, b)
                 ties += 1
     assert total == 240 and ties <= 4
+
+
+def test_device_philox_equals_the_oracles_on_a_million_counters():
+    """The two independent implementations of Philox4x32-10 (device, CPU oracle) agree word for word, and the device's
+    uniforms are the oracle's, on 10^6 consecutive counters per setting: the addressing of every draw purpose."""
+    n = 1_000_000
+    for seed, c0, c1, c2, c3 in ((7, 0, 512, 0, 0), (0xDEADBEEFCAFEF00D, 0xFFFFFFF0, 4095, 1, 2), (2**63 + 5, 31000, 0, 2, 1)):
+        words, u = psd.philox_block(seed, c0, n, c1, c2, c3)
+        ref = oracle.philox_block(seed, c0, n, c1, c2, c3)     # c0 wraps modulo 2^32 on both sides
+        assert np.array_equal(words, ref)
+        assert np.array_equal(u, (((ref >> 9).astype(np.float64) + 0.5) / 8388608.0).astype(np.float32))
+        assert u.min() > 0.0 and u.max() < 1.0
+    # the oracle's own uniform, as its sampling code asks for it, on a sample of those counters
+    words, u = psd.philox_block(7, 0, 1024, 512, 0, 0)
+    for v in (0, 1, 2, 3, 5, 4094, 4095):
+        assert oracle.uniform(7, v, 512, 0, 0) == float(u[v >> 2, v & 3])
+
+
+def test_accept_batch_workspace_one_byte_short_is_enomem_and_writes_nothing():
+    B, k, V = 3, 4, 4099
+    rng = np.random.default_rng(1)
+    dp = psd.DeviceBuffer.from_numpy(rng.normal(0, 2, (B, k + 1, V)).astype(np.float32))
+    dq = psd.DeviceBuffer.from_numpy(rng.normal(0, 2, (B, k, V)).astype(np.float32))
+    dx = psd.DeviceBuffer.from_numpy(rng.integers(0, V, (B, k)).astype(np.int32))
+    na = psd.DeviceBuffer.from_numpy(np.full(B, -77, np.int32)); nt = psd.DeviceBuffer.from_numpy(np.full(B, -77, np.int32))
+    dv = psd.DeviceBuffer.from_numpy(np.full(B * k, -77.0, np.float32))
+    wsb = psd.accept_workspace_bytes(B, k, V)
+    ws = psd.DeviceBuffer(wsb)
+    with pytest.raises(psd.PsdError) as e:
+        psd.accept_batch(dp, dq, dx, B, k, V, 0.1, 1.0, 1, 0, 1, True, na, nt, dv, ws, wsb - 1, None)
+    assert e.value.code == -3 and "workspace" in str(e.value) and str(wsb) in str(e.value)   # PSD_ENOMEM, message set
+    psd.dev_sync()
+    assert (na.to_numpy(np.int32, B) == -77).all() and (nt.to_numpy(np.int32, B) == -77).all()
+    assert (dv.to_numpy(np.float32, B * k) == -77.0).all()
+    psd.accept_batch(dp, dq, dx, B, k, V, 0.1, 1.0, 1, 0, 1, True, na, nt, dv, ws, wsb, None)   # the exact size is enough
+    psd.dev_sync()
+    assert (na.to_numpy(np.int32, B) >= 0).all()

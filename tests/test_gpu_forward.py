@@ -268,6 +268,37 @@ def test_small_config_target_logits_sampled():
     ctx.close()
 
 
+def test_full_width_layer_at_the_long_context_matches_the_oracle():
+    """One layer of the 8B shape (d 4096, 32 query / 8 KV heads of 128) over a context of 4.2 K tokens, the context of the
+    long-prompt configuration (33 key ranges, the 48-range launch bucket): logits of a 1-token, an 11-token and a
+    17-token pass against the oracle's forward over the same 4229 tokens."""
+    shape = ModelShape(1, 4096, 32, 8, 512, 512)
+    blob = synth.target_weights(shape, 41, synth.DTYPE_BF16, sigma=0.02)
+    n0, widths = 4200, (1, 11, 17)
+    n = n0 + sum(widths)
+    ms = n + 3
+    toks = synth.tokens(43, 0, n, shape.vocab)
+    ctx = _ctx((shape,) * 3, (blob,) * 3, synth.DTYPE_BF16, 500000.0, ms, k1=5, k2=16)
+    pos = 0
+    while pos < n0:
+        w = min(512, n0 - pos)
+        ctx.forward(2, toks[pos:pos + w], pos, want_logits=False)
+        pos += w
+    got = []
+    for w in widths:
+        got.append(ctx.forward(2, toks[pos:pos + w], pos))
+        pos += w
+    got = np.concatenate(got)
+    ctx.close()
+    om = oracle.Model(shape, blob, synth.DTYPE_BF16, 500000.0, ms)
+    om.forward(toks[:n0], 0, want_logits=False)
+    ref = om.forward(toks[n0:], n0)
+    err = float(np.abs(got - ref).max())
+    print(f"full-width layer at {n0} tokens of context: max |logit err| {err:.3e}, logit std {ref.std():.3f}", flush=True)
+    assert ref.std() > 0.05          # the comparison is not between two flat rows
+    assert err <= TOL_BF16
+
+
 def test_forward_argument_errors(tiny_stack):
     cfg, d, q, t, prompt = tiny_stack
     ctx = _ctx((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, 48)

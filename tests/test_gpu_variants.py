@@ -5,11 +5,10 @@ import pytest
 import oracle
 import paper_2510_12966_amd as psd
 from paper_2510_12966_amd import synth
+from replay import TIE_RACE, GreedyReplay, Replay, forced_for
 
 pytestmark = pytest.mark.gpu
 
-TIE_DIV, TIE_COIN, TIE_RACE = 1e-6, 1e-6, 1e-5
-DIV_TOL = 1e-5
 
 
 def _desc(shape, blob, dtype, theta):
@@ -21,40 +20,6 @@ def _ctx(cfg, blobs, max_seq, T_q, T_t, k1, k2, flags=0, temperature=1.0):
     shapes = (cfg.draft, cfg.qualifier, cfg.target)
     d, q, t = (_desc(s, b, cfg.dtype, cfg.rope_theta) for s, b in zip(shapes, blobs))
     return psd.Context(d, q, t, T_q, T_t, k1, k2, max_seq, temperature=temperature, flags=flags)
-
-
-class Replay:
-    """Every sampling / ACCEPT step of a GPU run, with the GPU's own logits, decided again by the oracle."""
-
-    def __init__(self, seed, T_t, temperature=1.0):
-        self.seed, self.T_t, self.temp = seed, T_t, temperature
-        self.events = self.ties = self.kinds = 0
-
-    def __call__(self, kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
-        self.events += 1
-        self.kinds |= 1 << kind
-        if kind == 0:
-            want, gap = oracle.sample_row(lp[0], self.temp, self.seed, pos0)
-            if want != nxt:
-                assert gap < TIE_RACE, ("proposal", pos0, want, nxt, gap)
-                self.ties += 1
-            return
-        if kind == 3:   # assisted stage: token comparison is exact, only the replacement draw can tie
-            res = oracle.accept_assisted(lp, tk, self.temp, self.seed, pos0, 1, bool(bonus))
-            assert n_acc == res.n_accepted, ("assisted", pos0, n_acc, res.n_accepted)
-            if nxt != res.next_token:
-                assert res.margin_race < TIE_RACE
-                self.ties += 1
-            return
-        assert kind == 2
-        res, odiv = oracle.accept(lp, lq, tk, self.T_t, self.temp, self.seed, pos0, 2, bool(bonus))
-        assert np.abs(div - odiv).max(initial=0.0) <= DIV_TOL
-        if n_acc != res.n_accepted:
-            assert res.margin_div < TIE_DIV or res.margin_coin < TIE_COIN, ("accept", pos0, n_acc, res.n_accepted)
-            self.ties += 1
-        elif nxt != res.next_token:
-            assert res.margin_race < TIE_RACE
-            self.ties += 1
 
 
 def _om(shape, blob, cfg, ms):
@@ -69,20 +34,19 @@ def test_two_model_baseline_matches_oracle(tiny_stack, proposer, k, tau, temp, g
     n_new, seed = 48, 11
     ms = len(prompt) + n_new + 8 + 2
     ctx = _ctx(cfg, (d, q, t), ms, 0.3, 0.2, 4, 8, flags=graph, temperature=temp)
-    rp = Replay(seed, tau, temp)
+    forced = forced_for((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, ms, prompt, (proposer, 2))
+    rp = Replay(seed, 0.0, tau, temp, forced, proposer)
     ctx.set_trace(rp)
     out, st = ctx.generate_sd(proposer, k, tau, prompt, n_new, seed)
     ctx.set_trace(None)
     assert rp.events > 0 and rp.kinds == 0b101
+    assert forced.rows >= rp.events and forced.cur[len(prompt):len(prompt) + n_new] == out.tolist()
     shape, blob = ((cfg.draft, d), (cfg.qualifier, q))[proposer]
     ref, ost = oracle.generate_sd(_om(shape, blob, cfg, ms), _om(cfg.target, t, cfg, ms), prompt, n_new, seed, k, tau, temp)
     if rp.ties == 0 and np.array_equal(out, ref):
         for key in ("proposed_t", "accepted_t", "fuzzy_t", "passes_t"):
             assert st[key] == ost[key], key
         assert (st["passes_d"], st["passes_q"])[proposer] == ost["passes_d"]
-    else:
-        first = int(np.argmax(out != ref)) if not np.array_equal(out, ref) else n_new
-        assert first > 0 or rp.ties > 0
     assert st["proposed_t"] == k * st["passes_t"] and 0 < st["accepted_t"] <= st["proposed_t"]
     # the three-model loop afterwards is unaffected (graphs and caches are per pass shape), and a second
     # two-model call repeats the first
@@ -148,20 +112,19 @@ def test_assisted_loop_matches_oracle(tiny_stack, T_t, k1, k2, temp, graph):
     n_new, seed = 48, 4
     ms = len(prompt) + n_new + k2 + 2
     ctx = _ctx(cfg, (d, q, t), ms, 0.0, T_t, k1, k2, flags=graph | psd.FLAG_ASSISTED, temperature=temp)
-    rp = Replay(seed, T_t, temp)
+    forced = forced_for((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, ms, prompt)
+    rp = Replay(seed, 0.0, T_t, temp, forced)
     ctx.set_trace(rp)
     out, st = ctx.generate(prompt, n_new, seed)
     ctx.set_trace(None)
     assert rp.kinds == 0b1101
+    assert forced.rows >= rp.events and forced.cur[len(prompt):len(prompt) + n_new] == out.tolist()
     D, Q, T = _om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms)
     ref, ost = oracle.generate_assisted(D, Q, T, prompt, n_new, seed, k1, k2, T_t, temp)
     if rp.ties == 0 and np.array_equal(out, ref):
         for key in ("proposed_q", "accepted_q", "fuzzy_q", "proposed_t", "accepted_t", "fuzzy_t", "passes_d", "passes_q",
                     "passes_t"):
             assert st[key] == ost[key], key
-    else:
-        first = int(np.argmax(out != ref)) if not np.array_equal(out, ref) else n_new
-        assert first > 0 or rp.ties > 0
     assert st["fuzzy_q"] == 0
     # switching the rule off on the same context gives the fuzzy loop again
     ctx.set_assisted(False)
@@ -224,22 +187,6 @@ def test_row_stats_collected_in_the_loop_match_the_oracle_on_the_same_rows(tiny_
 
 # ---- greedy decoding (temperature -> 0 limit, Section 3.1) --------------------------------------------------
 
-class GreedyReplay:
-    """Every proposal and every stage of a greedy run decided again by the oracle on the GPU's own logits: exact."""
-
-    def __init__(self):
-        self.kinds = 0
-
-    def __call__(self, kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
-        self.kinds |= 1 << kind
-        if kind == 6:
-            assert nxt == int(lp[0].argmax())
-            return
-        assert kind in (4, 5)
-        res = oracle.accept_greedy(lp, tk, bool(bonus))
-        assert (n_acc, nxt) == (res.n_accepted, res.next_token), (kind, pos0, n_acc, nxt, res.n_accepted, res.next_token)
-
-
 @pytest.mark.parametrize("graph", [0, psd.FLAG_GRAPH])
 @pytest.mark.parametrize("k1,k2", [(4, 8), (1, 1), (3, 7), (8, 3)])
 def test_greedy_loop_matches_oracle_stage_by_stage(tiny_stack, k1, k2, graph):
@@ -247,11 +194,13 @@ def test_greedy_loop_matches_oracle_stage_by_stage(tiny_stack, k1, k2, graph):
     n_new = 40
     ms = len(prompt) + n_new + k2 + 2
     ctx = _ctx(cfg, (d, q, t), ms, 0.3, 0.2, k1, k2, flags=graph | psd.FLAG_GREEDY)
-    rp = GreedyReplay()
+    forced = forced_for((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, ms, prompt)
+    rp = GreedyReplay(forced)
     ctx.set_trace(rp)
     out, st = ctx.generate(prompt, n_new, 0)
     ctx.set_trace(None)
     assert rp.kinds == (1 << 4) | (1 << 5) | (1 << 6)
+    assert forced.rows > 0 and forced.cur[len(prompt):len(prompt) + n_new] == out.tolist()
     assert st["fuzzy_q"] == 0 and st["fuzzy_t"] == 0 and st["proposed_t"] == k2 * st["passes_t"]
     ref, ost = oracle.generate_greedy(_om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms),
                                       prompt, n_new, k1, k2)
@@ -316,7 +265,8 @@ def test_randomised_bf16_stacks_variants(case):
     ctx = psd.Context(descs[0], descs[1], descs[2], tau, tau, k1, k2, max_seq, temperature=temp, flags=flags)
     if mode == 0:
         proposer = int(rng.integers(2))
-        rp = Replay(case, tau, temp)
+        forced = forced_for(shapes, blobs, synth.DTYPE_BF16, 10000.0, max_seq, prompt, (proposer, 2))
+        rp = Replay(case, 0.0, tau, temp, forced, proposer)
         ctx.set_trace(rp)
         k = min(k1, k2)                     # the baseline's window is bounded by the context's k2
         out, st = ctx.generate_sd(proposer, k, tau, prompt, n_new, case)
@@ -324,13 +274,15 @@ def test_randomised_bf16_stacks_variants(case):
         assert rp.kinds == 0b101 and rp.ties <= 1
         assert st["proposed_t"] == k * st["passes_t"]
     elif mode == 1:
-        rp = Replay(case, tau, temp)
+        forced = forced_for(shapes, blobs, synth.DTYPE_BF16, 10000.0, max_seq, prompt)
+        rp = Replay(case, 0.0, tau, temp, forced)
         ctx.set_trace(rp)
         out, st = ctx.generate(prompt, n_new, case)
         ctx.set_trace(None)
         assert rp.kinds == 0b1101 and rp.ties <= 1 and st["fuzzy_q"] == 0
     else:
-        rp = GreedyReplay()
+        forced = forced_for(shapes, blobs, synth.DTYPE_BF16, 10000.0, max_seq, prompt)
+        rp = GreedyReplay(forced)
         ctx.set_trace(rp)
         out, st = ctx.generate(prompt, n_new, case)
         ctx.set_trace(None)
@@ -339,6 +291,7 @@ def test_randomised_bf16_stacks_variants(case):
         assert np.array_equal(out, want)
         sd, _ = ctx.generate_sd(int(rng.integers(2)), min(k1, k2), 0.0, prompt, n_new, 0)
         assert np.array_equal(sd, want)
-    print("case", case, "mode", mode, shapes, "k1", k1, "k2", k2, "tau", round(tau, 3), "prompt", n_prompt, st, flush=True)
+    assert forced.rows > 0 and forced.cur[n_prompt:n_prompt + n_new] == out.tolist()
+    print("case", case, "mode", mode, "max |logit err| in the loop", forced.max_err, shapes, "k1", k1, "k2", k2, "tau", round(tau, 3), "prompt", n_prompt, st, flush=True)
     assert out.size == n_new and (out >= 0).all() and (out < vocab).all()
     ctx.close()
