@@ -262,9 +262,13 @@ int psd_accept_batch_noalloc(const float* logits_p, const float* logits_q, const
  *      satisfied, so the expiry handling below can be exercised without a stuck kernel
  * Both sweeps give bit-identical results.  When a wait expires, psd_accept, psd_generate and psd_generate_sd
  * switch the process to path 1 and run the stage again; psd_get_accept_path tells which path is in force.
- * Not thread-safe against running calls.  Returns PSD_EINVAL for other values. */
+ * The switch may be flipped while other threads run stages (they pick it up at their next stage).  Returns PSD_EINVAL
+ * for other values. */
 int psd_set_accept_path(int32_t path);
 int psd_get_accept_path(void);
+/* How many times, in this process, a bounded wait expired and the library ran a stage again on path 1: normally 0;
+ * anything else explains an ACCEPT slowdown (the two-launch sweep reads the logits twice). */
+int64_t psd_get_accept_expiries(void);
 
 /* Fresh sample from softmax(logits / temperature) by the exponential race (how the
  * draft proposes, Figure 1): rows [n_rows][vocab], row r is decided for position position0 + r.

@@ -221,6 +221,12 @@ def get_accept_path():
     return lib().psd_get_accept_path()
 
 
+def get_accept_expiries():
+    f = lib().psd_get_accept_expiries
+    f.restype = C.c_int64
+    return int(f())
+
+
 def accept_workspace_bytes(n_trials, k, vocab):
     return lib().psd_accept_workspace_bytes(n_trials, k, vocab)
 

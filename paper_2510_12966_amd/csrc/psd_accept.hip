@@ -43,10 +43,16 @@ constexpr float kBig = 1e30f;
 constexpr unsigned long long kWaitTicks = 5000000ull;  // 50 ms of the 100 MHz wall clock
 constexpr uint32_t kUnwritten = 0xffffffffu;           // a NaN pattern no maximum can have
 
-static int g_accept_path = 0;   // 0 automatic, 1 two-launch sweep, 2 one-launch sweep where it is allowed
-static unsigned long long g_wait_ticks = kWaitTicks;  // bound of the wait between workgroups (0: test aid)
+// Process-wide switches, read once per launch sequence; atomics, so that contexts on different threads may read and
+// flip them concurrently (a flip between two stages is harmless: both sweeps give the same bits).
+static std::atomic<int> g_accept_path{0};   // 0 automatic, 1 two-launch sweep, 2 one-launch sweep where it is allowed
+static std::atomic<unsigned long long> g_wait_ticks{kWaitTicks};  // bound of the wait between workgroups (0: test aid)
+static std::atomic<long long> g_wait_expiries{0};   // how often a bounded wait ran out and a stage was run again
 
-void accept_wait_expired() { g_accept_path = 1; }
+void accept_wait_expired() {
+    g_accept_path.store(1);
+    g_wait_expiries.fetch_add(1);
+}
 
 // base-2 maximum of a chunk and its sum of 2^(z - m), for the verifier row (p) and the proposer row (q);
 // each half is published with one 64-bit store and is valid once its m is not the unwritten pattern
@@ -579,7 +585,7 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     if ((long long)pairs * nsw > 0x7fffffffLL) PSD_FAIL(PSD_EINVAL, errbuf, "accept: n_trials * k * chunks overflows the grid");
     AcceptWs w;
     carve(&w, workspace, n_trials, k, vocab);
-    AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw, g_wait_ticks};
+    AcceptShape s{logits_p, logits_q, tokens, k, vocab, nch, 1.0f / temperature, kSweepWaves * nsw, g_wait_ticks.load()};
     const size_t n_parts = (size_t)pairs * nsw * kSweepWaves;
     if (assisted) {   // 1: assisted stage, 2: greedy stage
         const int greedy = assisted == 2, rows = greedy ? k + 1 : k;
@@ -597,7 +603,7 @@ int accept_launch(const float* logits_p, const float* logits_q, const int32_t* t
     if (pairs > 0) {
         const int n_items = pairs * nsw;
         const bool vec = (vocab & 3) == 0;  // rows are then 16-byte aligned and hold whole quads
-        const bool one_launch = g_accept_path != 1 && kSweepWaves * nsw <= kSweepMaxSlots;
+        const bool one_launch = g_accept_path.load() != 1 && kSweepWaves * nsw <= kSweepMaxSlots;
         if (one_launch) {
             if (vec) accept_sweep<SWEEP_ONE_LAUNCH, true><<<n_items, kAccThreads, 0, stream>>>(s, w);
             else accept_sweep<SWEEP_ONE_LAUNCH, false><<<n_items, kAccThreads, 0, stream>>>(s, w);
@@ -776,12 +782,14 @@ using namespace psd;
 
 extern "C" int psd_set_accept_path(int32_t path) {
     if (path < 0 || path > 3) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_accept_path: path=%d", path);
-    g_accept_path = path == 3 ? 0 : path;
-    g_wait_ticks = path == 3 ? 0ull : kWaitTicks;
+    g_accept_path.store(path == 3 ? 0 : path);
+    g_wait_ticks.store(path == 3 ? 0ull : kWaitTicks);
     return PSD_OK;
 }
 
-extern "C" int psd_get_accept_path(void) { return g_accept_path; }
+extern "C" int psd_get_accept_path(void) { return g_accept_path.load(); }
+
+extern "C" int64_t psd_get_accept_expiries(void) { return g_wait_expiries.load(); }
 
 extern "C" size_t psd_accept_workspace_bytes(int32_t n_trials, int32_t k, int32_t vocab) {
     if (n_trials < 1 || k < 0 || vocab < 1) return 0;

@@ -149,6 +149,22 @@ static int upload(psd_ctx* c, void* dst, const void* src, size_t bytes) {
     return PSD_OK;
 }
 
+// KV pages for positions < upto of model M (pages wholly beyond `keep` are returned); the page-table entries that
+// changed travel in stream order through the pinned ring, so the host does not wait for the device here
+static int map_pages(psd_ctx* c, Model& M, int keep, int upto) {
+    int first = 0, n = 0;
+    int rc = model_map_pages(M, keep, upto, &first, &n, c->err);
+    if (rc != PSD_OK) return rc;
+    constexpr int kPerSlot = kStageSlotBytes / (int)sizeof(int32_t);
+    int32_t tmp[kPerSlot];
+    for (int done = 0; done < n; done += kPerSlot) {
+        const int cnt = std::min(kPerSlot, n - done);
+        for (int i = 0; i < cnt; ++i) tmp[i] = std::max(M.h_page_table[first + done + i], 0);   // unmapped: page 0, never read
+        if ((rc = upload(c, M.page_table + first + done, tmp, (size_t)cnt * sizeof(int32_t))) != PSD_OK) return rc;
+    }
+    return PSD_OK;
+}
+
 // launch class of a pass of w tokens: the smallest narrow class that holds it, or (prompt ingestion only) the next
 // multiple of 128
 static int wclass(int w) { return w <= kMaxW ? kNarrowClasses[narrow_class_index(w)] : (w + 127) / 128 * 128; }
@@ -228,7 +244,7 @@ static int prefill(psd_ctx* c, int mi, const int32_t* seq, int upto) {
     Model& M = c->M[mi];
     while (M.len < upto) {
         const int w = std::min(M.ingest_max, upto - M.len);
-        int rc = model_map_pages(M, M.len, M.len + w, c->stream, c->err);
+        int rc = map_pages(c, M, M.len, M.len + w);
         if (rc != PSD_OK) return rc;
         PassDesc d;
         fill_desc(d, seq, M.len, M.len + w, 0, 0, 0);
@@ -261,7 +277,7 @@ static int prefill_all(psd_ctx* c, const int32_t* seq, int upto, unsigned models
                 const int w = std::min(M.ingest_max, upto - M.len);
                 // the model's descriptor and page table are free again once its previous pass is done
                 if (used[mi]) PSD_HIP(hipStreamWaitEvent(c->stream, c->aux_done[mi], 0), c->err);
-                int rc = model_map_pages(M, M.len, M.len + w, c->stream, c->err);
+                int rc = map_pages(c, M, M.len, M.len + w);
                 if (rc != PSD_OK) return rc;
                 PassDesc d;
                 fill_desc(d, seq, M.len, M.len + w, 0, 0, 0);
@@ -514,7 +530,7 @@ extern "C" int psd_forward(psd_ctx* c, int32_t which, const int32_t* tokens, int
     int rc = check_tokens(c, tokens, w);
     if (rc != PSD_OK) return rc;
     PSD_HIP(hipSetDevice(c->device), c->err);
-    if ((rc = model_map_pages(M, pos0, pos0 + w, c->stream, c->err)) != PSD_OK) return rc;
+    if ((rc = map_pages(c, M, pos0, pos0 + w)) != PSD_OK) return rc;
     PassDesc d;
     fill_desc(d, tokens, 0, w, 0, logits_out ? w : 0, 0);
     d.pos0 = pos0;
@@ -560,8 +576,8 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             const int hq = L - Q.len;  // host-known tokens the qualifier still has to ingest
             if (L - D.len < 1 || L - D.len > 3 || hq < 1 || hq > 2)
                 PSD_FAIL(PSD_EINVAL, c->err, "internal: cache lengths out of step (L=%d D=%d Q=%d)", L, D.len, Q.len);
-            if ((rc = model_map_pages(D, D.len, L + m, c->stream, c->err)) != PSD_OK) return rc;
-            if ((rc = model_map_pages(Q, Q.len, L + m, c->stream, c->err)) != PSD_OK) return rc;
+            if ((rc = map_pages(c, D, D.len, L + m)) != PSD_OK) return rc;
+            if ((rc = map_pages(c, Q, Q.len, L + m)) != PSD_OK) return rc;
             PassDesc dd, qd;
             fill_desc(dd, seq.data(), D.len, L, 0, 1, 0);
             fill_desc(qd, seq.data(), Q.len, L, m, m + 1, nbuf);
@@ -606,7 +622,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         // target verifies the window
         const int wT = C + k2 - T.len;
         if (wT != k2 + 1) PSD_FAIL(PSD_EINVAL, c->err, "internal: target cache out of step (C=%d T=%d)", C, T.len);
-        if ((rc = model_map_pages(T, T.len, C + k2, c->stream, c->err)) != PSD_OK) return rc;
+        if ((rc = map_pages(c, T, T.len, C + k2)) != PSD_OK) return rc;
         PassDesc td;
         fill_desc(td, seq.data(), T.len, C + k2, 0, k2 + 1, 0);
         if ((rc = upload(c, T.desc, &td, desc_bytes(td))) != PSD_OK) return rc;
@@ -720,8 +736,8 @@ extern "C" int psd_generate_sd(psd_ctx* c, int32_t proposer, int32_t k, float ta
         const int hp = C - P.len, ht = C - T.len;
         if (hp < 1 || hp > 2 || ht != 1)
             PSD_FAIL(PSD_EINVAL, c->err, "internal: cache lengths out of step (C=%d P=%d T=%d)", C, P.len, T.len);
-        if ((rc = model_map_pages(P, P.len, C + k, c->stream, c->err)) != PSD_OK) return rc;
-        if ((rc = model_map_pages(T, T.len, C + k, c->stream, c->err)) != PSD_OK) return rc;
+        if ((rc = map_pages(c, P, P.len, C + k)) != PSD_OK) return rc;
+        if ((rc = map_pages(c, T, T.len, C + k)) != PSD_OK) return rc;
         PassDesc pd, td;
         fill_desc(pd, seq.data(), P.len, C, 0, 1, 0);
         fill_desc(td, seq.data(), T.len, C, k, k + 1, 0);
@@ -796,7 +812,7 @@ extern "C" int psd_generate_plain(psd_ctx* c, int32_t which, const int32_t* prom
     PSD_HIP(hipEventRecord(c->ev[1], c->stream), c->err);
     for (int i = 0; i < n_new; ++i) {
         const int L = n_prompt + i;
-        if ((rc = model_map_pages(M, M.len, L, c->stream, c->err)) != PSD_OK) return rc;
+        if ((rc = map_pages(c, M, M.len, L)) != PSD_OK) return rc;
         PassDesc d;
         fill_desc(d, seq.data(), M.len, L, 0, 1, 0);
         if ((rc = upload(c, M.desc, &d, desc_bytes(d))) != PSD_OK) return rc;

@@ -139,8 +139,10 @@ size_t model_pool_bytes(const psd_model_desc& m, int max_seq);
 int model_init(Model& M, const psd_model_desc& desc, const char* tag, int max_seq, bool scramble_pages, Pool& pool,
                hipStream_t stream, char* err);
 
-// Makes sure KV pages exist for positions < upto and frees pages wholly beyond `keep`; uploads the table if it changed.
-int model_map_pages(Model& M, int keep, int upto, hipStream_t stream, char* err);
+// Makes sure KV pages exist for positions < upto and frees pages wholly beyond `keep`, in the host mirror of the page
+// table; reports which entries changed ([*first_changed, +*n_changed), none: 0 entries) so that the caller can upload
+// just those (device entries of unmapped blocks are never read: attention stops at the pass's last position).
+int model_map_pages(Model& M, int keep, int upto, int* first_changed, int* n_changed, char* err);
 
 // Enqueues one pass described by *M.desc (already on the device).  wmax: one of kNarrowClasses = widest pass the launch must cover;
 // 128, 256, 384 or 512 (bf16 models, logits == nullptr): prompt ingestion.

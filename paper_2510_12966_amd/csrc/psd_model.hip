@@ -609,6 +609,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             if constexpr (LB) {
                 if (staged_ready) return;
                 staged_ready = true;
+                // Counts on the loads issued since the staging loads: exactly the U * RT weight loads of the first full batch,
+                // all unconditional (a predicated or split weight load would make the count, and with it this wait, wrong:
+                // then wait for vmcnt(0) instead).  The narrow-against-wide bit-exactness tests guard this.
+                static_assert(!LB || U * RT <= 63, "the vmcnt field holds at most 63");
                 if (full_batch) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(U * RT < 63 ? U * RT : 63) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
@@ -1438,31 +1442,27 @@ int model_init(Model& M, const psd_model_desc& m, const char* tag, int max_seq, 
     return PSD_OK;
 }
 
-int model_map_pages(Model& M, int keep, int upto, hipStream_t stream, char* err) {
+int model_map_pages(Model& M, int keep, int upto, int* first_changed, int* n_changed, char* err) {
+    *first_changed = 0;
+    *n_changed = 0;
     if (upto > M.max_seq) PSD_FAIL(PSD_ESHAPE, err, "%s: position %d exceeds max_seq %d", M.tag, upto, M.max_seq);
     const int need = (upto + kPage - 1) / kPage, keep_pages = (keep + kPage - 1) / kPage;
-    bool changed = false;
+    int lo = M.n_pages, hi = 0;
     // rollback: blocks wholly beyond the kept prefix go back to the free list (unless needed again right away)
     for (int b = M.pages_mapped - 1; b >= std::max(keep_pages, need); --b) {
         M.free_pages.push_back(M.h_page_table[b]);
         M.h_page_table[b] = -1;
         M.pages_mapped = b;
-        changed = true;
+        lo = std::min(lo, b); hi = std::max(hi, b + 1);
     }
     for (int b = M.pages_mapped; b < need; ++b) {
         if (M.free_pages.empty()) PSD_FAIL(PSD_ENOMEM, err, "%s: out of KV pages", M.tag);
         M.h_page_table[b] = M.free_pages.back();
         M.free_pages.pop_back();
         M.pages_mapped = b + 1;
-        changed = true;
+        lo = std::min(lo, b); hi = std::max(hi, b + 1);
     }
-    if (changed) {
-        // unmapped blocks point at page 0 on the device: never read (attention stops at the pass's last position)
-        std::vector<int32_t> tmp(M.h_page_table);
-        for (auto& v : tmp) if (v < 0) v = 0;
-        PSD_HIP(hipMemcpyAsync(M.page_table, tmp.data(), tmp.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream), err);
-        PSD_HIP(hipStreamSynchronize(stream), err);  // tmp is pageable host memory on this stack frame
-    }
+    if (hi > lo) { *first_changed = lo; *n_changed = hi - lo; }
     return PSD_OK;
 }
 
@@ -1511,7 +1511,7 @@ static int forward_f32(Model& M, int wmax, float* logits, Launch& L) {
         L.begin("rope_kv", (double)wmax * M.nqkv * 4);
         rope_kv<float><<<dim3(wmax, H + 2 * KV), hd / 2, 0, stream>>>(M.qkv, M.desc, M.rope, (float*)M.kv, M.page_table, l, M.L, H, KV, hd, M.nqkv);
         L.end();
-        L.begin("attn", 0);
+        L.begin("attn", (double)std::min(M.max_seq, M.len + wmax) * KV * hd * 2 * 4 + (double)wmax * H * hd * 4 * 2);
         attn_partial<float><<<dim3(H, M.nsplit_max), 256, lds, stream>>>(M.qkv, M.desc, (const float*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, hd, M.nqkv);
         L.end();
         L.begin("attn_combine", act);
@@ -1636,6 +1636,9 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     // narrow passes of small models: the o projection merges the attention split partials itself (one launch less).
     // Every workgroup of it repeats the merge, so past a dozen key ranges the separate merge kernel is cheaper
     // (draft o projection at 36 ranges: 19.8 us against 4.2 + 6.5 us); both routes give the same bits.
+    // algorithmic bytes of one layer's attention: K and V of every key the pass can see, as bf16 (the cache holds a hi and a
+    // lo plane per value, so the kernels move twice that), plus the queries in and the outputs back
+    const double kv_bytes = (double)std::min(M.max_seq, M.len + wmax) * KV * hd * 2 * 2 + (double)wmax * H * hd * 4 * 2;
     const bool fold_merge = wmax <= 4 && d <= 2048 && d / 16 <= 256 && H * hd == d && nsplit <= kFoldSplits;
     GemmArgs base{};
     base.ss_in = ss; base.ss_tiles = d / 16; base.inv_d = inv_d; base.eps = M.eps;
@@ -1648,7 +1651,7 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         a.Wt = (const u32x4*)w.wqkv; a.XB = (const u32x4*)xb; a.N = M.nqkv; a.KS = d / 32;
         a.Y = M.qkv; a.ldy = M.nqkv; a.layer = l;
         launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
-        L.begin("attn", 0);
+        L.begin("attn", kv_bytes);
         const dim3 agrid(KV, nsplit, qt_max);
         if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
         else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);

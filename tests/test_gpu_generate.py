@@ -211,13 +211,13 @@ def test_paper_shapes_sampled_parity():
     print("paper stack:", st, "ties", rp.ties, "max div err", rp.max_div_err, flush=True)
     assert rp.ties <= 1 and rp.events >= 10
     # thresholds inside this stack's divergence range, so that rejections and resampling run at full size too
-    ctx.set_decoding(0.1, 0.12, cfg.k1, cfg.k2)
-    rp = Replay(5, 0.1, 0.12)
+    ctx.set_decoding(0.205, 0.266, cfg.k1, cfg.k2)   # the medians of the two stages' divergences on this stack
+    rp = Replay(5, 0.205, 0.266)
     ctx.set_trace(rp)
     out, st = ctx.generate(prompt[:n_prompt], n_new, 5)
     ctx.set_trace(None)
     print("paper stack, tighter thresholds:", st, "ties", rp.ties, flush=True)
-    assert rp.ties <= 1
+    assert rp.ties <= 1 and 0 < st["fuzzy_q"] < st["proposed_q"] and 0 < st["fuzzy_t"] < st["proposed_t"]
     toks = prompt[:12]
     shapes, blobs = (cfg.draft, cfg.qualifier, cfg.target), (d, q, t)
     for which in range(3):
