@@ -41,6 +41,21 @@ class Stats(C.Structure):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
+class Adapt(C.Structure):
+    """Ranges of the adaptive controller (see psd_oracle.c)."""
+    _fields_ = [("k2_min", C.c_int32), ("k2_max", C.c_int32), ("k1_max", C.c_int32), ("steps", C.c_int32),
+                ("period", C.c_int32), ("T_q_min", C.c_float), ("T_q_max", C.c_float), ("T_t_min", C.c_float),
+                ("T_t_max", C.c_float)]
+
+
+class AdaptState(C.Structure):
+    _fields_ = [("k1", C.c_int32), ("k2", C.c_int32), ("s_q", C.c_int32), ("s_t", C.c_int32), ("since", C.c_int32),
+                ("p_q", C.c_int64), ("a_q", C.c_int64), ("p_t", C.c_int64), ("a_t", C.c_int64)]
+
+    def params(self):
+        return (self.k1, self.k2, self.s_q, self.s_t)
+
+
 ROW_TRACE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_float), C.c_int)
 
 _LIB = None
@@ -91,6 +106,13 @@ def lib():
         L.orc_generate_plain.restype = C.c_int
         L.orc_generate_plain.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_int, C.c_int, C.c_uint64,
                                          C.c_void_p]
+        L.orc_adapt_threshold.restype = C.c_double
+        L.orc_adapt_threshold.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
+        L.orc_adapt_init.argtypes = [C.POINTER(Adapt), C.c_double, C.c_double, C.c_int, C.POINTER(AdaptState)]
+        L.orc_adapt_step.argtypes = [C.POINTER(Adapt), C.POINTER(AdaptState), C.c_int, C.c_int64, C.c_int64]
+        L.orc_generate_adaptive.restype = C.c_int
+        L.orc_generate_adaptive.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params), C.POINTER(Adapt), C.c_void_p,
+                                            C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.POINTER(Stats), C.c_void_p, C.c_int]
         L.orc_philox_block.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
         L.orc_residual.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         L.orc_set_row_trace.argtypes = [ROW_TRACE_FN, C.c_void_p]
@@ -312,3 +334,32 @@ def generate_plain(M, prompt, n_new, seed, temperature=1.0):
     if rc != 0:
         raise ValueError(f"orc_generate_plain failed: {rc}")
     return out
+
+
+def adapt_threshold(lo, hi, s, steps):
+    return lib().orc_adapt_threshold(lo, hi, s, steps)
+
+
+def adapt_init(ad, T_q, T_t, k2):
+    st = AdaptState()
+    lib().orc_adapt_init(C.byref(ad), T_q, T_t, k2, C.byref(st))
+    return st
+
+
+def adapt_step(ad, st, n_t, p_q, a_q):
+    lib().orc_adapt_step(C.byref(ad), C.byref(st), n_t, p_q, a_q)
+    return st
+
+
+def generate_adaptive(D, Q, T, prompt, n_new, seed, k2, T_q, T_t, ad, temperature=1.0):
+    """The loop under the adaptive controller; returns (tokens, stats, log [iterations, 4] of (k1, k2, s_q, s_t))."""
+    prm = Params(T_q, T_t, temperature, 1, k2)
+    pr = np.ascontiguousarray(prompt, dtype=np.int32)
+    out = np.empty(n_new, dtype=np.int32)
+    st = Stats()
+    log = np.full((max(n_new, 1), 4), -1, dtype=np.int32)
+    rc = lib().orc_generate_adaptive(D.h, Q.h, T.h, C.byref(prm), C.byref(ad), pr.ctypes.data, pr.size, n_new, seed,
+                                     out.ctypes.data, C.byref(st), log.ctypes.data, log.shape[0])
+    if rc != 0:
+        raise ValueError(f"orc_generate_adaptive failed: {rc}")
+    return out, st.as_dict(), log[log[:, 0] >= 0]

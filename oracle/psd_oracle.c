@@ -509,6 +509,80 @@ static int run_model(orc_model* m, int which, const int32_t* seq, int* len, int 
     return rc;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Adaptive controller for (tau_Q, tau_T, l_D, l_Q)                          */
+/* The paper only names it (Conclusion and Future Work: controllers that     */
+/* adjust divergence thresholds and speculative lengths from the decoding    */
+/* context); the rule below is this build's reading, assembled from what the */
+/* paper observes: full acceptance invites a longer window and rejection     */
+/* cascades a shorter one (Section 4.4), l_D about half of l_Q (Section 4.4), */
+/* tau_Q <= tau_T (Section 4.2), thresholds only as loose as acceptance      */
+/* needs (the stability / peak-speed trade-off of Section 4.2).  Integer     */
+/* arithmetic throughout; thresholds sit on S + 1 positions of a band.       */
+/*                                                                           */
+/* After every target pass with window k2 and n accepted tokens:             */
+/*   n == k2   -> k2 + 1 (at most k2_max);  2 n < k2 -> k2 - 1 (at least     */
+/*   k2_min);  k1 = clamp((k2 + 1) / 2, 1, k1_max).                          */
+/* Every `period` target passes, per stage, from the tokens proposed (p) and */
+/* accepted (a) since the last adjustment:                                   */
+/*   8 a >= 7 p -> one position tighter;  2 a < p -> one position looser;    */
+/* then tau_Q is lowered position by position while it exceeds tau_T.        */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t k2_min, k2_max, k1_max;
+    int32_t steps, period; /* S >= 1 positions above the band's minimum; period >= 1 */
+    float T_q_min, T_q_max, T_t_min, T_t_max;
+} orc_adapt;
+
+typedef struct {
+    int32_t k1, k2, s_q, s_t;        /* lengths and threshold positions in force */
+    int32_t since;                   /* target passes since the last threshold adjustment */
+    int64_t p_q, a_q, p_t, a_t;      /* proposed / accepted per stage since then */
+} orc_adapt_state;
+
+/* threshold at position s of the band [lo, hi]: computed in double, rounded once to float (the type thresholds
+ * have at the library's boundary) */
+double orc_adapt_threshold(float lo, float hi, int s, int steps) {
+    return (double)(float)((double)lo + ((double)hi - (double)lo) * (double)s / (double)steps);
+}
+
+static int iclamp(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+static int nearest_position(float lo, float hi, double T, int steps) {
+    if (!(hi > lo)) return 0;
+    double x = (T - (double)lo) / ((double)hi - (double)lo) * steps;
+    return iclamp((int)floor(x + 0.5), 0, steps);
+}
+
+void orc_adapt_init(const orc_adapt* ad, double T_q, double T_t, int k2, orc_adapt_state* st) {
+    memset(st, 0, sizeof(*st));
+    st->k2 = iclamp(k2, ad->k2_min, ad->k2_max);
+    st->k1 = iclamp((st->k2 + 1) / 2, 1, ad->k1_max);
+    st->s_q = nearest_position(ad->T_q_min, ad->T_q_max, T_q, ad->steps);
+    st->s_t = nearest_position(ad->T_t_min, ad->T_t_max, T_t, ad->steps);
+}
+
+/* one target pass is over: the window was st->k2 long, n_t of it were accepted; stage 1 proposed p_q and accepted
+ * a_q draft tokens while the window was filled */
+void orc_adapt_step(const orc_adapt* ad, orc_adapt_state* st, int n_t, int64_t p_q, int64_t a_q) {
+    int k2 = st->k2;
+    st->p_q += p_q; st->a_q += a_q; st->p_t += k2; st->a_t += n_t;
+    if (n_t == k2) st->k2 = k2 + 1 > ad->k2_max ? ad->k2_max : k2 + 1;
+    else if (2 * n_t < k2) st->k2 = k2 - 1 < ad->k2_min ? ad->k2_min : k2 - 1;
+    st->k1 = iclamp((st->k2 + 1) / 2, 1, ad->k1_max);
+    if (++st->since < ad->period) return;
+    if (st->p_q > 0) {
+        if (8 * st->a_q >= 7 * st->p_q) st->s_q = st->s_q > 0 ? st->s_q - 1 : 0;
+        else if (2 * st->a_q < st->p_q) st->s_q = st->s_q < ad->steps ? st->s_q + 1 : ad->steps;
+    }
+    if (8 * st->a_t >= 7 * st->p_t) st->s_t = st->s_t > 0 ? st->s_t - 1 : 0;
+    else if (2 * st->a_t < st->p_t) st->s_t = st->s_t < ad->steps ? st->s_t + 1 : ad->steps;
+    while (st->s_q > 0 && orc_adapt_threshold(ad->T_q_min, ad->T_q_max, st->s_q, ad->steps) >
+                              orc_adapt_threshold(ad->T_t_min, ad->T_t_max, st->s_t, ad->steps))
+        st->s_q--;
+    st->since = 0; st->p_q = st->a_q = st->p_t = st->a_t = 0;
+}
+
 /* Generates exactly n_new tokens after the prompt.  seq = committed tokens
  * followed by the window of qualified tokens; every model holds KV rows for a
  * prefix of seq and, before each pass, ingests whatever it has not cached.
@@ -527,16 +601,29 @@ static int run_model(orc_model* m, int which, const int32_t* seq, int* len, int 
  */
 static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, int assisted,
                          const int32_t* prompt, int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens,
-                         orc_stats* st) {
+                         orc_stats* st, const orc_adapt* ad, int32_t* adapt_log, int adapt_log_cap) {
     int V = T->vocab, k1 = prm->k1, k2 = prm->k2;
+    double T_q = prm->T_q, T_t = prm->T_t;
+    orc_adapt_state as;
+    int k1_top = k1, k2_top = k2, n_logged = 0;   /* largest lengths the run can reach: buffer sizes */
+    if (ad) {
+        if (ad->k2_min < 1 || ad->k2_max < ad->k2_min || ad->k1_max < 1 || ad->steps < 1 || ad->period < 1 ||
+            !(ad->T_q_max >= ad->T_q_min) || !(ad->T_t_max >= ad->T_t_min) || !(ad->T_q_min >= 0) || !(ad->T_t_min >= 0))
+            return -1;
+        orc_adapt_init(ad, T_q, T_t, k2, &as);
+        k1 = as.k1; k2 = as.k2;
+        T_q = orc_adapt_threshold(ad->T_q_min, ad->T_q_max, as.s_q, ad->steps);
+        T_t = orc_adapt_threshold(ad->T_t_min, ad->T_t_max, as.s_t, ad->steps);
+        k1_top = ad->k1_max; k2_top = ad->k2_max;
+    }
     if (D->vocab != V || Q->vocab != V || k1 < 1 || k2 < 1 || n_prompt < 1 || n_new < 0) return -1;
-    int cap = n_prompt + n_new + k2 + 2;
+    int cap = n_prompt + n_new + k2_top + 2;
     if (cap > D->max_seq || cap > Q->max_seq || cap > T->max_seq) return -3;
     int32_t* seq = (int32_t*)malloc((size_t)cap * sizeof(int32_t));
-    float* dl = (float*)malloc((size_t)k1 * V * sizeof(float));        /* draft rows of this round */
-    float* ql = (float*)malloc((size_t)(k1 + 1) * V * sizeof(float));  /* qualifier rows of this round */
-    float* qrows = (float*)malloc((size_t)(k2 + 1) * V * sizeof(float)); /* qualifier row per window token */
-    float* tl = (float*)malloc((size_t)(k2 + 1) * V * sizeof(float));
+    float* dl = (float*)malloc((size_t)k1_top * V * sizeof(float));        /* draft rows of this round */
+    float* ql = (float*)malloc((size_t)(k1_top + 1) * V * sizeof(float));  /* qualifier rows of this round */
+    float* qrows = (float*)malloc((size_t)(k2_top + 1) * V * sizeof(float)); /* qualifier row per window token */
+    float* tl = (float*)malloc((size_t)(k2_top + 1) * V * sizeof(float));
     memcpy(seq, prompt, (size_t)n_prompt * sizeof(int32_t));
     memset(st, 0, sizeof(*st));
     int C = n_prompt, lenD = 0, lenQ = 0, lenT = 0, rc = 0;
@@ -549,6 +636,11 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
     orc_accept_result ar;
     while (rc == 0 && C - n_prompt < n_new) {
         int nbuf = 0;
+        int64_t pq0 = st->proposed_q, aq0 = st->accepted_q;
+        if (ad && adapt_log && n_logged < adapt_log_cap) {   /* parameters this outer iteration runs with */
+            int32_t* e = adapt_log + 4 * (size_t)n_logged++;
+            e[0] = k1; e[1] = k2; e[2] = as.s_q; e[3] = as.s_t;
+        }
         while (nbuf < k2) {
             int m = imin(k1, k2 - nbuf), L = C + nbuf;
             for (int i = 0; i < m; ++i) {
@@ -566,7 +658,7 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
             else if (assisted)
                 orc_accept_assisted(ql, seq + L, m, V, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar);
             else
-                orc_accept(ql, dl, seq + L, m, V, prm->T_q, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar, NULL);
+                orc_accept(ql, dl, seq + L, m, V, T_q, prm->temperature, seed, (uint32_t)L, 1u, bonus, &ar, NULL);
             int n = ar.n_accepted, has_y = ar.next_token >= 0;
             memcpy(qrows + (size_t)nbuf * V, ql, (size_t)(n + has_y) * V * sizeof(float));
             if (has_y) seq[L + n] = ar.next_token;
@@ -580,12 +672,18 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
         if (assisted == 2)
             orc_accept_greedy(tl, seq + C, k2, V, 1, &ar);
         else
-            orc_accept(tl, qrows, seq + C, k2, V, prm->T_t, prm->temperature, seed, (uint32_t)C, 2u, 1, &ar, NULL);
+            orc_accept(tl, qrows, seq + C, k2, V, T_t, prm->temperature, seed, (uint32_t)C, 2u, 1, &ar, NULL);
         int n = ar.n_accepted;
         seq[C + n] = ar.next_token;
         lenT = imin(lenT, C + n); lenQ = imin(lenQ, C + n); lenD = imin(lenD, C + n);
         C += n + 1;
         st->proposed_t += k2; st->accepted_t += n; st->fuzzy_t += ar.n_fuzzy;
+        if (ad) {   /* the controller sees this iteration's counts and sets the next iteration's parameters */
+            orc_adapt_step(ad, &as, n, st->proposed_q - pq0, st->accepted_q - aq0);
+            k1 = as.k1; k2 = as.k2;
+            T_q = orc_adapt_threshold(ad->T_q_min, ad->T_q_max, as.s_q, ad->steps);
+            T_t = orc_adapt_threshold(ad->T_t_min, ad->T_t_max, as.s_t, ad->steps);
+        }
     }
     if (rc == 0) memcpy(out_tokens, seq + n_prompt, (size_t)n_new * sizeof(int32_t));
     free(seq); free(dl); free(ql); free(qrows); free(tl);
@@ -594,7 +692,17 @@ static int generate_loop(orc_model* D, orc_model* Q, orc_model* T, const orc_par
 
 int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
                  int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
-    return generate_loop(D, Q, T, prm, 0, prompt, n_prompt, n_new, seed, out_tokens, st);
+    return generate_loop(D, Q, T, prm, 0, prompt, n_prompt, n_new, seed, out_tokens, st, NULL, NULL, 0);
+}
+
+/* The loop under the adaptive controller: prm gives the starting thresholds and window (brought into the
+ * controller's ranges), ad the ranges.  adapt_log (optional, [adapt_log_cap][4] ints) receives (k1, k2, position
+ * of tau_Q, position of tau_T) of every outer iteration; *n_logged how many were written. */
+int orc_generate_adaptive(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const orc_adapt* ad,
+                          const int32_t* prompt, int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens,
+                          orc_stats* st, int32_t* adapt_log, int adapt_log_cap) {
+    if (!ad) return -1;
+    return generate_loop(D, Q, T, prm, 0, prompt, n_prompt, n_new, seed, out_tokens, st, ad, adapt_log, adapt_log_cap);
 }
 
 /* The assisted variant of the loop (Section 3.4): the qualifier stage matches tokens
@@ -602,7 +710,7 @@ int orc_generate(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm
  * target stage is unchanged. */
 int orc_generate_assisted(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
                           int n_prompt, int n_new, uint64_t seed, int32_t* out_tokens, orc_stats* st) {
-    return generate_loop(D, Q, T, prm, 1, prompt, n_prompt, n_new, seed, out_tokens, st);
+    return generate_loop(D, Q, T, prm, 1, prompt, n_prompt, n_new, seed, out_tokens, st, NULL, NULL, 0);
 }
 
 /* Greedy decoding through the loop (temperature -> 0): proposals and replacements are top predictions,
@@ -610,7 +718,7 @@ int orc_generate_assisted(orc_model* D, orc_model* Q, orc_model* T, const orc_pa
  * target's own greedy continuation whatever draft and qualifier are. */
 int orc_generate_greedy(orc_model* D, orc_model* Q, orc_model* T, const orc_params* prm, const int32_t* prompt,
                         int n_prompt, int n_new, int32_t* out_tokens, orc_stats* st) {
-    return generate_loop(D, Q, T, prm, 2, prompt, n_prompt, n_new, 0, out_tokens, st);
+    return generate_loop(D, Q, T, prm, 2, prompt, n_prompt, n_new, 0, out_tokens, st, NULL, NULL, 0);
 }
 
 /* Two-model speculative decoding, the comparison the speed-up is quoted against
