@@ -179,6 +179,31 @@ int psd_set_greedy(psd_ctx* ctx, int32_t on);
  * Section 3.4 (1), as PSD_FLAG_ASSISTED does at creation. */
 int psd_set_assisted(psd_ctx* ctx, int32_t on);
 
+/* Adaptive controller for (tau_Q, tau_T, l_D, l_Q) inside psd_generate.  The paper names such a controller as future
+ * work (Conclusion and Future Work: adjust divergence thresholds and speculative lengths from the decoding context) and
+ * gives no rule; this is the library's reading, built from the paper's observations (Sections 4.2 and 4.4): full
+ * acceptance invites a longer window and a rejection cascade a shorter one, l_D about half of l_Q, tau_Q <= tau_T,
+ * thresholds no looser than acceptance needs.  All decisions are integer comparisons of counts:
+ *   after every target pass with window k2 and n accepted:  n == k2 -> k2 + 1 (<= k2_max);  2 n < k2 -> k2 - 1
+ *   (>= k2_min);  k1 = clamp((k2 + 1) / 2, 1, k1_max);
+ *   every `period` target passes, per stage, with p proposed and a accepted tokens since the last adjustment:
+ *   8 a >= 7 p -> threshold one position lower;  2 a < p -> one position higher; then tau_Q is lowered while it
+ *   exceeds tau_T.  Thresholds sit on the steps + 1 positions  min + (max - min) s / steps  of their band (evaluated in
+ *   double, rounded once to float).
+ * The run starts from the context's thresholds and k2, brought into the ranges (nearest position; clamped).
+ * Requirements: 1 <= k2_min <= k2_max <= the context's k2, 1 <= k1_max <= the context's k1, steps >= 1, period >= 1,
+ * 0 <= min <= max for both bands.  cfg == NULL switches the controller off.  psd_generate then needs
+ * n_prompt + n_new + k2_max + 2 <= max_seq.  psd_get_adaptive_log copies (k1, k2, position of tau_Q, position of
+ * tau_T) of up to `cap` outer iterations of the last psd_generate call into out[cap][4] (host) and returns how many
+ * iterations there were (or a negative error). */
+typedef struct {
+    int32_t k2_min, k2_max, k1_max;
+    int32_t steps, period;
+    float T_q_min, T_q_max, T_t_min, T_t_max;
+} psd_adapt;
+int psd_set_adaptive(psd_ctx* ctx, const psd_adapt* cfg);
+int psd_get_adaptive_log(psd_ctx* ctx, int32_t* out, int32_t cap);
+
 /* Plain autoregressive sampling from one model (0 draft, 1 qualifier, 2 target)
  * with the same fresh-sample draws: the no-speculation baseline. */
 int psd_generate_plain(psd_ctx* ctx, int32_t which, const int32_t* prompt, int32_t n_prompt, int32_t n_new,
@@ -287,7 +312,9 @@ int psd_philox_block(uint64_t seed, uint32_t c0, uint32_t n, uint32_t c1, uint32
 /* Trace hook for tests: when set, psd_generate copies the inputs of every draft
  * sample (kind 0, k = 0, logits_p = the draft row) and every ACCEPT (kind 1 / 2 =
  * stage; kind 3 = stage 1 under the assisted rule; greedy decoding: kind 6 = proposal, 4 / 5 = stage 1 / 2)
- * back to the host and calls fn after the step has been decided.  All
+ * back to the host and calls fn after the step has been decided.  Under the adaptive controller every outer
+ * iteration starts with a kind 7 call: position0 = committed length, k = k2, take_bonus = k1, n_accepted / next_token =
+ * positions of tau_Q / tau_T, div = {tau_Q, tau_T}, the other pointers NULL.  All
  * pointers are host memory valid during the callback only.  Slow; tests only. */
 typedef void (*psd_trace_fn)(void* user, int32_t kind, uint32_t position0, int32_t k, int32_t take_bonus,
                              const float* logits_p, const float* logits_q, const int32_t* tokens,

@@ -47,6 +47,13 @@ class Stats(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class Adapt(C.Structure):
+    """psd_adapt: ranges of the adaptive controller."""
+    _fields_ = [("k2_min", C.c_int32), ("k2_max", C.c_int32), ("k1_max", C.c_int32), ("steps", C.c_int32),
+                ("period", C.c_int32), ("T_q_min", C.c_float), ("T_q_max", C.c_float), ("T_t_min", C.c_float),
+                ("T_t_max", C.c_float)]
+
+
 class KernelStat(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("ms_total", C.c_double), ("bytes_total", C.c_double)]
 
@@ -107,6 +114,8 @@ def lib():
         L.psd_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p]
         L.psd_accept_assisted.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
                                           C.c_uint32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.psd_set_adaptive.argtypes = [C.c_void_p, C.POINTER(Adapt)]
+        L.psd_get_adaptive_log.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.psd_forward.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.psd_set_trace.argtypes = [C.c_void_p, TRACE_FN, C.c_void_p]
         L.psd_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -347,6 +356,19 @@ class Context:
         return {name: (int(out[3 * i]), float(out[3 * i + 1]), float(out[3 * i + 2]))
                 for i, name in enumerate(("draft", "qualifier", "target"))}
 
+    def set_adaptive(self, cfg):
+        """cfg: an Adapt (ranges of the controller) or None to switch it off."""
+        _check(lib().psd_set_adaptive(self._h, C.byref(cfg) if cfg is not None else None), self._h)
+
+    def adaptive_log(self):
+        """(k1, k2, position of tau_Q, position of tau_T) per outer iteration of the last generate call, [n, 4]."""
+        n = lib().psd_get_adaptive_log(self._h, None, 0)
+        if n < 0:
+            _check(n, self._h)
+        out = np.zeros((max(n, 1), 4), dtype=np.int32)
+        lib().psd_get_adaptive_log(self._h, out.ctypes.data, n)
+        return out[:n]
+
     def set_greedy(self, on: bool):
         _check(lib().psd_set_greedy(self._h, int(on)), self._h)
 
@@ -378,7 +400,10 @@ class Context:
         V = self.vocab
 
         def cb(user, kind, position0, k, take_bonus, lp, lq, tk, n_acc, nxt, div):
-            rows_p = 1 if kind == 0 else k + 1
+            if kind == 7:   # controller state at the start of an outer iteration: div = (tau_Q, tau_T)
+                fn(kind, position0, k, take_bonus, None, None, None, n_acc, nxt, np.ctypeslib.as_array(div, shape=(2,)).copy())
+                return
+            rows_p = 1 if kind in (0, 6) else k + 1
             a = np.ctypeslib.as_array(lp, shape=(rows_p, V)).copy()
             b = np.ctypeslib.as_array(lq, shape=(k, V)).copy() if k > 0 and lq else np.zeros((0, V), np.float32)
             t = np.ctypeslib.as_array(tk, shape=(k,)).copy() if k > 0 and tk else np.zeros(0, np.int32)

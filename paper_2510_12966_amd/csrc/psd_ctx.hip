@@ -7,6 +7,7 @@
 // into the next draft pass descriptor and into the qualifier's, so the host synchronises once per
 // qualifier round and once per target pass, when it reads the ACCEPT result.
 #include <stddef.h>
+#include <math.h>
 #include <string.h>
 
 #include <algorithm>
@@ -24,6 +25,56 @@ struct RoundResult {  // pinned host mirror of what a round leaves on the device
     AcceptOut acc;
     int32_t tok[kMaxW];
     float div[kMaxW];
+};
+
+// Adaptive controller (the header states the rule).  Pure host arithmetic on accept counts between outer iterations.
+struct Controller {
+    psd_adapt cfg{};
+    bool on = false;
+    int k1 = 0, k2 = 0, pos_q = 0, pos_t = 0;     // in force for the next outer iteration
+    int passes = 0;                               // target passes since the thresholds were last looked at
+    long long prop[2] = {0, 0}, acc[2] = {0, 0};  // per stage, since then
+    std::vector<int32_t> log;                     // (k1, k2, pos_q, pos_t) per outer iteration of the last call
+
+    static float at(float lo, float hi, int pos, int steps) {
+        return (float)((double)lo + ((double)hi - (double)lo) * (double)pos / (double)steps);
+    }
+    static int nearest(float lo, float hi, float T, int steps) {
+        if (!(hi > lo)) return 0;
+        const double x = ((double)T - (double)lo) / ((double)hi - (double)lo) * (double)steps;
+        return std::min(steps, std::max(0, (int)floor(x + 0.5)));
+    }
+    float tau_q() const { return at(cfg.T_q_min, cfg.T_q_max, pos_q, cfg.steps); }
+    float tau_t() const { return at(cfg.T_t_min, cfg.T_t_max, pos_t, cfg.steps); }
+    void set_window(int k) {
+        k2 = std::min((int)cfg.k2_max, std::max((int)cfg.k2_min, k));
+        k1 = std::min((int)cfg.k1_max, std::max(1, (k2 + 1) / 2));
+    }
+    void start(float T_q, float T_t, int k2_start) {
+        set_window(k2_start);
+        pos_q = nearest(cfg.T_q_min, cfg.T_q_max, T_q, cfg.steps);
+        pos_t = nearest(cfg.T_t_min, cfg.T_t_max, T_t, cfg.steps);
+        passes = 0;
+        prop[0] = prop[1] = acc[0] = acc[1] = 0;
+        log.clear();
+    }
+    // one outer iteration is over: the target accepted n of the k2 window tokens, the qualifier aq of pq draft tokens
+    void observe(int n, long long pq, long long aq) {
+        prop[0] += pq; acc[0] += aq; prop[1] += k2; acc[1] += n;
+        if (n == k2) set_window(k2 + 1);
+        else if (2 * n < k2) set_window(k2 - 1);
+        else set_window(k2);
+        if (++passes < cfg.period) return;
+        int* pos[2] = {&pos_q, &pos_t};
+        for (int s = 0; s < 2; ++s) {
+            if (prop[s] == 0) continue;
+            if (8 * acc[s] >= 7 * prop[s]) *pos[s] = std::max(0, *pos[s] - 1);
+            else if (2 * acc[s] < prop[s]) *pos[s] = std::min((int)cfg.steps, *pos[s] + 1);
+        }
+        while (pos_q > 0 && tau_q() > tau_t()) --pos_q;
+        passes = 0;
+        prop[0] = prop[1] = acc[0] = acc[1] = 0;
+    }
 };
 
 struct GraphSlot {
@@ -98,6 +149,7 @@ struct psd_ctx {
     GraphSlot chain_graphs[3][3][kNumNarrowClasses][kNumCtxBuckets];  // sampling steps: [proposer][model whose pass descriptor receives the tokens][launch class][context bucket]
     Profiler prof;
     StageTimer timer;
+    Controller ctl;
     psd_trace_fn trace = nullptr;
     void* trace_user = nullptr;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -546,10 +598,18 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
                             int32_t* out_tokens, psd_stats* out_stats) {
     if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_generate: null context");
     if (!prompt || n_prompt < 1 || n_new < 0 || (n_new > 0 && !out_tokens)) PSD_FAIL(PSD_EINVAL, c->err, "psd_generate: bad argument");
-    const int k1 = c->prm.k1, k2 = c->prm.k2, V = c->V;
+    const int V = c->V;
     const int greedy = (c->prm.flags & PSD_FLAG_GREEDY) ? 1 : 0;
     const int assisted = greedy ? 2 : (c->prm.flags & PSD_FLAG_ASSISTED) ? 1 : 0;  // rule of the qualifier stage
-    const int cap = n_prompt + n_new + k2 + 2;
+    // thresholds and window lengths of the current outer iteration: fixed, or moved by the adaptive controller
+    Controller& ctl = c->ctl;
+    int k1 = c->prm.k1, k2 = c->prm.k2;
+    float T_q = c->prm.T_q, T_t = c->prm.T_t;
+    if (ctl.on) {
+        ctl.start(T_q, T_t, k2);
+        k1 = ctl.k1; k2 = ctl.k2; T_q = ctl.tau_q(); T_t = ctl.tau_t();
+    }
+    const int cap = n_prompt + n_new + (ctl.on ? (int)ctl.cfg.k2_max : k2) + 2;
     if (cap > c->prm.max_seq) PSD_FAIL(PSD_ESHAPE, c->err, "psd_generate: n_prompt + n_new + k2 + 2 = %d exceeds max_seq %d", cap, c->prm.max_seq);
     int rc = check_tokens(c, prompt, n_prompt);
     if (rc != PSD_OK) return rc;
@@ -570,6 +630,15 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
 
     while (C - n_prompt < n_new) {
         int nbuf = 0;
+        const int64_t pq0 = st.proposed_q, aq0 = st.accepted_q;
+        if (ctl.on) {
+            const int32_t row[4] = {k1, k2, ctl.pos_q, ctl.pos_t};
+            ctl.log.insert(ctl.log.end(), row, row + 4);
+            if (c->trace) {
+                const float thr[2] = {T_q, T_t};
+                c->trace(c->trace_user, 7, (uint32_t)C, k2, k1, nullptr, nullptr, nullptr, ctl.pos_q, ctl.pos_t, thr);
+            }
+        }
         while (nbuf < k2) {
             const int m = std::min(k1, k2 - nbuf), L = C + nbuf;
             // draft: first step ingests the host-known uncached suffix, the rest chain on the device
@@ -598,7 +667,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
             if ((rc = note_rows(c, 0, c->DL, m)) != PSD_OK) return rc;
             if ((rc = note_rows(c, 1, c->QL + (size_t)nbuf * V, m + 1)) != PSD_OK) return rc;
             const int bonus = nbuf + m < k2;
-            if ((rc = accept_sync(c, "accept stage1", c->QL + (size_t)nbuf * V, c->DL, c->round_tok, m, c->prm.T_q, seed,
+            if ((rc = accept_sync(c, "accept stage1", c->QL + (size_t)nbuf * V, c->DL, c->round_tok, m, T_q, seed,
                                   (uint32_t)L, 1u, bonus, assisted, m)) != PSD_OK) return rc;
             const int n = c->res->acc.n_accepted, y = c->res->acc.next_token, has_y = y >= 0;
             if (n < 0 || n > m || (!has_y && (n < m || bonus))) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
@@ -632,7 +701,7 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         c->timer.end(c->stream);
         st.passes_t++;
         if ((rc = note_rows(c, 2, c->TL, k2 + 1)) != PSD_OK) return rc;
-        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->win_tok, k2, c->prm.T_t, seed, (uint32_t)C, 2u, 1,
+        if ((rc = accept_sync(c, "accept stage2", c->TL, c->QL, c->win_tok, k2, T_t, seed, (uint32_t)C, 2u, 1,
                               greedy ? 2 : 0, 0)) != PSD_OK) return rc;
         const int n = c->res->acc.n_accepted, y = c->res->acc.next_token;
         if (n < 0 || n > k2 || y < 0) PSD_FAIL(PSD_EHIP, c->err, "internal: impossible ACCEPT result (n=%d y=%d)", n, y);
@@ -649,6 +718,10 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
         st.proposed_t += k2;
         st.accepted_t += n;
         st.fuzzy_t += c->res->acc.n_fuzzy;
+        if (ctl.on) {   // this iteration's counts set the next iteration's parameters
+            ctl.observe(n, st.proposed_q - pq0, st.accepted_q - aq0);
+            k1 = ctl.k1; k2 = ctl.k2; T_q = ctl.tau_q(); T_t = ctl.tau_t();
+        }
     }
     PSD_HIP(hipEventRecord(c->ev[2], c->stream), c->err);
     PSD_HIP(hipEventSynchronize(c->ev[2]), c->err);
@@ -663,6 +736,28 @@ extern "C" int psd_generate(psd_ctx* c, const int32_t* prompt, int32_t n_prompt,
     if (n_new > 0) memcpy(out_tokens, seq.data() + n_prompt, (size_t)n_new * sizeof(int32_t));
     if (out_stats) *out_stats = st;
     return PSD_OK;
+}
+
+extern "C" int psd_set_adaptive(psd_ctx* c, const psd_adapt* cfg) {
+    if (!c) PSD_FAIL(PSD_EINVAL, tls_error(), "psd_set_adaptive: null context");
+    if (!cfg) { c->ctl.on = false; return PSD_OK; }
+    if (cfg->k2_min < 1 || cfg->k2_max < cfg->k2_min || cfg->k2_max > c->k2cap || cfg->k1_max < 1 || cfg->k1_max > c->k1cap)
+        PSD_FAIL(PSD_EINVAL, c->err, "psd_set_adaptive: windows k2 [%d, %d], k1 <= %d outside the context's capacity (k1 %d, k2 %d)",
+                 cfg->k2_min, cfg->k2_max, cfg->k1_max, c->k1cap, c->k2cap);
+    if (cfg->steps < 1 || cfg->period < 1) PSD_FAIL(PSD_EINVAL, c->err, "psd_set_adaptive: steps=%d period=%d", cfg->steps, cfg->period);
+    if (!(cfg->T_q_min >= 0.f) || !(cfg->T_q_max >= cfg->T_q_min) || !(cfg->T_t_min >= 0.f) || !(cfg->T_t_max >= cfg->T_t_min))
+        PSD_FAIL(PSD_EINVAL, c->err, "psd_set_adaptive: threshold bands must satisfy 0 <= min <= max");
+    c->ctl.cfg = *cfg;
+    c->ctl.on = true;
+    c->ctl.log.clear();
+    return PSD_OK;
+}
+
+extern "C" int psd_get_adaptive_log(psd_ctx* c, int32_t* out, int32_t cap) {
+    if (!c || (cap > 0 && !out) || cap < 0) PSD_FAIL(PSD_EINVAL, c ? c->err : tls_error(), "psd_get_adaptive_log: bad argument");
+    const int n = (int)(c->ctl.log.size() / 4);
+    if (cap > 0 && n > 0) memcpy(out, c->ctl.log.data(), (size_t)std::min(n, (int)cap) * 4 * sizeof(int32_t));
+    return n;
 }
 
 extern "C" int psd_set_row_stats(psd_ctx* c, int32_t on) {

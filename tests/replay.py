@@ -72,10 +72,16 @@ class Replay:
         self.forced, self.proposer = forced, proposer
         self.events = self.ties = self.kinds = 0
         self.max_div_err = 0.0
+        self.windows, self.counts = [], []
 
     def __call__(self, kind, pos0, k, bonus, lp, lq, tk, n_acc, nxt, div):
         self.events += 1
         self.kinds |= 1 << kind
+        if kind == 7:   # adaptive controller: thresholds and windows in force from this outer iteration on
+            self.T = {1: float(div[0]), 2: float(div[1])}
+            self.windows.append((bonus, k, n_acc, nxt))      # (k1, k2, position of tau_Q, position of tau_T)
+            self.counts.append([0, 0, 0])                    # this iteration's (stage-1 proposed, stage-1 accepted, stage-2 accepted)
+            return
         if kind == 0:
             if self.forced:
                 self.forced.check(self.proposer, pos0, [], lp)
@@ -96,6 +102,12 @@ class Replay:
                 self.ties += 1
             return
         assert kind in (1, 2)
+        if self.counts:
+            if kind == 1:
+                self.counts[-1][0] += k
+                self.counts[-1][1] += n_acc
+            else:
+                self.counts[-1][2] = n_acc
         res, odiv = oracle.accept(lp, lq, tk, self.T[kind], self.temp, self.seed, pos0, kind, bool(bonus))
         self.max_div_err = max(self.max_div_err, float(np.abs(div - odiv).max(initial=0.0)))
         assert self.max_div_err <= DIV_TOL

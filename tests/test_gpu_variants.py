@@ -295,3 +295,69 @@ def test_randomised_bf16_stacks_variants(case):
     print("case", case, "mode", mode, "max |logit err| in the loop", forced.max_err, shapes, "k1", k1, "k2", k2, "tau", round(tau, 3), "prompt", n_prompt, st, flush=True)
     assert out.size == n_new and (out >= 0).all() and (out < vocab).all()
     ctx.close()
+
+
+# ---- adaptive controller for thresholds and window lengths (the paper's future work; the rule is this build's reading) ----
+
+@pytest.mark.parametrize("graph", [0, psd.FLAG_GRAPH])
+@pytest.mark.parametrize("ranges", [
+    (2, 12, 5, 6, 2, (0.0, 0.012), (0.0, 0.024), 6, 0.004, 0.012),     # both bands around this stack's divergences
+    (1, 8, 4, 4, 1, (0.002, 0.006), (0.004, 0.03), 3, 0.004, 0.012),   # adjusts after every target pass
+    (8, 8, 4, 1, 3, (0.004, 0.004), (0.012, 0.012), 8, 0.004, 0.012),  # nowhere to go: the plain loop
+])
+def test_adaptive_loop_matches_oracle(tiny_stack, ranges, graph):
+    cfg, d, q, t, prompt = tiny_stack
+    k2_min, k2_max, k1_max, steps, period, bq, bt, k2_start, T_q, T_t = ranges
+    T_q, T_t = float(np.float32(T_q)), float(np.float32(T_t))          # the library takes float thresholds
+    n_new, seed = 64, 5
+    ms = len(prompt) + n_new + 12 + 2
+    ctx = _ctx(cfg, (d, q, t), ms, T_q, T_t, 6, 12, flags=graph)
+    ctx.set_decoding(T_q, T_t, min(6, k2_start), k2_start)
+    ctx.set_adaptive(psd.Adapt(k2_min, k2_max, k1_max, steps, period, bq[0], bq[1], bt[0], bt[1]))
+    forced = forced_for((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, ms, prompt)
+    rp = Replay(seed, T_q, T_t, 1.0, forced)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(prompt, n_new, seed)
+    ctx.set_trace(None)
+    log = ctx.adaptive_log()
+    assert rp.kinds == 0b10000111 and forced.cur[len(prompt):len(prompt) + n_new] == out.tolist()
+    assert len(log) == st["passes_t"] == len(rp.windows) and [tuple(r) for r in log] == rp.windows
+    assert st["proposed_t"] == int(log[:, 1].sum())
+    ad = oracle.Adapt(k2_min, k2_max, k1_max, steps, period, bq[0], bq[1], bt[0], bt[1])
+    ref, ost, olog = oracle.generate_adaptive(_om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms),
+                                              prompt, n_new, seed, k2_start, T_q, T_t, ad)
+    # the controller itself, replayed on the GPU run's own counts, must give the GPU's trajectory exactly
+    sto = oracle.adapt_init(ad, T_q, T_t, k2_start)
+    for row, (p_q, a_q, n_t) in zip(log, rp.counts):
+        assert sto.params() == tuple(row)
+        oracle.adapt_step(ad, sto, n_t, p_q, a_q)
+    if rp.ties == 0 and np.array_equal(out, ref):
+        assert np.array_equal(log, olog)
+        for key in ("proposed_q", "accepted_q", "proposed_t", "accepted_t", "passes_d", "passes_q", "passes_t"):
+            assert st[key] == ost[key], key
+    if k2_min == k2_max:
+        plain, _ = _ctx(cfg, (d, q, t), ms, T_q, T_t, 4, 8, flags=graph).generate(prompt, n_new, seed)
+        assert np.array_equal(out, plain)
+    else:
+        assert len({tuple(r) for r in log}) > 2        # the parameters really moved
+    # switching the controller off gives the fixed loop again, with the parameters set before
+    ctx.set_adaptive(None)
+    fixed, _ = ctx.generate(prompt, 24, seed)
+    D, Q, T = _om(cfg.draft, d, cfg, ms), _om(cfg.qualifier, q, cfg, ms), _om(cfg.target, t, cfg, ms)
+    fref, _ = oracle.generate(D, Q, T, prompt, 24, seed, min(6, k2_start), k2_start, T_q, T_t)
+    assert np.array_equal(fixed, fref) or (fixed[:3] == fref[:3]).all()
+    ctx.close()
+
+
+def test_adaptive_argument_errors(tiny_stack):
+    cfg, d, q, t, prompt = tiny_stack
+    ctx = _ctx(cfg, (d, q, t), 64, 0.3, 0.2, 4, 8)
+    for bad in (psd.Adapt(0, 8, 4, 4, 2, 0, 0.1, 0, 0.1), psd.Adapt(2, 9, 4, 4, 2, 0, 0.1, 0, 0.1), psd.Adapt(2, 8, 5, 4, 2, 0, 0.1, 0, 0.1),
+                psd.Adapt(2, 8, 4, 0, 2, 0, 0.1, 0, 0.1), psd.Adapt(2, 8, 4, 4, 0, 0, 0.1, 0, 0.1), psd.Adapt(2, 8, 4, 4, 2, 0.2, 0.1, 0, 0.1),
+                psd.Adapt(2, 8, 4, 4, 2, 0, 0.1, -0.1, 0.1)):
+        with pytest.raises(psd.PsdError):
+            ctx.set_adaptive(bad)
+    ctx.set_adaptive(psd.Adapt(2, 8, 4, 4, 2, 0, 0.1, 0, 0.1))
+    with pytest.raises(psd.PsdError):
+        ctx.generate(prompt, 40, 1)          # 16 + 40 + k2_max 8 + 2 > 64
+    ctx.close()
