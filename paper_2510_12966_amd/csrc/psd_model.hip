@@ -138,10 +138,21 @@ template <>
 __device__ inline float kv_load<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
 
 // bf16 models keep every K and V element as a bf16 hi + lo pair (value = hi + lo to 2^-17) in four planes per
-// (page, layer, kv head): K hi [slot][hd], K lo, V hi [hd][slot] (transposed), V lo.  One bf16 rounding of the
+// (page, layer, kv head): K hi, K lo, V hi, V lo, each of kPage x hd elements.  One bf16 rounding of the
 // cache alone would put ~0.1 % * sqrt(layers) of noise on the logits, which at 32 layers is past the tolerance.
 __device__ inline size_t kv_plane(int page, int layer, int L, int g, int KV, int plane, int hd) {
     return ((((size_t)page * L + layer) * KV + g) * 4 + plane) * (size_t)kPage * hd;
+}
+
+// Inside a plane the elements sit in the order the attention MFMAs consume them, so that a wave's operand load is one
+// contiguous block (1 KiB for K, 512 bytes for V) instead of sixteen strided pieces:
+//   K planes: A-operand tiles of v_mfma_f32_16x16x32_bf16, [slot / 16][hd / 32][64 lanes][8], lane = (dim % 32) / 8 * 16 + slot % 16
+//   V planes: B-operand tiles of v_mfma_f32_16x16x16_bf16, [hd / 16][slot / 16][64 lanes][4], lane = (slot % 16) / 4 * 16 + dim % 16
+__device__ inline int kv_k_off(int slot, int dim, int hd) {
+    return ((((slot >> 4) * (hd >> 5) + (dim >> 5)) * 64 + ((dim & 31) >> 3) * 16 + (slot & 15)) << 3) + (dim & 7);
+}
+__device__ inline int kv_v_off(int slot, int dim) {
+    return ((((dim >> 4) * (kPage >> 4) + (slot >> 4)) * 64 + ((slot & 15) >> 2) * 16 + (dim & 15)) << 2) + (slot & 3);
 }
 
 __device__ inline size_t kv_base(int page, int layer, int L, int g, int KV, int which, int hd) {
@@ -472,17 +483,18 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
             float* q = a.Y + (size_t)c * a.ldy + (size_t)head * hd;
             *reinterpret_cast<float2*>(q + j0) = make_float2(x0[0], x0[1]);
             *reinterpret_cast<float2*>(q + j0 + half) = make_float2(x1[0], x1[1]);
-        } else if (head < a.H + a.KV) {   // K planes: [slot][hd]
-            uint16_t* kh = a.kv + kv_plane(page, a.layer, a.L, head - a.H, a.KV, 0, hd) + (size_t)slot * hd;
+        } else if (head < a.H + a.KV) {   // K planes
+            uint16_t* kh = a.kv + kv_plane(page, a.layer, a.L, head - a.H, a.KV, 0, hd);
             uint16_t* kl = kh + (size_t)kPage * hd;
             uint32_t h0, l0, h1, l1;
             f32x2_split(x0[0], x0[1], h0, l0);
             f32x2_split(x1[0], x1[1], h1, l1);
-            *reinterpret_cast<uint32_t*>(kh + j0) = h0;
-            *reinterpret_cast<uint32_t*>(kh + j0 + half) = h1;
-            *reinterpret_cast<uint32_t*>(kl + j0) = l0;
-            *reinterpret_cast<uint32_t*>(kl + j0 + half) = l1;
-        } else {                          // V planes, transposed: [hd][slot]
+            const int o0 = kv_k_off(slot, j0, hd), o1 = kv_k_off(slot, j0 + half, hd);   // j0 is even: the pair stays together
+            *reinterpret_cast<uint32_t*>(kh + o0) = h0;
+            *reinterpret_cast<uint32_t*>(kh + o1) = h1;
+            *reinterpret_cast<uint32_t*>(kl + o0) = l0;
+            *reinterpret_cast<uint32_t*>(kl + o1) = l1;
+        } else {                          // V planes
             uint16_t* vh = a.kv + kv_plane(page, a.layer, a.L, head - a.H - a.KV, a.KV, 2, hd);
             uint16_t* vl = vh + (size_t)kPage * hd;
 #pragma unroll
@@ -490,10 +502,11 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
                 const int j = j0 + pr;
                 uint32_t hi, lo;
                 f32x2_split(x0[pr], x1[pr], hi, lo);
-                vh[(size_t)j * kPage + slot] = (uint16_t)hi;
-                vh[(size_t)(j + half) * kPage + slot] = (uint16_t)(hi >> 16);
-                vl[(size_t)j * kPage + slot] = (uint16_t)lo;
-                vl[(size_t)(j + half) * kPage + slot] = (uint16_t)(lo >> 16);
+                const int o0 = kv_v_off(slot, j), o1 = kv_v_off(slot, j + half);
+                vh[o0] = (uint16_t)hi;
+                vh[o1] = (uint16_t)(hi >> 16);
+                vl[o0] = (uint16_t)lo;
+                vl[o1] = (uint16_t)(lo >> 16);
             }
         }
     }
@@ -985,44 +998,66 @@ __global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const Pa
 // grid (KV heads, nsplit_max, query tiles), 256 threads.  A workgroup owns one KV head, the absolute key range
 // [split * 128, +128) and 16 query rows rho = token * G + head_in_group; wave j owns the 32 keys
 // [split * 128 + 32 j, +32):
-//   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 head dims straight from the K planes (hi, lo),
-//                  B = queries as bf16 hi + lo built in registers; result lane (g, c): keys 4g..4g+3 of query c
+//   S^T = K Q^T    v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 head dims: one contiguous 1 KiB tile of the K planes
+//                  (hi, lo), B = queries as bf16 hi + lo built in registers; result lane (g, c): keys 4g..4g+3 of query c
 //   P   = exp(S - max) per query over the wave's 32 keys (masked causally), kept in registers: the result
 //         layout of S^T is exactly the A operand layout of v_mfma_f32_16x16x16bf16_1k
-//   O   = P V      B = 4 consecutive keys of one head dim: one 8-byte load from the transposed V page
+//   O   = P V      B = 4 consecutive keys of one head dim: one contiguous 512-byte tile of the V planes
 // The four waves' (max, sum, O) are merged through LDS in wave order and written as one partial per split.
+// Memory round trips on the critical path: the pass descriptor and the page-table entry travel together, then the
+// queries (from L2), keys and values go out back to back; the kernel is latency-bound, so that is what counts.
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDesc* desc, const uint16_t* kv,
-                                                 const int32_t* page_table, float* part, int layer, int L, int H,
+                                                 const int32_t* page_table, int n_pages, float* part, int layer, int L, int H,
                                                  int KV, int nqkv, int qt_per_wg) {
     constexpr int KSQ = HD / 32, JT = HD / 16;
     __shared__ float mrg[4][16][HD + 2];
-    __shared__ float fac[4][16];
-    __shared__ int row_head[16];
     const int gkv = blockIdx.x, split = blockIdx.y;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, g = lane >> 4, cq = lane & 15;
+    const int key0 = split * kAttnSplit, wkey0 = key0 + wave * 32;
+    // asked for together with the descriptor: the entry exists for every key range a launch covers
+    const int page = page_table[min(wkey0 / kPage, n_pages - 1)];
     const int w = desc->w, pos0 = desc->pos0;
-    const int key0 = split * kAttnSplit, kv_max = pos0 + w;
+    const int kv_max = pos0 + w;
     const int G = H / KV, R = w * G;
     if (key0 >= kv_max || (int)blockIdx.z * qt_per_wg * 16 >= R) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, cq = lane & 15;
-    const int wkey0 = key0 + wave * 32;
     const bool wave_live = wkey0 < kv_max;
+    const float scale = rsqrtf((float)HD);
+    // query rows of the first tile, as they come from the q/k/v projection (fp32); converted when they are used
+    auto load_q = [&](int qt, float (&v)[KSQ][8]) {
+        const int rho = qt * 16 + cq;
+        const float* qrow = qkv + (size_t)(rho / G) * nqkv + (size_t)(gkv * G + rho % G) * HD;
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) {
+            if (rho < R) {
+                const float4 a0 = *reinterpret_cast<const float4*>(qrow + ks * 32 + g * 8);
+                const float4 a1 = *reinterpret_cast<const float4*>(qrow + ks * 32 + g * 8 + 4);
+                v[ks][0] = a0.x; v[ks][1] = a0.y; v[ks][2] = a0.z; v[ks][3] = a0.w;
+                v[ks][4] = a1.x; v[ks][5] = a1.y; v[ks][6] = a1.z; v[ks][7] = a1.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[ks][e] = 0.f;
+            }
+        }
+    };
+    float qraw[KSQ][8];
+    if (wave_live) load_q(blockIdx.z * qt_per_wg, qraw);
     // the wave's keys and values stay in registers for all of the workgroup's query tiles
     u32x4 ka[2][KSQ], kb[2][KSQ];   // hi and lo halves
     uint2 vraw[JT][2], vlow[JT][2];
     if (wave_live) {
-        // this wave's 32 keys sit inside one page: K rows are the A operand of S^T, V^T columns the B operand of P V
-        const int page = page_table[wkey0 / kPage], slot0 = wkey0 % kPage;
+        // this wave's 32 keys are two 16-slot tiles of one page
+        const int st0 = (wkey0 % kPage) >> 4;
         constexpr size_t kPlane = (size_t)kPage * HD;
-        const uint16_t* Kp = kv + kv_plane(page, layer, L, gkv, KV, 0, HD) + (size_t)slot0 * HD;
-        const uint16_t* Vp = kv + kv_plane(page, layer, L, gkv, KV, 2, HD) + slot0;
+        const uint16_t* Kp = kv + kv_plane(page, layer, L, gkv, KV, 0, HD);
+        const uint16_t* Vp = Kp + 2 * kPlane;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int ks = 0; ks < KSQ; ++ks) {
-                const uint16_t* p = Kp + (size_t)(kt * 16 + cq) * HD + ks * 32 + g * 8;
+                const uint16_t* p = Kp + ((size_t)((st0 + kt) * KSQ + ks) * 64 + lane) * 8;
                 ka[kt][ks] = *reinterpret_cast<const u32x4*>(p);
                 kb[kt][ks] = *reinterpret_cast<const u32x4*>(p + kPlane);
             }
@@ -1030,7 +1065,7 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
         for (int j = 0; j < JT; ++j)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                const uint16_t* p = Vp + (size_t)(j * 16 + cq) * kPage + kt * 16 + g * 4;
+                const uint16_t* p = Vp + ((size_t)(j * (kPage >> 4) + st0 + kt) * 64 + lane) * 4;
                 vraw[j][kt] = *reinterpret_cast<const uint2*>(p);
                 vlow[j][kt] = *reinterpret_cast<const uint2*>(p + kPlane);
             }
@@ -1047,24 +1082,14 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
     for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (wave_live) {
         // query row rho as B operand: lane (g, c) holds head dims 32 ks + 8 g .. + 8 of row c, scaled by 1/sqrt(hd)
-        const float scale = rsqrtf((float)HD);
+        if (qi > 0) load_q(qt, qraw);
         u32x4 qh[KSQ], ql[KSQ];
-        const float* qrow = qkv + (size_t)(rho / G) * nqkv + (size_t)(gkv * G + rho % G) * HD;
 #pragma unroll
         for (int ks = 0; ks < KSQ; ++ks) {
-            float v[8];
-            if (rho < R) {
-                const float4 a0 = *reinterpret_cast<const float4*>(qrow + ks * 32 + g * 8);
-                const float4 a1 = *reinterpret_cast<const float4*>(qrow + ks * 32 + g * 8 + 4);
-                v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = 0.f;
-            }
             uint32_t hw[4], lw[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                f32x2_split(v[2 * e] * scale, v[2 * e + 1] * scale, hw[e], lw[e]);
+                f32x2_split(qraw[ks][2 * e] * scale, qraw[ks][2 * e + 1] * scale, hw[e], lw[e]);
             }
             qh[ks] = u32x4{hw[0], hw[1], hw[2], hw[3]};
             ql[ks] = u32x4{lw[0], lw[1], lw[2], lw[3]};
@@ -1128,39 +1153,35 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
 #pragma unroll
         for (int r = 0; r < 4; ++r) mrg[wave][g * 4 + r][2 + j * 16 + cq] = O[j][r];
     __syncthreads();
-    // per query row, once: the four waves' rescaling factors, the merged (max, sum) and where the row goes
-    if (threadIdx.x < 16) {
-        const int qr = threadIdx.x, rr = qt * 16 + qr;
-        int rh = -1;
+    // sixteen threads per query row: each works out the row's merged maximum and the four waves' rescaling factors for
+    // itself (the same arithmetic in every thread), one of them stores (max, sum), and together they merge the row's
+    // head dims, sixteen at a time
+    {
+        const int qr = threadIdx.x >> 4, i0 = threadIdx.x & 15, rr = qt * 16 + qr;
         if (rr < R) {
             float M = -INFINITY;
 #pragma unroll
             for (int v = 0; v < 4; ++v) M = fmaxf(M, mrg[v][qr][0]);
-            float Ls = 0.f;
+            float fac[4], Ls = 0.f;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float f = mrg[v][qr][0] == -INFINITY ? 0.f : expf(mrg[v][qr][0] - M);
-                Ls = fmaf(mrg[v][qr][1], f, Ls);
-                fac[v][qr] = f;
+                fac[v] = mrg[v][qr][0] == -INFINITY ? 0.f : expf(mrg[v][qr][0] - M);
+                Ls = fmaf(mrg[v][qr][1], fac[v], Ls);
             }
-            rh = (rr / G) * H + gkv * G + rr % G;
+            const int rh = (rr / G) * H + gkv * G + rr % G;
             float* out = part + ((size_t)split * kCols * H + rh) * (HD + 2);
-            out[0] = M;
-            out[1] = Ls;
-        }
-        row_head[qr] = rh;
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
-        const int qr = idx / HD, i = idx % HD, rh = row_head[qr];
-        if (rh >= 0) {
-            float o = 0.f;
+            if (i0 == 0) { out[0] = M; out[1] = Ls; }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o = fmaf(mrg[v][qr][2 + i], fac[v][qr], o);
-            part[((size_t)split * kCols * H + rh) * (HD + 2) + 2 + i] = o;
+            for (int jj = 0; jj < JT; ++jj) {
+                const int i = jj * 16 + i0;
+                float o = 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) o = fmaf(mrg[v][qr][2 + i], fac[v], o);
+                out[2 + i] = o;
+            }
         }
     }
-    __syncthreads();   // the merge buffer is reused by the next query tile
+    if (qi + 1 < qt_per_wg) __syncthreads();   // the merge buffer is reused by the next query tile
     }
 }
 
@@ -1653,9 +1674,9 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
         launch_gemm_bf16<EPI_QKV>(L, "gemm_qkv", a);
         L.begin("attn", kv_bytes);
         const dim3 agrid(KV, nsplit, qt_max);
-        if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
-        else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
-        else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
+        if (hd == 128) attn_mfma<128><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.n_pages, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
+        else if (hd == 64) attn_mfma<64><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.n_pages, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
+        else attn_mfma<32><<<agrid, 256, 0, stream>>>(M.qkv, M.desc, (const uint16_t*)M.kv, M.page_table, M.n_pages, M.attn_part, l, M.L, H, KV, M.nqkv, qt_per_wg);
         L.end();
         a = base;
         a.Wt = (const u32x4*)w.wo; a.XB = (const u32x4*)xb2; a.N = d; a.KS = (H * hd) / 32;
