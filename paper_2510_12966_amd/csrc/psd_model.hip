@@ -1074,7 +1074,10 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
     const int qt = blockIdx.z * qt_per_wg + qi;
     if (qt * 16 >= R) break;
     // every key of this split lies after the tile's last query: nothing to attend to, and the merge never reads it
-    if (key0 > pos0 + ((qt * 16 + 15 < R ? qt * 16 + 15 : R - 1) / G)) continue;
+    if (key0 > pos0 + ((qt * 16 + 15 < R ? qt * 16 + 15 : R - 1) / G)) {
+        if (wave_live && qi + 1 < qt_per_wg) load_q(qt + 1, qraw);   // qraw always holds the queries of the tile about to be worked on
+        continue;
+    }
     const int rho = qt * 16 + cq;
     float m = -INFINITY, l = 0.f;
     f32x4 O[JT];
@@ -1082,7 +1085,6 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
     for (int j = 0; j < JT; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (wave_live) {
         // query row rho as B operand: lane (g, c) holds head dims 32 ks + 8 g .. + 8 of row c, scaled by 1/sqrt(hd)
-        if (qi > 0) load_q(qt, qraw);
         u32x4 qh[KSQ], ql[KSQ];
 #pragma unroll
         for (int ks = 0; ks < KSQ; ++ks) {
@@ -1094,6 +1096,7 @@ __global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDes
             qh[ks] = u32x4{hw[0], hw[1], hw[2], hw[3]};
             ql[ks] = u32x4{lw[0], lw[1], lw[2], lw[3]};
         }
+        if (qi + 1 < qt_per_wg) load_q(qt + 1, qraw);   // the next tile's queries travel while this tile is worked on
         f32x4 Sx[2];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
