@@ -310,24 +310,27 @@ __device__ inline bool sweep_second(const AcceptShape& s, const AcceptWs& w, con
         if (threadIdx.x == 0) __hip_atomic_store(w.expired, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return false;
     }
-    // p_v = 2^(a_v c2 - lp), q_v = 2^(c_v c2 - lq);  t = log2 q_v - log2 p_v = (c_v - a_v) c2 + dl
+    // With xp = log2 p_v = a_v c2 - lp and xq = log2 q_v = c_v c2 - lq, call the larger probability B = 2^max(xp, xq) and
+    // the smaller one S = B e with e = 2^-A, A = |xq - xp|.  Then m = (B + S) / 2 and
+    //   log2(B / m) = 1 - log2(1 + e) =: u,    log2(S / m) = u - A,
+    // so the entry contributes B u + S (u - A) whichever of p, q is the larger: three transcendentals (2^max, 2^-A,
+    // log2(1 + e)), no selects.  Equal rows give A = 0, e = 1, u = 0 exactly, hence a divergence of exactly 0; there is no
+    // cancellation anywhere.  Masked entries: A is clamped to a finite value, so they contribute B * 1 + 0 * finite (one
+    // row has no mass there) or 0 * finite (neither has).
     const float lSp = log2f(R.Sp), lSq = log2f(R.Sq);
     const float lp = R.Mp + lSp, lq = R.Mq + lSq;   // base-2 log-sum-exp of the rows
-    const float dl = (R.Mp - R.Mq) + (lSp - lSq);
     float acc = 0.f;
 #pragma unroll
     for (int j = 0; j < kSweepQuads; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp2(fmaf(a[j][e], c2, -lp));
-            const float q = fast_exp2(fmaf(c[j][e], c2, -lq));
-            // log2(p/m) = 1 - sp2(t), log2(q/m) = 1 - sp2(-t) with m = (p + q) / 2 and
-            // sp2(y) = log2(1 + 2^y) = max(y, 0) + log2(1 + 2^-|y|).
-            // Clamped: masked entries (t = +-inf or inf - inf) then contribute 0 * finite.
-            const float t = __builtin_amdgcn_fmed3f(fmaf(c[j][e] - a[j][e], c2, dl), -kBig, kBig);
-            const float u = 1.f - fast_log2(1.f + fast_exp2(-fabsf(t)));
-            acc = fmaf(p, u - fmaxf(t, 0.f), acc);
-            acc = fmaf(q, u - fmaxf(-t, 0.f), acc);
+        for (int e4 = 0; e4 < 4; ++e4) {
+            const float xp = fmaf(a[j][e4], c2, -lp), xq = fmaf(c[j][e4], c2, -lq);
+            const float big = fast_exp2(fmaxf(fmaxf(xp, xq), -kBig));
+            const float A = fabsf(__builtin_amdgcn_fmed3f(xq - xp, -kBig, kBig));   // inf - inf (both masked) clamps to a finite value too
+            const float e = fast_exp2(-A);
+            const float u = 1.f - fast_log2(1.f + e);
+            acc = fmaf(big, u, acc);
+            acc = fmaf(big * e, u - A, acc);
         }
     acc = wave_sum_dpp(acc);
     if ((threadIdx.x & 63) == 0)
