@@ -50,70 +50,188 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def accept_microbench(psd, synth, ks=(4, 8, 16, 32), quick=False, calibrate=False) -> int:
-    """Stand-alone ACCEPT stage on batched trials: achieved GB/s (algorithmic bytes: every logit read once) and
-    accept-length histogram parity with the oracle on the same trials."""
-    import math
+ACCEPT_V, ACCEPT_SEED = 128256, 7
+ACCEPT_THRESHOLDS = (0.0, 0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.6931471805599453)
+PAIRINGS = ("T<-Q", "Q<-D")   # (verifier <- proposer): target judging the qualifier's rows, qualifier judging the draft's
+
+
+def _oracle_own_draws(args):
+    """Worker (its own process, CPU only): the oracle's ACCEPT on trials it draws itself from the host generator, every
+    threshold; returns {(pairing, T): accept-length histogram}.  Trials are numbered from 10^6 on, apart from the GPU's."""
+    k, rho, trials = args
+    os.environ["OMP_NUM_THREADS"] = "1"
+    import oracle
+    from paper_2510_12966_amd import synth
+
+    hist = {(pr, T): np.zeros(k + 1, dtype=np.int64) for pr in PAIRINGS for T in ACCEPT_THRESHOLDS}
+    for trial in trials:
+        t, q, d = synth.accept_logits(ACCEPT_SEED, 1_000_000 + trial, k, ACCEPT_V, rho)
+        for pr, (lp, lq) in zip(PAIRINGS, ((t, q[:k]), (q, d[:k]))):
+            x = np.array([oracle.sample_row(lq[i], 1.0, ACCEPT_SEED + trial, 1000 + i)[0] for i in range(k)], dtype=np.int32)
+            for T in ACCEPT_THRESHOLDS:
+                res, _ = oracle.accept(lp, lq, x, T, 1.0, 100 + trial, 50, 2 if pr == "T<-Q" else 1, True)
+                hist[(pr, T)][res.n_accepted] += 1
+    return k, rho, hist
+
+
+def accept_microbench(ks=(4, 8, 16, 32), rhos=(0.5, 0.8, 0.95), trials=10000, B=50, oracle_exact=2, oracle_own=32,
+                      calibrate=False) -> int:
+    """The stand-alone ACCEPT stage on the microbenchmark's inputs: vocabulary 128256, k + 1 rows, correlated synthetic
+    logits generated on the device, `trials` trials per (k, rho, threshold) in launches of B trials, both stage pairings.
+    Reports achieved GB/s (every logit counted once), the accept-length histograms, exact parity with the oracle on
+    copied-back trials and a chi-square comparison with histograms of the oracle's own draws."""
+    import multiprocessing as mp
+
+    import scipy.stats
+
+    # the oracle's own draws run in CPU worker processes, started before this process touches the GPU
+    own = None
+    if oracle_own > 0:
+        pool = mp.get_context("spawn").Pool(min(16, int(os.environ.get("OMP_NUM_THREADS", "8"))))
+        chunks = [list(range(i, min(i + 4, oracle_own))) for i in range(0, oracle_own, 4)]
+        own = pool.map_async(_oracle_own_draws, [(k, rho, c) for k in ks for rho in rhos for c in chunks])
 
     import oracle
+    import paper_2510_12966_amd as psd
+    from paper_2510_12966_amd import synth
 
-    V, seed, B, reps = 128256, 7, 48, 5
-    rows, single = [], {}
+    V, seed = ACCEPT_V, ACCEPT_SEED
     if calibrate:   # a kernel of known traffic, for scaling hardware counters read under rocprofv3 --pmc
         a, b = psd.DeviceBuffer(256 << 20), psd.DeviceBuffer(256 << 20)
         psd.lib().psd_dev_copy(b.data_ptr(), a.data_ptr(), 256 << 20, 2)
         psd.dev_sync()
         a.free(); b.free()
+    rows, exact_checked, exact_ties = [], 0, 0
+    hists = {}
     for k in ks:
-        for rho in ((0.8,) if quick else (0.5, 0.8, 0.95)):
-            P, Q, X = [], [], []
-            for b in range(B):
-                t, q, _ = synth.accept_logits(seed, b, k, V, rho)     # stage "target <- qualifier"
-                x = psd.sample(q[:k], 1.0, seed + b, 1000).astype(np.int32)   # proposals ~ proposer rows, drawn on the device
-                P.append(t); Q.append(q[:k]); X.append(x)
-            dp, dq, dx = (psd.DeviceBuffer.from_numpy(np.stack(a)) for a in (P, Q, X))
-            na, nt, dv = psd.DeviceBuffer(4 * B), psd.DeviceBuffer(4 * B), psd.DeviceBuffer(4 * B * k)
-            wsb = psd.accept_workspace_bytes(B, k, V)
-            ws = psd.DeviceBuffer(wsb)
-            for T in ((0.2,) if quick else (0.0, 0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, math.log(2))):
-                psd.accept_batch(dp, dq, dx, B, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
-                psd.dev_sync()
-                t0 = time.perf_counter()
-                for _ in range(reps):
-                    psd.accept_batch(dp, dq, dx, B, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
-                psd.dev_sync()
-                dt = (time.perf_counter() - t0) / reps
-                gbs = B * (2 * k + 1) * V * 4 / dt / 1e9
-                hist = np.bincount(na.to_numpy(np.int32, B), minlength=k + 1)
-                row = {"k": k, "rho": rho, "T": round(T, 4), "GBps": round(gbs, 1), "us_per_trial": round(dt / B * 1e6, 2),
-                       "hist": hist.tolist()}
-                if T in (0.0, 0.2):   # oracle on every trial of two thresholds per (k, rho)
-                    oh = np.zeros(k + 1, dtype=np.int64)
-                    for b in range(B):
-                        res, _ = oracle.accept(P[b], Q[b], X[b], T, 1.0, 100 + b, 50, 2, True)
-                        oh[res.n_accepted] += 1
-                    row["oracle_hist"] = oh.tolist()
-                    row["hist_equal"] = bool(np.array_equal(oh, hist))
-                rows.append(row)
-                log(f"[accept] k={k:2d} rho={rho:.2f} T={T:.3f}: {gbs:7.1f} GB/s, {dt / B * 1e6:7.2f} us/trial, hist {hist.tolist()}"
-                    + (f" oracle {row['oracle_hist']}" if "oracle_hist" in row else ""))
-            if rho == 0.8:   # latency of one stand-alone stage (one trial per launch sequence), same buffers
-                psd.accept_batch(dp, dq, dx, 1, k, V, 0.2, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
-                psd.dev_sync()
-                t0 = time.perf_counter()
-                for _ in range(20):
-                    psd.accept_batch(dp, dq, dx, 1, k, V, 0.2, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
-                psd.dev_sync()
-                single[k] = round((time.perf_counter() - t0) / 20 * 1e6, 1)
-                log(f"[accept] k={k:2d}: one trial per call {single[k]:.1f} us "
-                    f"({(2 * k + 1) * V * 4 / single[k] / 1e3:.0f} GB/s; launch-latency-bound)")
-            for b_ in (dp, dq, dx, na, nt, dv, ws):
-                b_.free()
+        n_full, n_lead = (k + 1) * V, k * V
+        dT, dQ = psd.DeviceBuffer(4 * B * n_full), psd.DeviceBuffer(4 * B * n_full)
+        dQk, dDk = psd.DeviceBuffer(4 * B * n_lead), psd.DeviceBuffer(4 * B * n_lead)
+        dX = {pr: psd.DeviceBuffer(4 * B * k) for pr in PAIRINGS}
+        nT = len(ACCEPT_THRESHOLDS)
+        na, nt, dv = psd.DeviceBuffer(4 * B * nT), psd.DeviceBuffer(4 * B * nT), psd.DeviceBuffer(4 * B * k * nT)
+        wsb = psd.accept_workspace_bytes(B, k, V)
+        ws = psd.DeviceBuffer(wsb)
+        stage = {"T<-Q": (dT, dQk, 2), "Q<-D": (dQ, dDk, 1)}
+
+        class At:   # a position inside a device buffer
+            def __init__(self, buf, byte_offset):
+                self.p = buf.data_ptr() + byte_offset
+
+            def data_ptr(self):
+                return self.p
+        for rho in rhos:
+            hist = {(pr, T): np.zeros(k + 1, dtype=np.int64) for pr in PAIRINGS for T in ACCEPT_THRESHOLDS}
+            secs = {pr: 0.0 for pr in PAIRINGS}
+            calls = 0
+            for b0 in range(0, trials, B):
+                synth.accept_logits_device(seed, b0, B, k, V, rho, t=dT, q=dQ, qk=dQk, dk=dDk)
+                for pr in PAIRINGS:   # proposals ~ the proposer's own rows, drawn on the device
+                    psd.sample_device(stage[pr][1], B * k, V, 1.0, seed + b0, 1000, dX[pr])
+                keep = None
+                if b0 == 0 and oracle_exact > 0:   # a few trials of the first launch go back to the host for the oracle
+                    n = oracle_exact
+                    keep = {"T": dT.to_numpy(np.float32, (B, k + 1, V))[:n], "Q": dQ.to_numpy(np.float32, (B, k + 1, V))[:n],
+                            "Qk": dQk.to_numpy(np.float32, (B, k, V))[:n], "Dk": dDk.to_numpy(np.float32, (B, k, V))[:n],
+                            "X": {pr: dX[pr].to_numpy(np.int32, (B, k))[:n] for pr in PAIRINGS}}
+                for pr in PAIRINGS:
+                    lp, lq, stg = stage[pr]
+                    psd.dev_sync()
+                    t0 = time.perf_counter()
+                    for i, T in enumerate(ACCEPT_THRESHOLDS):   # the launch sequences of all thresholds go out back to back
+                        psd.accept_batch(lp, lq, dX[pr], B, k, V, T, 1.0, 100 + b0, 50, stg, True, At(na, 4 * B * i), At(nt, 4 * B * i),
+                                         At(dv, 4 * B * k * i), ws, wsb, None)
+                    psd.dev_sync()
+                    if keep is None:   # the first launch of a setting (also the one that is checked) is not timed
+                        secs[pr] += time.perf_counter() - t0
+                        calls += pr == PAIRINGS[0]
+                    h_na, h_nt = na.to_numpy(np.int32, (nT, B)), nt.to_numpy(np.int32, (nT, B))
+                    h_dv = dv.to_numpy(np.float32, (nT, B, k)) if keep is not None else None
+                    for i, T in enumerate(ACCEPT_THRESHOLDS):
+                        hist[(pr, T)] += np.bincount(h_na[i], minlength=k + 1)
+                        if keep is None:
+                            continue
+                        o = (h_na[i], h_nt[i], h_dv[i])
+                        P = keep["T"] if pr == "T<-Q" else keep["Q"]
+                        Qr = keep["Qk"] if pr == "T<-Q" else keep["Dk"]
+                        for b in range(oracle_exact):
+                            res, odiv = oracle.accept(P[b], Qr[b], keep["X"][pr][b], T, 1.0, 100 + b0 + b, 50, stg, True)
+                            exact_checked += 1
+                            assert np.abs(o[2][b] - odiv).max(initial=0.0) <= 1e-5, ("divergence", pr, k, rho, T, b)
+                            if (o[0][b], o[1][b]) != (res.n_accepted, res.next_token):
+                                assert res.margin_div < 1e-6 or res.margin_coin < 1e-6 or res.margin_race < 1e-5, (pr, k, rho, T, b)
+                                exact_ties += 1
+            per_call = {pr: secs[pr] / max(calls, 1) / len(ACCEPT_THRESHOLDS) for pr in PAIRINGS}
+            for pr in PAIRINGS:
+                gbs = B * (2 * k + 1) * V * 4 / per_call[pr] / 1e9 if per_call[pr] > 0 else 0.0
+                for T in ACCEPT_THRESHOLDS:
+                    hists[(pr, k, rho, T)] = hist[(pr, T)]
+                rows.append({"pairing": pr, "k": k, "rho": rho, "GBps": round(gbs, 1), "us_per_trial": round(per_call[pr] / B * 1e6, 2),
+                             "hist": {f"{T:.4f}": hist[(pr, T)].tolist() for T in ACCEPT_THRESHOLDS}})
+                log(f"[accept] {pr} k={k:2d} rho={rho:.2f}: {gbs:7.1f} GB/s over {trials} trials x {len(ACCEPT_THRESHOLDS)} thresholds; "
+                    f"mean accepted length at T=0 / 0.2 / ln2: " + " / ".join(
+                        f"{(hist[(pr, T)] * np.arange(k + 1)).sum() / hist[(pr, T)].sum():.2f}" for T in (0.0, 0.2, ACCEPT_THRESHOLDS[-1])))
+        for b_ in (dT, dQ, dQk, dDk, na, nt, dv, ws, *dX.values()):
+            b_.free()
+    # chi-square of the oracle's own histograms against the GPU's frequencies (cells with an expectation below 5 merged)
+    stat = {"settings": 0, "rejected_at_0.001": 0, "min_p": 1.0}
+    if own is not None:
+        merged = {}
+        for k, rho, h in own.get():
+            for (pr, T), v in h.items():
+                merged[(pr, k, rho, T)] = merged.get((pr, k, rho, T), 0) + v
+        pool.close()
+        for key, oh in merged.items():
+            gh = hists[key].astype(np.float64)
+            exp = gh / gh.sum() * oh.sum()
+            order = np.argsort(-exp)
+            cells_o, cells_e, acc_o, acc_e = [], [], 0.0, 0.0
+            for i in order:
+                acc_o += oh[i]; acc_e += exp[i]
+                if acc_e >= 5:
+                    cells_o.append(acc_o); cells_e.append(acc_e); acc_o = acc_e = 0.0
+            if cells_e and acc_e > 0:
+                cells_o[-1] += acc_o; cells_e[-1] += acc_e
+            p = 1.0
+            if len(cells_e) > 1:
+                chi2 = sum((o - e) ** 2 / e for o, e in zip(cells_o, cells_e))
+                p = float(scipy.stats.chi2.sf(chi2, len(cells_e) - 1))
+            elif acc_e == 0 and not cells_e:
+                p = 1.0
+            stat["settings"] += 1
+            stat["rejected_at_0.001"] += p < 1e-3
+            stat["min_p"] = min(stat["min_p"], p)
+        stat["oracle_trials_per_setting"] = oracle_own
+        log(f"[accept] oracle's own draws ({oracle_own} trials per setting) against the GPU histograms: {stat}")
     best = max(r["GBps"] for r in rows)
     print(json.dumps({"metric": "stand-alone ACCEPT stage, achieved GB/s (logits read once)", "value": best, "unit": "GB/s",
-                      "peak": HBM_PEAK_GBS, "frac": round(best / HBM_PEAK_GBS, 4), "trials_per_launch": B,
-                      "single_trial_call_us": single, "histograms_equal": all(r.get("hist_equal", True) for r in rows), "rows": rows}), flush=True)
+                      "peak": HBM_PEAK_GBS, "frac": round(best / HBM_PEAK_GBS, 4), "trials_per_setting": trials, "trials_per_launch": B,
+                      "single_trial_call_us": accept_single_trial_latency(psd, synth, ks),
+                      "thresholds": list(ACCEPT_THRESHOLDS), "exact_parity": {"stages_checked": exact_checked, "near_ties": exact_ties},
+                      "oracle_own_draws": stat, "rows": rows}), flush=True)
     return 0
+
+
+def accept_single_trial_latency(psd, synth, ks=(4, 8, 16, 32), rho=0.8, T=0.2):
+    """One trial per launch sequence (the in-loop shape): microseconds per call."""
+    V, out = ACCEPT_V, {}
+    for k in ks:
+        t, q, _ = synth.accept_logits(ACCEPT_SEED, 0, k, V, rho)
+        x = psd.sample(q[:k], 1.0, ACCEPT_SEED, 1000).astype(np.int32)
+        dp, dq, dx = psd.DeviceBuffer.from_numpy(t), psd.DeviceBuffer.from_numpy(q[:k]), psd.DeviceBuffer.from_numpy(x)
+        na, nt, dv = psd.DeviceBuffer(4), psd.DeviceBuffer(4), psd.DeviceBuffer(4 * k)
+        wsb = psd.accept_workspace_bytes(1, k, V)
+        ws = psd.DeviceBuffer(wsb)
+        psd.accept_batch(dp, dq, dx, 1, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
+        psd.dev_sync()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            psd.accept_batch(dp, dq, dx, 1, k, V, T, 1.0, 100, 50, 2, True, na, nt, dv, ws, wsb, None)
+        psd.dev_sync()
+        out[k] = round((time.perf_counter() - t0) / 20 * 1e6, 1)
+        for b_ in (dp, dq, dx, na, nt, dv, ws):
+            b_.free()
+    return out
 
 
 def accept_quick(psd, synth, ks=(4, 32), rho=0.8, T=0.2, B=48, reps=5):
@@ -192,7 +310,8 @@ def main() -> int:
                          "correlated synthetic logits) and check accept-length histograms against the oracle")
     ap.add_argument("--accept-k", default="4,8,16,32", help="window lengths of --accept-microbench")
     ap.add_argument("--accept-quick", action="store_true",
-                    help="--accept-microbench on one setting per k (rho 0.8, T 0.2): short enough to run under a profiler")
+                    help="--accept-microbench on rho 0.8 only, 500 trials per setting, no oracle runs: short enough to run under a profiler")
+    ap.add_argument("--accept-trials", type=int, default=10000, help="trials per (pairing, k, rho, threshold) of --accept-microbench")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the timed steps: sweep k1 x k2 x T_q x T_t on the chosen configuration and print a table")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -204,12 +323,15 @@ def main() -> int:
             "(the loop is a dependency chain: it would shard by model placement or tensor-parallel projections)")
         return 2
 
+    if args.accept_microbench:   # starts its CPU workers before anything touches the GPU
+        ks = tuple(int(x) for x in args.accept_k.split(","))
+        if args.accept_quick:
+            return accept_microbench(ks, (0.8,), min(args.accept_trials, 500), 50, 0, 0, args.calibrate_copy)
+        return accept_microbench(ks, trials=args.accept_trials, calibrate=args.calibrate_copy)
+
     import paper_2510_12966_amd as psd
     from paper_2510_12966_amd import synth
 
-    if args.accept_microbench:
-        return accept_microbench(psd, synth, tuple(int(x) for x in args.accept_k.split(",")), args.accept_quick,
-                                 args.calibrate_copy)
     cfg = synth.CONFIGS[args.config]
     n_new = args.n_new or cfg.n_new
     t0 = time.time()

@@ -264,6 +264,11 @@ def accept_batch_noalloc(logits_p, logits_q, tokens, n_trials, k, vocab, T, temp
                                           _ptr(next_token), _ptr(div_out), stream))
 
 
+def sample_device(logits, n_rows, vocab, temperature, seed, position0, tokens_out):
+    """psd_sample on device buffers: logits [n_rows, vocab] floats, tokens_out [n_rows] int32 (objects with data_ptr())."""
+    _check(lib().psd_sample(_ptr(logits), n_rows, vocab, temperature, seed, position0, 1, _ptr(tokens_out)))
+
+
 def philox_block(seed, c0, n, c1, c2, c3):
     """psd_philox_block into host arrays: (raw words [n, 4] uint32, uniforms [n, 4] float32)."""
     out = np.empty((n, 4), dtype=np.uint32)

@@ -9,6 +9,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsd.so")
+SYNTH_DEV_SRC = os.path.join(HERE, "synth", "synth_dev.hip")
+SYNTH_DEV_LIB = os.path.join(HERE, "synth", "libsynth_dev.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -22,16 +24,21 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles every HIP source into libpsd.so; always recompiles."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(os.path.dirname(HERE), "include"), "-o", LIB] + sources()
+def _hipcc(cmd, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
     log = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + log)
     if verbose and log.strip():
         print(log, file=sys.stderr)
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles every HIP source into libpsd.so, and the device-side input generator of the acceptance microbenchmark
+    into synth/libsynth_dev.so; always recompiles."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _hipcc([hipcc] + HIPCC_FLAGS + ["-I", os.path.join(os.path.dirname(HERE), "include"), "-o", LIB] + sources(), verbose)
+    _hipcc([hipcc] + HIPCC_FLAGS + ["-o", SYNTH_DEV_LIB, SYNTH_DEV_SRC], verbose)
     return LIB
 
 

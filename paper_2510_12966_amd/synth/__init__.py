@@ -85,6 +85,31 @@ def correlated(seed: int, stream: int, base: np.ndarray, rho: float, sigma: floa
     return out
 
 
+_DEV_LIB = None
+
+
+def accept_logits_device(seed: int, trial0: int, n_trials: int, k: int, vocab: int, rho: float, t=None, q=None, d=None,
+                         qk=None, dk=None, sigma: float = 3.0):
+    """accept_logits for trials trial0 .. trial0 + n_trials - 1, written on the GPU into device buffers (objects with
+    data_ptr()): t, q, d [n_trials, k + 1, vocab] floats, qk, dk [n_trials, k, vocab] = the first k rows of the qualifier and
+    draft stacks, packed; None skips an output.  Same recipe as accept_logits; only enqueues work on the default
+    stream.  Needs synth/libsynth_dev.so (built by paper_2510_12966_amd.build)."""
+    global _DEV_LIB
+    if _DEV_LIB is None:
+        path = os.path.join(_HERE, "libsynth_dev.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2510_12966_amd.build`")
+        L = ctypes.CDLL(path)
+        L.synth_dev_accept_logits.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        _DEV_LIB = L
+    ptr = lambda b: None if b is None else b.data_ptr()
+    rc = _DEV_LIB.synth_dev_accept_logits(seed, trial0, n_trials, k, vocab, rho, sigma, ptr(t), ptr(q), ptr(d), ptr(qk), ptr(dk), None)
+    if rc != 0:
+        raise RuntimeError(f"synth_dev_accept_logits failed: {rc}")
+
+
 def tokens(seed: int, stream: int, n: int, vocab: int) -> np.ndarray:
     out = np.empty(n, dtype=np.int32)
     _lib().synth_tokens(seed, stream, n, vocab, out.ctypes.data)

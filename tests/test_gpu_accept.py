@@ -321,3 +321,22 @@ def test_accept_batch_workspace_one_byte_short_is_enomem_and_writes_nothing():
     psd.accept_batch(dp, dq, dx, B, k, V, 0.1, 1.0, 1, 0, 1, True, na, nt, dv, ws, wsb, None)   # the exact size is enough
     psd.dev_sync()
     assert (na.to_numpy(np.int32, B) >= 0).all()
+
+
+def test_device_input_generator_follows_the_host_recipe():
+    """The microbenchmark's logits can be manufactured on the GPU (ten thousand trials per setting are terabytes of
+    normals): same counter hash, same Box-Muller transform, so the stacks agree with the host generator's to the last
+    bits of the double-precision library functions."""
+    k, V, B, rho = 3, 1000, 4, 0.8
+    bufs = {n: psd.DeviceBuffer(4 * B * rows * V) for n, rows in (("t", k + 1), ("q", k + 1), ("d", k + 1), ("qk", k), ("dk", k))}
+    synth.accept_logits_device(7, 20, B, k, V, rho, **bufs)
+    psd.dev_sync()
+    got = {n: b.to_numpy(np.float32, (B, (k if n in ("qk", "dk") else k + 1), V)) for n, b in bufs.items()}
+    same = total = 0
+    for b in range(B):
+        t, q, d = synth.accept_logits(7, 20 + b, k, V, rho)
+        for name, want in (("t", t), ("q", q), ("d", d), ("qk", q[:k]), ("dk", d[:k])):
+            assert np.abs(got[name][b] - want).max() <= 2e-6
+            same += int((got[name][b] == want).sum()); total += want.size
+    assert same >= 0.999 * total
+    assert abs(float(got["t"].std()) - 3.0) < 0.1 and abs(float(np.corrcoef(got["t"].ravel(), got["q"].ravel())[0, 1]) - rho) < 0.03
