@@ -225,7 +225,9 @@ int psd_forward(psd_ctx* ctx, int32_t which, const int32_t* tokens, int32_t w, i
  *   take_bonus  when all k are accepted: draw one more token from verifier row k
  * Outputs (same memory space as the inputs): n_accepted (int32), next_token (int32, -1 if none),
  * div_out [k] floats (may be NULL): the divergence of every proposed position.
- * 0 <= k <= PSD_MAX_WIDTH.  Stateless: equal arguments give equal results. */
+ * 0 <= k <= PSD_MAX_WIDTH.  Stateless: equal arguments give equal results.  The call allocates and frees its
+ * device scratch (and, for host pointers, staging buffers) every time and synchronises the device: it is the
+ * convenient form, for tests; time psd_accept_batch or psd_accept_batch_noalloc instead. */
 int psd_accept(const float* logits_p, const float* logits_q, const int32_t* tokens, int32_t k, int32_t vocab,
                float T, float temperature, uint64_t seed, uint32_t position0, uint32_t stage, int32_t take_bonus,
                int32_t where, int32_t* n_accepted, int32_t* next_token, float* div_out);
