@@ -12,7 +12,6 @@ namespace psd {
 constexpr int kPage = 64;        // tokens per KV page
 constexpr int kAttnSplit = 128;  // keys per attention workgroup (two pages); boundaries are absolute positions
 constexpr int kFoldSplits = 12;  // up to this many key ranges the narrow o projection merges the partials itself
-constexpr int kQuadTileSplits = 16;  // beyond this many, one attention workgroup of a narrow pass takes four query tiles
 
 // Context buckets: a pass is launched for the smallest bucket of key ranges that holds every key it can attend to
 // (the host knows an upper bound of the pass's last position), so the attention grid does not grow with max_seq and

@@ -1199,6 +1199,57 @@ __global__ void attn_combine_bf16(const float* part, const PassDesc* desc, void*
     pack_store<true, CT>(xb, H * hd, c, h * hd + i, o[0]);
 }
 
+// The same merge for long contexts (more than eight key ranges): one workgroup per (token, head) brings the partials of
+// all its ranges into LDS with one round of loads (the thread-per-head-dim form above walks them in dependent rounds of
+// sixteen: 9-11 us at 36 ranges), then takes the maximum (exact, so any order), the rescaling factors (one thread per
+// range) and the sums in range order: the arithmetic, hence the bits, of attn_merge.
+// grid (wmax, H), 256 threads, dynamic LDS: nsplit * (hd + 3) floats.
+template <int CT>
+__global__ __launch_bounds__(256) void attn_combine_long(const float* part, const PassDesc* desc, void* xb, int H, int hd, int nsp_cap) {
+    extern __shared__ float cmb[];
+    __shared__ float red[4];
+    const int c = blockIdx.x, h = blockIdx.y;
+    if (c >= desc->w) return;
+    // splits holding keys <= pos0 + c; never more than the launch covers (the LDS area is sized for those)
+    const int nsp = min((desc->pos0 + c + kAttnSplit) / kAttnSplit, nsp_cap);
+    const int row = hd + 2;
+    const size_t stride = (size_t)kCols * H * row;
+    const float* p0 = part + ((size_t)c * H + h) * row;
+    // batches of 24 loads per thread, all of a batch in flight together (one batch covers 47 ranges at head dim 128)
+    constexpr int kBatch = 24;
+    for (int base = 0; base < nsp * row; base += kBatch * 256) {
+        float v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int idx = base + u * 256 + (int)threadIdx.x;
+            const int sp = idx / row, i = idx - sp * row;
+            v[u] = idx < nsp * row ? p0[(size_t)sp * stride + i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int idx = base + u * 256 + (int)threadIdx.x;
+            if (idx < nsp * row) cmb[idx] = v[u];
+        }
+    }
+    __syncthreads();
+    float m = -INFINITY;
+    for (int sp = threadIdx.x; sp < nsp; sp += 256) m = fmaxf(m, cmb[sp * row]);
+    const float M = block_max<4>(m, red);
+    float* fac = cmb + nsp * row;
+    for (int sp = threadIdx.x; sp < nsp; sp += 256) fac[sp] = expf(cmb[sp * row] - M);
+    __syncthreads();
+    if ((int)threadIdx.x < hd) {
+        const int i = threadIdx.x;
+        float Lsum = 0.f, o = 0.f;
+        for (int sp = 0; sp < nsp; ++sp) {
+            const float f = fac[sp];
+            Lsum = fmaf(cmb[sp * row + 1], f, Lsum);
+            o = fmaf(cmb[sp * row + 2 + i], f, o);
+        }
+        pack_store<true, CT>(xb, H * hd, c, h * hd + i, o / Lsum);
+    }
+}
+
 // fp32 weights, row-major [N][K]; X fp32 rows [c][K].  One wave per output row.
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_f32(const float* __restrict__ W, const float* __restrict__ X,
@@ -1653,9 +1704,11 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     L.end();
     // key ranges this launch covers: the bucket of the pass's last position (the caller's bound), never beyond the cache
     const int nsplit = std::min(M.nsplit_max, kCtxBuckets[M.ctx_bucket]);
-    // wide passes, and narrow ones over long contexts: four query tiles share one load of the keys and values (narrow
-    // target pass at 3 K tokens of context 4.28 -> 4.06 ms, at 1 K 3.87 -> 3.92 ms)
-    const int qt_per_wg = (wmax > kMaxW || nsplit > kQuadTileSplits) ? 4 : 1;
+    // prompt-ingestion passes: four query tiles share one load of the keys and values.  Narrow passes take one tile per
+    // workgroup at every context length: since the key and value planes are tiled their loads are cheap enough that more
+    // workgroups beat fewer loads (target pass at 4.6 K tokens of context 4.29 -> 4.27 ms; with the untiled planes it was
+    // the other way round beyond 16 key ranges)
+    const int qt_per_wg = wmax > kMaxW ? 4 : 1;
     const int qt_max = ((wmax * G + 15) / 16 + qt_per_wg - 1) / qt_per_wg;
     // narrow passes of small models: the o projection merges the attention split partials itself (one launch less).
     // Every workgroup of it repeats the merge, so past a dozen key ranges the separate merge kernel is cheaper
@@ -1691,8 +1744,17 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
             L.end();
         } else {
             L.begin("attn_combine", act);
-            if (c128) attn_combine_bf16<kWideCT><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
-            else attn_combine_bf16<2><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
+            // more than eight key ranges: the form that fetches a row's partials in one round (its LDS need grows with the
+            // ranges; the dependent-rounds form takes over where that no longer fits)
+            const size_t cmb_lds = (size_t)nsplit * (hd + 3) * sizeof(float);
+            if (nsplit > 8 && cmb_lds <= 64 * 1024) {
+                if (c128) attn_combine_long<kWideCT><<<dim3(wmax, H), 256, cmb_lds, stream>>>(M.attn_part, M.desc, xb2, H, hd, nsplit);
+                else attn_combine_long<2><<<dim3(wmax, H), 256, cmb_lds, stream>>>(M.attn_part, M.desc, xb2, H, hd, nsplit);
+            } else if (c128) {
+                attn_combine_bf16<kWideCT><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
+            } else {
+                attn_combine_bf16<2><<<dim3(wmax, H), hd, 0, stream>>>(M.attn_part, M.desc, xb2, H, hd);
+            }
             L.end();
             launch_gemm_bf16<EPI_RESID>(L, "gemm_o", a);
         }
