@@ -25,8 +25,10 @@ class TeacherForced:
     for that model).  The sequence is rebuilt from the trace events alone: a sampling event at position P appends its
     token after the first P tokens, a stage event at position P keeps the accepted proposals and the replacement."""
 
-    def __init__(self, models, prompt, tol):
+    def __init__(self, models, prompt, tol, max_rows=None):
         self.models, self.tol = dict(models), tol
+        self.budget = dict(max_rows) if max_rows else {}   # model index -> rows still to be checked (absent: no limit)
+        self.rows_of = {w: 0 for w in self.models}
         self.cur = [int(t) for t in prompt]
         self.cached = {w: [] for w in self.models}
         self.rows = 0
@@ -45,8 +47,11 @@ class TeacherForced:
 
     def check(self, which, pos0, proposals, lp):
         """lp[i] must be the logits of the token at pos0 + i given cur[:pos0] + proposals[:i]."""
-        if which not in self.models:
+        if which not in self.models or self.budget.get(which, 1) <= 0:
             return
+        if which in self.budget:
+            self.budget[which] -= lp.shape[0]
+        self.rows_of[which] += lp.shape[0]
         assert 1 <= pos0 <= len(self.cur), (pos0, len(self.cur))
         tokens = self.cur[:pos0] + [int(t) for t in proposals]
         want = self._rows(which, tokens, lp.shape[0])
@@ -142,7 +147,8 @@ class GreedyReplay:
         assert (n_acc, nxt) == (res.n_accepted, res.next_token), (kind, pos0, n_acc, nxt, res.n_accepted, res.next_token)
 
 
-def forced_for(shapes, blobs, dtype, theta, max_seq, prompt, which=(0, 1, 2)):
-    """TeacherForced over fresh oracle models of the given library model indices."""
+def forced_for(shapes, blobs, dtype, theta, max_seq, prompt, which=(0, 1, 2), max_rows=None):
+    """TeacherForced over fresh oracle models of the given library model indices; max_rows: {model index: rows to check}
+    bounds the oracle's work on large models (the sequence is followed to the end either way)."""
     models = {w: oracle.Model(shapes[w], blobs[w], dtype, theta, max_seq) for w in which}
-    return TeacherForced(models, prompt, LOGIT_TOL[dtype])
+    return TeacherForced(models, prompt, LOGIT_TOL[dtype], max_rows)

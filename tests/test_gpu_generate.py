@@ -198,7 +198,9 @@ def test_create_with_a_pool_too_small_is_enomem(tiny_stack):
 def test_paper_shapes_sampled_parity():
     """Full-size models (1B / 3B / 8B shapes, vocabulary 128256) in the launch configuration bench.py times
     (graph replay): every ACCEPT and every draft sample of a short run is replayed through the oracle on the GPU's
-    own logits, and one teacher-forced pass per model is compared with the oracle's forward.  The 512-token
+    own logits; the logits rows the loop consumed in its first rounds (thresholds at which both stages reject, so the
+    caches have been rolled back) are recomputed by the oracle's forward, teacher-forced on the GPU's own sequence; and
+    one more pass per model is compared with the oracle's forward.  The 512-token
     prompt-ingestion passes, which the oracle cannot follow at this size in reasonable time, are tied to the
     passes it does check: they must leave the same KV cache bit for bit."""
     cfg = synth.CONFIGS["paper"]
@@ -218,6 +220,17 @@ def test_paper_shapes_sampled_parity():
     ctx.set_trace(None)
     print("paper stack, tighter thresholds:", st, "ties", rp.ties, flush=True)
     assert rp.ties <= 1 and 0 < st["fuzzy_q"] < st["proposed_q"] and 0 < st["fuzzy_t"] < st["proposed_t"]
+    # in-loop rows against the oracle's forward: a short prompt and a bounded number of rows per model keep the oracle's
+    # share to a few hundred GFLOP (the 8B-shaped forward costs it 15 GFLOP per token)
+    short = prompt[:6]
+    forced = forced_for((cfg.draft, cfg.qualifier, cfg.target), (d, q, t), cfg.dtype, cfg.rope_theta, 64, short,
+                        max_rows={0: 12, 1: 12, 2: 11})
+    rp = Replay(9, 0.205, 0.266, 1.0, forced)
+    ctx.set_trace(rp)
+    out, st = ctx.generate(short, 14, 9)
+    ctx.set_trace(None)
+    print("paper stack, in-loop rows checked per model:", forced.rows_of, "max |logit err|", forced.max_err, st, flush=True)
+    assert min(forced.rows_of.values()) >= 10 and forced.cur[6:20] == out.tolist()
     toks = prompt[:12]
     shapes, blobs = (cfg.draft, cfg.qualifier, cfg.target), (d, q, t)
     for which in range(3):
