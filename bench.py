@@ -422,16 +422,24 @@ def main() -> int:
                                               "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
                                               "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4)}
         # thresholds inside this synthetic stack's divergence range (paper shapes: stage 1 0.198-0.213, stage 2
-        # 0.256-0.275 at the medians below), so that both stages accept by threshold, by coin, and reject
-        mid = {"paper": (0.205, 0.266), "long": (0.205, 0.266), "small": (0.05, 0.05), "tiny": (0.004, 0.012)}[cfg.name]
-        ctx.set_decoding(mid[0], mid[1], cfg.k1, cfg.k2, cfg.temperature)
-        r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), min(n_new, 256))
+        # 0.256-0.275), so that both stages accept by threshold, by coin, and reject: three points from strict to loose,
+        # each with the closed forms of Section 3.3 evaluated at its own accept rates and per-pass speeds
+        curve = {"paper": ((0.200, 0.260), (0.205, 0.266), (0.210, 0.272)), "long": ((0.200, 0.260), (0.205, 0.266), (0.210, 0.272)),
+                 "small": ((0.03, 0.03), (0.05, 0.05), (0.08, 0.08)), "tiny": ((0.002, 0.006), (0.004, 0.012), (0.008, 0.02))}[cfg.name]
+        points = []
+        for tq, tt in curve:
+            ctx.set_decoding(tq, tt, cfg.k1, cfg.k2, cfg.temperature)
+            r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), min(n_new, 256))
+            bq, bt = s_["accepted_q"] / max(s_["proposed_q"], 1), s_["accepted_t"] / max(s_["proposed_t"], 1)
+            vd, vq, vt = (1e3 * s_[p] / max(s_[m], 1e-9) for p, m in (("passes_d", "ms_d"), ("passes_q", "ms_q"), ("passes_t", "ms_t")))
+            _, v_model, _ = throughput_model(bq, bt, cfg.k1, cfg.k2, vd, vq, vt)
+            points.append({"T_q": tq, "T_t": tt, "tokens_per_s": r, "accept_rate_q": round(bq, 4), "accept_rate_t": round(bt, 4),
+                           "threshold_accepts_q": round(s_["fuzzy_q"] / max(s_["proposed_q"], 1), 4),
+                           "threshold_accepts_t": round(s_["fuzzy_t"] / max(s_["proposed_t"], 1), 4),
+                           "section_3_3_V_PSD": round(v_model, 1)})
         ctx.set_decoding(cfg.T_q, cfg.T_t, cfg.k1, cfg.k2, cfg.temperature)
-        baselines["psd_mid_thresholds"] = {"T_q": mid[0], "T_t": mid[1], "tokens_per_s": r,
-                                           "accept_rate_q": round(s_["accepted_q"] / max(s_["proposed_q"], 1), 4),
-                                           "accept_rate_t": round(s_["accepted_t"] / max(s_["proposed_t"], 1), 4),
-                                           "threshold_accepts_q": round(s_["fuzzy_q"] / max(s_["proposed_q"], 1), 4),
-                                           "threshold_accepts_t": round(s_["fuzzy_t"] / max(s_["proposed_t"], 1), 4)}
+        baselines["psd_mid_thresholds"] = points[1]
+        baselines["psd_threshold_curve"] = points
         ctx.set_greedy(True)      # temperature -> 0 limit: top predictions everywhere, exact token match in both stages
         r, s_ = rate(lambda n: ctx.generate(prompt, n, seed), min(n_new, 64))
         ctx.set_greedy(False)
