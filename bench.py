@@ -276,10 +276,11 @@ def accept_quick(psd, synth, ks=(4, 32), rho=0.8, T=0.2, B=48, reps=5):
 SWEEP_K1, SWEEP_K2 = (3, 5, 8), (6, 10, 16)
 
 
-def sweep(ctx, cfg, prompt, n_new) -> int:
-    """k1 x k2 x T_q x T_t grid (81 points) on one context created with the largest windows of the grid."""
+def sweep(ctx, cfg, prompt, n_new, only_k1=0) -> int:
+    """k1 x k2 x T_q x T_t grid (81 points) on one context created with the largest windows of the grid; only_k1
+    restricts the run to one draft length (27 points)."""
     print("k1 k2 T_q T_t decode_tok_s accept_q accept_t ms_d ms_q ms_t passes_d passes_q passes_t", flush=True)
-    for (k1, k2) in [(a, b) for a in SWEEP_K1 for b in SWEEP_K2]:
+    for (k1, k2) in [(a, b) for a in SWEEP_K1 for b in SWEEP_K2 if only_k1 in (0, a)]:
         for T_q in (0.2, 0.5, 0.8):
             for T_t in (0.0, 0.3, 0.6):
                 ctx.set_decoding(T_q, T_t, k1, k2, cfg.temperature)
@@ -314,6 +315,7 @@ def main() -> int:
     ap.add_argument("--accept-trials", type=int, default=10000, help="trials per (pairing, k, rho, threshold) of --accept-microbench")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the timed steps: sweep k1 x k2 x T_q x T_t on the chosen configuration and print a table")
+    ap.add_argument("--sweep-k1", type=int, default=0, help="--sweep for this draft length only (0: all of 3, 5, 8)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
                          "hardware counters read under rocprofv3 --pmc)")
@@ -354,7 +356,7 @@ def main() -> int:
         psd.dev_sync()
         a.free(); b.free()
     if args.sweep:
-        return sweep(ctx, cfg, prompt, n_new)
+        return sweep(ctx, cfg, prompt, n_new, args.sweep_k1)
     for i in range(args.warmup):
         out, st = ctx.generate(prompt, n_new, cfg.sample_seed)
         log(f"[bench] warmup {i}: decode {st['ms_decode']:.1f} ms, prefill {st['ms_prefill']:.1f} ms")

@@ -70,3 +70,18 @@ def test_throughput_model_of_section_3_3():
     # a faster first stage can only help, and beta = 1, l -> large approaches the proposer's speed
     assert bench.throughput_model(1.0, 1.0, 4, 8, 2000.0, 400.0, 250.0)[1] > v_psd
     assert abs(bench.throughput_model(1.0, 1.0, 10 ** 6, 8, 1000.0, 400.0, 250.0)[0] - 1000.0) < 1.0
+
+
+def test_bench_reads_measured_traffic_from_the_committed_profile():
+    import bench
+    val, src = bench.measured_traffic("paper", "gemm_gate_up draft")
+    assert src == bench.TRAFFIC_PROFILE and os.path.exists(os.path.join(ROOT, src))
+    assert 67.1e6 <= val <= 70e6          # HBM bytes per launch of the dominant kernel: its 67.11 MB of weights plus ~1 %
+    assert bench.measured_traffic("paper", "no such kernel") == (None, None)
+
+
+def test_adaptive_structs_have_the_same_layout_on_both_sides():
+    import oracle
+    from paper_2510_12966_amd import binding as b
+    assert ctypes.sizeof(b.Adapt) == ctypes.sizeof(oracle.Adapt) == 5 * 4 + 4 * 4
+    assert [n for n, _ in b.Adapt._fields_] == [n for n, _ in oracle.Adapt._fields_]
