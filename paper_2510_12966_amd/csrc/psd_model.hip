@@ -1006,10 +1006,12 @@ __global__ __launch_bounds__(64) void embed_pack(const uint16_t* embed, const Pa
 // The four waves' (max, sum, O) are merged through LDS in wave order and written as one partial per split.
 // Memory round trips on the critical path: the pass descriptor and the page-table entry travel together, then the
 // queries (from L2), keys and values go out back to back; the kernel is latency-bound, so that is what counts.
+// Two waves per SIMD are asked for (at head dim 128 the kernel would otherwise take 284 registers and run one workgroup
+// per CU): with dozens of key ranges a launch has several workgroups per CU, and their round trips then overlap.
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 template <int HD>
-__global__ __launch_bounds__(256) void attn_mfma(const float* qkv, const PassDesc* desc, const uint16_t* kv,
+__global__ __launch_bounds__(256, 2) void attn_mfma(const float* qkv, const PassDesc* desc, const uint16_t* kv,
                                                  const int32_t* page_table, int n_pages, float* part, int layer, int L, int H,
                                                  int KV, int nqkv, int qt_per_wg) {
     constexpr int KSQ = HD / 32, JT = HD / 16;
@@ -1706,8 +1708,8 @@ static int forward_bf16(Model& M, int wmax, float* logits, Launch& L) {
     const int nsplit = std::min(M.nsplit_max, kCtxBuckets[M.ctx_bucket]);
     // prompt-ingestion passes: four query tiles share one load of the keys and values.  Narrow passes take one tile per
     // workgroup at every context length: since the key and value planes are tiled their loads are cheap enough that more
-    // workgroups beat fewer loads (target pass at 4.6 K tokens of context 4.29 -> 4.27 ms; with the untiled planes it was
-    // the other way round beyond 16 key ranges)
+    // workgroups beat fewer loads (target pass at 4.6 K tokens of context: 3.99 ms with one tile per workgroup, 4.06 ms with
+    // the pass's three tiles sharing one load; with the untiled planes it was the other way round beyond 16 key ranges)
     const int qt_per_wg = wmax > kMaxW ? 4 : 1;
     const int qt_max = ((wmax * G + 15) / 16 + qt_per_wg - 1) / qt_per_wg;
     // narrow passes of small models: the o projection merges the attention split partials itself (one launch less).
