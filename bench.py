@@ -46,6 +46,35 @@ def throughput_model(beta_qd, beta_tq, l_d, l_q, v_d, v_q, v_t):
     return v_fsd_qd, v_psd, v_sd
 
 
+LAUNCH_FLOOR_US = 4.3      # a dependent kernel launch, begin to begin of useful streaming (rocprofv3 timestamps of near-empty kernels)
+STREAM_GBPS = 6600.0       # what a plain streaming read reaches on this part (non-temporal loads)
+
+
+def cost_model(kernels, passes, measured_ms):
+    """The two-constant model the forward kernels sit on, evaluated on this run's own launch counts and bytes:
+    time of a pass = launches x LAUNCH_FLOOR_US + algorithmic bytes / STREAM_GBPS.  kernels: rows of the per-kernel table
+    (name, launches, bytes_total); passes / measured_ms: per model name.  Ingestion launches (classes wider than 32
+    tokens) are left out; the draft's sampling step counts as two launches per timed unit."""
+    import re
+    out = {"per_launch_us": LAUNCH_FLOOR_US, "stream_GBps": STREAM_GBPS, "pass": {}}
+    for m in ("draft", "qualifier", "target"):
+        rows = []
+        for r in kernels:
+            cls = re.search(r"w<=(\d+)", r["name"])
+            if r["name"].split()[1:2] == [m] and (cls is None or int(cls.group(1)) <= 32):
+                rows.append(r)
+        n = passes.get(m, 0)
+        if not rows or n <= 0:
+            continue
+        launches = sum(r["launches"] * (2 if r["name"].startswith("sample") else 1) for r in rows) / n
+        gb = sum(r["bytes_total"] for r in rows) / n / 1e9
+        pred = launches * LAUNCH_FLOOR_US * 1e-3 + gb * 1e9 / (STREAM_GBPS * 1e6)
+        out["pass"][m] = {"launches": round(launches, 1), "GB": round(gb, 3), "predicted_ms": round(pred, 4),
+                          "measured_ms": round(measured_ms[m], 4), "measured_over_predicted": round(measured_ms[m] / pred, 3),
+                          "floor_share_of_predicted": round(launches * LAUNCH_FLOOR_US * 1e-3 / pred, 3)}
+    return out
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -499,6 +528,10 @@ def main() -> int:
             roofline["attention_GBps"] = round(sum(r["bytes_total"] for r in att) / sum(r["ms_total"] for r in att) / 1e6, 1)
         if g:
             roofline["all_gemm_GBps"] = round(sum(r["bytes_total"] for r in g) / sum(r["ms_total"] for r in g) / 1e6, 1)
+        roofline["cost_model"] = cost_model(
+            kernels, {"draft": pst["passes_d"], "qualifier": pst["passes_q"], "target": pst["passes_t"]},
+            {m: st[k] / max(st[p_], 1) for m, k, p_ in (("draft", "ms_d", "passes_d"), ("qualifier", "ms_q", "passes_q"),
+                                                         ("target", "ms_t", "passes_t"))})
 
     acc_mb = None
     if not args.no_accept:

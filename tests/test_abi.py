@@ -85,3 +85,17 @@ def test_adaptive_structs_have_the_same_layout_on_both_sides():
     from paper_2510_12966_amd import binding as b
     assert ctypes.sizeof(b.Adapt) == ctypes.sizeof(oracle.Adapt) == 5 * 4 + 4 * 4
     assert [n for n, _ in b.Adapt._fields_] == [n for n, _ in oracle.Adapt._fields_]
+
+
+def test_bench_cost_model_arithmetic():
+    import bench
+    rows = [{"name": "gemm_gate_up draft w<=1", "launches": 160, "bytes_total": 160 * 67.1e6},
+            {"name": "gemm_gate_up draft w<=512", "launches": 16, "bytes_total": 16 * 67.1e6},   # ingestion: left out
+            {"name": "sample draft", "launches": 10, "bytes_total": 10 * 513e3},                  # two launches per unit
+            {"name": "attn target w<=12", "launches": 32, "bytes_total": 32 * 1e6}]
+    cm = bench.cost_model(rows, {"draft": 10, "qualifier": 0, "target": 1}, {"draft": 0.3, "qualifier": 0.0, "target": 0.2})
+    d = cm["pass"]["draft"]
+    assert d["launches"] == 18.0 and abs(d["GB"] - 1.074) < 1e-3
+    # 18 launches x 4.3 us + 1.0741 GB at 6.6 TB/s = 0.0774 + 0.1627 ms
+    assert abs(d["predicted_ms"] - (18 * 4.3e-3 + 1.0741e9 / 6.6e9)) < 1e-3 and abs(d["measured_over_predicted"] - 0.3 / 0.2401) < 2e-3
+    assert "qualifier" not in cm["pass"] and cm["pass"]["target"]["launches"] == 32.0
