@@ -523,7 +523,7 @@ __device__ inline void epilogue(const GemmArgs& a, const DescVals& dv, int tile,
 // live blocks (4 columns x 4 k groups x hi, lo) of two K steps per instruction, no registers.  Loads return in order, so
 // the staged blocks are there before the first weight block, and a K step then reads its operand from LDS (~100
 // cycles) instead of L2 (~1400 cycles, of which a wave's two MFMAs per step hide nothing).
-template <int NT, int NW, int RT, int EPI, int CT, bool LB = false>
+template <int NT, int NW, int RT, int EPI, int CT, bool LB = false, bool SK = false>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
     static_assert(!LB || NT == 1, "LDS staging of the operand is for one column tile");
     extern __shared__ u32x4 lb_buf[];
@@ -590,7 +590,40 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
                                                                 __builtin_bit_cast(bf16x8, bl), acc[r][t], 0, 0, 0);
         }
     };
-    if constexpr (NT == 1) {
+    if constexpr (SK) {
+        // Short K ranges (at most D steps per wave: the draft's q/k/v projection, the qualifier's o projection): a wave asks
+        // for its whole range at once, weight blocks from memory and operand blocks from L2 side by side: one round of
+        // loads instead of a weight batch followed by operand groups that each cost an exposed L2 round trip (draft q/k/v
+        // 9.3 -> 8.6 us, qualifier o 9.8 -> 9.2 us between events).  A longer range would be walked D steps at a time; the
+        // host does not pick this variant for one.  A window of D steps refilled step by step was measured for the long
+        // ranges and loses to the batches below (target down 29.4 -> 31.1 us): loads return in order, so a window that
+        // holds operand blocks next to the weight blocks has 7 instead of 16 weight blocks in flight.  Same K order, same bits.
+        static_assert(NT == 1 && RT == 1 && !LB, "the short-range variant is for one tile per wave");
+        constexpr int D = 7;
+        for (int s0 = k0; s0 < k1; s0 += D) {
+            const int n = min(D, k1 - s0);
+            u32x4 wq[D], bq[D][2];
+#pragma unroll
+            for (int u = 0; u < D; ++u)
+                if (u < n) {
+                    wq[u] = __builtin_nontemporal_load(a_ptr + (size_t)u * 64);
+                    bq[u][0] = zero; bq[u][1] = zero;
+                    if (col_live[0]) {
+                        const u32x4* bp = b_ptr + (size_t)u * kBStep;
+                        bq[u][0] = bp[0]; bq[u][1] = bp[64];
+                    }
+                }
+            if (want_pre) prefetch_all();
+#pragma unroll
+            for (int u = 0; u < D; ++u)
+                if (u < n) {
+                    const u32x4 w1[1] = {wq[u]};
+                    mfma_step(w1, 0, bq[u][0], bq[u][1]);
+                }
+            a_ptr += (size_t)D * 64;
+            b_ptr += (size_t)D * kBStep;
+        }
+    } else if constexpr (NT == 1) {
         // Operand blocks come from L2.  BG steps' worth of them is asked for at a time; the first group goes out with the
         // batch's weights and is there long before them, every later group costs one exposed L2 round trip.  The whole
         // batch at once (BG = U) takes up to 64 registers: on in the variants that run at most one workgroup per CU
@@ -1676,9 +1709,16 @@ static void launch_gemm_bf16(Launch& L, const char* family, GemmArgs a) {
     do {                                                                                                           \
         if constexpr (kHasLb) gemm_bf16<1, NW_, RT_, EPI, 2, true><<<tiles / RT_, 64 * NW_, lb_bytes, L.s>>>(a);   \
     } while (0)
+        // one column tile, at most 7 K steps per wave: the variant that asks for a wave's whole range at once
+        const bool short_k = !wide && !lb && (a.KS + 15) / 16 <= 7 && (EPI == EPI_RESID || EPI == EPI_QKV);
         if (done) {
         } else if (tiles <= 256) {
-            if (lb) PSD_GEMM_LB(16, 1); else if (wide) PSD_GEMM(2, 16, 1, 2); else PSD_GEMM(1, 16, 1, 2);
+            if (lb) PSD_GEMM_LB(16, 1);
+            else if (wide) PSD_GEMM(2, 16, 1, 2);
+            else if (short_k) {
+                if constexpr (EPI == EPI_RESID || EPI == EPI_QKV) gemm_bf16<1, 16, 1, EPI, 2, false, true><<<tiles, 64 * 16, 0, L.s>>>(a);
+            }
+            else PSD_GEMM(1, 16, 1, 2);
         } else if (tiles % 2 == 0) {
             if (lb) PSD_GEMM_LB(8, 2); else if (wide) PSD_GEMM(2, 8, 2, 2); else PSD_GEMM(1, 8, 2, 2);
         } else {
