@@ -623,6 +623,48 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16(const GemmArgs a) {
             a_ptr += (size_t)D * 64;
             b_ptr += (size_t)D * kBStep;
         }
+    } else if constexpr (NT == 1 && RT == 4 && !LB) {
+        // Four row tiles per wave (the qualifier's gate/up projection, one workgroup per CU, 12 K steps per wave): a step is
+        // four weight blocks and one pair of operand blocks, and a window of D steps is on the way at all times: a step's
+        // registers are asked for again, D steps ahead, as soon as its MFMAs are issued.  Loads return in the order they
+        // were issued, which is the order the steps are used in.  Same K order, same bits as the batches that drain
+        // (21.5 -> 20.4 us between events).  Measured and not kept: the same window for the seven-tile variant (4 steps are
+        // all its registers hold: target gate/up 42.1 -> 42.6 us) and for the 8-wave q/k/v kernels (8 steps: qualifier 12.8
+        // -> 13.9 us, target 16.3 -> 16.7 us).
+        constexpr int D = 6;
+        const int n = k1 - k0;
+        u32x4 wq[D][RT], bq[D][2];
+        auto fetch = [&](int slot, int st) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) wq[slot][r] = __builtin_nontemporal_load(a_ptr + r * tile_stride + (size_t)st * 64);
+            bq[slot][0] = zero; bq[slot][1] = zero;
+            if (col_live[0]) {
+                const u32x4* bp = b_ptr + (size_t)st * kBStep;
+                bq[slot][0] = bp[0]; bq[slot][1] = bp[64];
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (u < n) fetch(u, u);
+        if (want_pre) prefetch_all();
+        int st = 0;
+        for (; st + 2 * D <= n; st += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                mfma_step(wq[u], 0, bq[u][0], bq[u][1]);
+                fetch(u, st + D + u);
+            }
+        }
+        // fewer than 2 D steps left, the first D of them (or all) on the way
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (st + u < n) {
+                mfma_step(wq[u], 0, bq[u][0], bq[u][1]);
+                if (st + D + u < n) fetch(u, st + D + u);
+            }
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (st + D + u < n) mfma_step(wq[u], 0, bq[u][0], bq[u][1]);
     } else if constexpr (NT == 1) {
         // Operand blocks come from L2.  BG steps' worth of them is asked for at a time; the first group goes out with the
         // batch's weights and is there long before them, every later group costs one exposed L2 round trip.  The whole
