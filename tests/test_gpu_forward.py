@@ -251,6 +251,26 @@ def test_bf16_narrow_passes_with_long_k_ranges_are_bit_exact():
     ctx.close()
 
 
+def test_bf16_full_size_projection_variants_are_bit_exact():
+    # one-layer stacks with the draft's, the qualifier's and the target's projection shapes (small vocabulary): these are the
+    # shapes that select the per-shape GEMM variants (a wave's whole K range in one round of loads for the draft's q/k/v and
+    # the qualifier's o projection, the windowed four-tile gate/up kernel, the seven-tile one): passes of 1, 5 and 11 tokens
+    # take them, 20-token passes take the two-column-tile kernels, and all four give the same bits; the logits match the oracle
+    shapes = (ModelShape(1, 2048, 32, 8, 8192, 512), ModelShape(1, 3072, 24, 8, 8192, 512), ModelShape(1, 4096, 32, 8, 14336, 512))
+    blobs = [synth.target_weights(s, 70 + i, synth.DTYPE_BF16, sigma=0.02) for i, s in enumerate(shapes)]
+    ctx = _ctx(shapes, blobs, synth.DTYPE_BF16, 500000.0, 128)
+    toks = synth.tokens(16, 0, 60, 512)
+    for which in range(3):
+        runs = []
+        for w in (1, 5, 11, 20):
+            runs.append(np.concatenate([ctx.forward(which, toks[p:p + w], p) for p in range(0, 55 if w != 20 else 60, w)])[:55])
+        for r in runs[1:]:
+            assert np.array_equal(runs[0], r), which
+        om = oracle.Model(shapes[which], blobs[which], synth.DTYPE_BF16, 500000.0, 128)
+        assert np.abs(runs[0] - om.forward(toks[:55], 0)).max() <= TOL_BF16
+    ctx.close()
+
+
 def test_small_config_target_logits_sampled():
     """Config "small" shapes (bf16, vocab 32000): one teacher-forced 24-token pass per model against the oracle."""
     cfg = synth.CONFIGS["small"]
